@@ -173,7 +173,7 @@ int orc_block_scatter(const int64_t *scat, int64_t n, int64_t blk, int64_t *out)
     return ORC_OK;
 }
 
-#define MR 8
+#define MR 4
 #define NR 8
 #define KC 1024
 #define NC 64
