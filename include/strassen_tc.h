@@ -1,0 +1,142 @@
+/*
+ * libstrassen_tc -- fp64 tensor contraction  C := alpha * A * B + beta * C  on one AMD MI355X (gfx950),
+ * evaluated classically or through one- or two-level Strassen, with no explicit tensor transposition.
+ *
+ * The operation is the general tensor contraction of the paper (Sec. 2.3 "Tensor Contraction"):
+ * every index label occurs in exactly two of the three tensors; labels shared by A and C form the free
+ * bundle I, labels shared by B and C the free bundle J, labels shared by A and B the contracted bundle P,
+ *
+ *     C[I J] := alpha * sum_P A[I P] * B[P J] + beta * C[I J],
+ *
+ * with the labels of each tensor listed in any order and every dimension carrying its own stride
+ * (Sec. 2.3 "General stride layouts").  The library views the contraction as a matrix product over the
+ * bundles, addressed through scatter vectors and block scatter vectors (Sec. 2.3 "Block Scatter Matrix
+ * View"), splits that matrix view 2x2 (4x4) for Strassen (Sec. 3, eq. (straprim1); the seven products of
+ * Sec. 2.2, eq. (allops)), forms the operand sums while staging tiles into LDS (Sec. 4.1) and adds each
+ * product to several blocks of C from registers (Sec. 4.2).  Variants (Sec. 4.1): ABC keeps no temporary,
+ * AB stores each product M densely and then accumulates it into C, Naive also stores the operand sums.
+ *
+ * Conventions
+ *   - All tensors are fp64.  Lengths and strides are in elements.  Device pointers address the element
+ *     whose multi-index is all zeros.
+ *   - Every function returns TC_OK (0) or a negative tc_status_t; nothing throws or aborts across this
+ *     boundary.  tc_strerror() names a status.
+ *   - Descriptor arrays are read during tc_plan only; the caller may free them afterwards.
+ *   - A plan owns small device-side tables (scatter vectors, block scatter vectors, product schedule) that
+ *     tc_destroy() releases.  A plan is immutable after creation and may be used for any number of
+ *     tc_contract() calls; calls that overlap in time on different streams must not share C or workspace.
+ *   - tc_contract() only enqueues work on the given HIP stream and never synchronises with the host.
+ */
+#ifndef STRASSEN_TC_H
+#define STRASSEN_TC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tc_plan tc_plan_t; /* opaque; created by tc_plan(), released by tc_destroy() */
+
+typedef enum {
+    TC_VARIANT_NAIVE = 0, /* operand sums and product stored in dense temporaries (Sec. 4.1) */
+    TC_VARIANT_AB = 1,    /* operand sums fused into tile staging; product M stored densely, then accumulated into C */
+    TC_VARIANT_ABC = 2    /* fully fused: no temporaries, each product added to up to 2^L blocks of C from registers */
+} tc_variant_t;
+
+typedef enum {
+    TC_OK = 0,
+    TC_ERR_NULL = -1,      /* a required pointer argument is NULL */
+    TC_ERR_NDIM = -2,      /* ndim < 0 or > TC_MAX_NDIM */
+    TC_ERR_LABEL = -3,     /* label repeated inside a tensor, or not in exactly two tensors */
+    TC_ERR_LENGTH = -4,    /* negative length, or one label with two different lengths */
+    TC_ERR_STRIDE = -5,    /* negative stride, zero stride on a dimension longer than 1, or C's elements may overlap */
+    TC_ERR_LEVEL = -6,     /* level not in {0, 1, 2} */
+    TC_ERR_VARIANT = -7,   /* unknown variant */
+    TC_ERR_WORKSPACE = -8, /* workspace is NULL although tc_plan_workspace_bytes() > 0 */
+    TC_ERR_HIP = -9,       /* a HIP runtime call failed (no device, out of memory, launch failure) */
+    TC_ERR_STATE = -10,    /* plan was created host-only and cannot run, or option value out of range */
+    TC_ERR_RANGE = -11     /* output buffer too small / index out of range in an inspection call */
+} tc_status_t;
+
+#define TC_MAX_NDIM 16
+
+/* One tensor of the contraction (Sec. 2.3 "Tensor" and "General stride layouts").
+ * idx holds ndim single-character labels, e.g. "aebf" (not necessarily NUL-terminated). */
+typedef struct {
+    int ndim;
+    const int64_t *len;    /* host array, ndim entries */
+    const int64_t *stride; /* host array, ndim entries, in elements */
+    const char *idx;       /* host array, ndim labels */
+} tc_tensor_desc_t;
+
+/* Optional knobs for tc_plan_ex(); zero-initialise for defaults. */
+typedef struct {
+    int bs_block;   /* entries per block of the block scatter vectors (Sec. 2.3); 0 = default 16 */
+    int host_only;  /* 1: analyse and schedule on the host only (no HIP call); the plan cannot run */
+    int no_merge;   /* 1: one kernel launch per Strassen product even where destinations are disjoint */
+    int reserved[5];
+} tc_options_t;
+
+/* Facts about a plan (tc_plan_info). */
+typedef struct {
+    int64_t m, n, k;      /* bundle lengths N_I, N_J, N_P of the matrix view */
+    int level_requested;
+    int level;            /* level actually executed: lowered while a bundle is shorter than 2^level */
+    int variant;
+    int n_products;       /* 1, 7 or 49 */
+    int n_launches;       /* kernel launches per tc_contract() */
+    int bs_block;
+    int a_mode, b_mode;   /* 0: stride-1 direction of the operand is its free bundle, 1: the contracted bundle */
+    int64_t mb, nb, kb;   /* extents of one Strassen block: ceil(m / 2^level) rounded up to a multiple of 16, etc. */
+    char I[TC_MAX_NDIM + 1], J[TC_MAX_NDIM + 1], P[TC_MAX_NDIM + 1]; /* labels of each bundle, fastest first, NUL-terminated */
+} tc_plan_info_t;
+
+/* One term of a Strassen product as scheduled (tc_plan_schedule): block (row, col) of the 2^L x 2^L grid and its sign. */
+typedef struct {
+    int n_a, n_b, n_c;
+    int a_row[4], a_col[4], a_sign[4];
+    int b_row[4], b_col[4], b_sign[4];
+    int c_row[4], c_col[4], c_sign[4];
+    int c_first[4]; /* 1 where this product is the first to write that block of C (beta is applied there) */
+    int launch;     /* index of the kernel launch that runs this product */
+} tc_product_t;
+
+/* Build a plan: classify labels into bundles (Sec. 2.3), choose the order inside each bundle, compute the
+ * scatter and block scatter vectors on the device (planner kernel, enqueued on `stream`, a hipStream_t or NULL),
+ * and schedule the 1 / 7 / 49 products of level 0 / 1 / 2 (Sec. 2.2 eq. (allops), Sec. 3 eq. (straprim1)).
+ * On failure *plan_out is set to NULL.  Synchronises `stream` before returning. */
+int tc_plan(tc_plan_t **plan_out, const tc_tensor_desc_t *A, const tc_tensor_desc_t *B, const tc_tensor_desc_t *C,
+            int level, int variant, void *stream);
+int tc_plan_ex(tc_plan_t **plan_out, const tc_tensor_desc_t *A, const tc_tensor_desc_t *B, const tc_tensor_desc_t *C,
+               int level, int variant, const tc_options_t *opts, void *stream);
+
+/* Bytes of device workspace tc_contract() needs (0 for level 0 and for the ABC variant). */
+size_t tc_plan_workspace_bytes(const tc_plan_t *plan);
+
+/* C := alpha * A * B + beta * C.  A_dev, B_dev, C_dev, workspace_dev are device pointers owned by the caller;
+ * C must not overlap A, B or the workspace.  With beta == 0, C is written without being read.
+ * A bundle of length zero: empty I or J makes the call a no-op; empty P gives C := beta * C.
+ * Work is enqueued on `stream` in order; the call returns without waiting for it. */
+int tc_contract(const tc_plan_t *plan, double alpha, const double *A_dev, const double *B_dev, double beta,
+                double *C_dev, void *workspace_dev, void *stream);
+
+/* Release the plan and its device tables.  NULL is accepted. */
+int tc_destroy(tc_plan_t *plan);
+
+const char *tc_strerror(int status);
+
+/* Inspection (tests, tools). */
+int tc_plan_info(const tc_plan_t *plan, tc_plan_info_t *out);
+/* Schedule entry `index` (0 <= index < n_products). */
+int tc_plan_schedule(const tc_plan_t *plan, int index, tc_product_t *out);
+/* Copy one planner output to host memory: which = 0..5 scatter vectors rscat_A, cscat_A, rscat_B, cscat_B, rscat_C, cscat_C;
+ * 6..11 the block scatter vectors rbs_A, cbs_A, rbs_B, cbs_B, rbs_C, cbs_C (Sec. 2.3).  Returns the number of entries
+ * (also when host_out is NULL), or a negative status; copies at most `capacity` entries.  Synchronous. */
+int64_t tc_plan_vector(const tc_plan_t *plan, int which, int64_t *host_out, int64_t capacity);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STRASSEN_TC_H */

@@ -1,0 +1,19 @@
+"""Python binding of libstrassen_tc (argument marshalling only; every step of the contraction runs in the
+library's HIP kernels).  The functions mirror the C ABI declared in include/strassen_tc.h."""
+from .binding import (  # noqa: F401
+    TcError,
+    Plan,
+    VARIANTS,
+    build,
+    lib_path,
+    load_library,
+    tc_contract,
+    tc_destroy,
+    tc_plan,
+    tc_plan_info,
+    tc_plan_schedule,
+    tc_plan_vector,
+    tc_plan_workspace_bytes,
+    tc_strerror,
+    contract,
+)

@@ -1,0 +1,240 @@
+"""ctypes binding of libstrassen_tc.so.
+
+Only marshals arguments: tensors are described by (labels, lengths, strides) and passed as device pointers
+(``torch`` tensors on the GPU, or raw integers).  There is no CPU fallback: if the shared library is missing
+or no GPU is present the calls fail with an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_HERE)
+_LIB = os.path.join(_HERE, "libstrassen_tc.so")
+_lib = None
+
+VARIANTS = {"naive": 0, "ab": 1, "abc": 2}
+TC_MAX_NDIM = 16
+
+HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-std=c++17", "-shared",
+               "-fPIC"]
+
+
+def lib_path() -> str:
+    return _LIB
+
+
+def build(verbose: bool = False) -> str:
+    """Compile the HIP library for gfx950 with hipcc (cross-compiles without a GPU)."""
+    src = [os.path.join(_HERE, "csrc", f) for f in ("tc_host.cpp", "tc_device.hip")]
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc] + HIPCC_FLAGS + ["-I" + os.path.join(_ROOT, "include"), "-o", _LIB] + src
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + out)
+    if verbose and out.strip():
+        print(out)
+    global _lib
+    _lib = None
+    return _LIB
+
+
+class tc_tensor_desc_t(ctypes.Structure):
+    _fields_ = [("ndim", ctypes.c_int), ("len", ctypes.POINTER(ctypes.c_int64)), ("stride", ctypes.POINTER(ctypes.c_int64)),
+                ("idx", ctypes.c_char_p)]
+
+
+class tc_options_t(ctypes.Structure):
+    _fields_ = [("bs_block", ctypes.c_int), ("host_only", ctypes.c_int), ("no_merge", ctypes.c_int), ("reserved", ctypes.c_int * 5)]
+
+
+class tc_plan_info_t(ctypes.Structure):
+    _fields_ = [("m", ctypes.c_int64), ("n", ctypes.c_int64), ("k", ctypes.c_int64), ("level_requested", ctypes.c_int),
+                ("level", ctypes.c_int), ("variant", ctypes.c_int), ("n_products", ctypes.c_int), ("n_launches", ctypes.c_int),
+                ("bs_block", ctypes.c_int), ("a_mode", ctypes.c_int), ("b_mode", ctypes.c_int), ("mb", ctypes.c_int64),
+                ("nb", ctypes.c_int64), ("kb", ctypes.c_int64), ("I", ctypes.c_char * (TC_MAX_NDIM + 1)),
+                ("J", ctypes.c_char * (TC_MAX_NDIM + 1)), ("P", ctypes.c_char * (TC_MAX_NDIM + 1))]
+
+
+class tc_product_t(ctypes.Structure):
+    _fields_ = [("n_a", ctypes.c_int), ("n_b", ctypes.c_int), ("n_c", ctypes.c_int)] + \
+               [(f"{o}_{w}", ctypes.c_int * 4) for o in "abc" for w in ("row", "col", "sign")] + \
+               [("c_first", ctypes.c_int * 4), ("launch", ctypes.c_int)]
+
+
+class TcError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: {tc_strerror(status)} ({status})")
+        self.status = status
+
+
+def load_library():
+    """Load libstrassen_tc.so; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            raise RuntimeError(f"{_LIB} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+        lib = ctypes.CDLL(_LIB)
+        vp, ci, dbl = ctypes.c_void_p, ctypes.c_int, ctypes.c_double
+        dp = ctypes.POINTER(tc_tensor_desc_t)
+        lib.tc_plan.restype = ci
+        lib.tc_plan.argtypes = [ctypes.POINTER(vp), dp, dp, dp, ci, ci, vp]
+        lib.tc_plan_ex.restype = ci
+        lib.tc_plan_ex.argtypes = [ctypes.POINTER(vp), dp, dp, dp, ci, ci, ctypes.POINTER(tc_options_t), vp]
+        lib.tc_plan_workspace_bytes.restype = ctypes.c_size_t
+        lib.tc_plan_workspace_bytes.argtypes = [vp]
+        lib.tc_contract.restype = ci
+        lib.tc_contract.argtypes = [vp, dbl, vp, vp, dbl, vp, vp, vp]
+        lib.tc_destroy.restype = ci
+        lib.tc_destroy.argtypes = [vp]
+        lib.tc_strerror.restype = ctypes.c_char_p
+        lib.tc_strerror.argtypes = [ci]
+        lib.tc_plan_info.restype = ci
+        lib.tc_plan_info.argtypes = [vp, ctypes.POINTER(tc_plan_info_t)]
+        lib.tc_plan_schedule.restype = ci
+        lib.tc_plan_schedule.argtypes = [vp, ci, ctypes.POINTER(tc_product_t)]
+        lib.tc_plan_vector.restype = ctypes.c_int64
+        lib.tc_plan_vector.argtypes = [vp, ci, vp, ctypes.c_int64]
+        _lib = lib
+    return _lib
+
+
+def tc_strerror(status: int) -> str:
+    return load_library().tc_strerror(int(status)).decode()
+
+
+def _desc(idx: str, lens: Sequence[int], strides: Sequence[int]):
+    n = len(idx)
+    if len(lens) != n or len(strides) != n:
+        raise ValueError("labels, lengths and strides must have the same number of entries")
+    L = (ctypes.c_int64 * max(n, 1))(*[int(x) for x in lens])
+    S = (ctypes.c_int64 * max(n, 1))(*[int(x) for x in strides])
+    d = tc_tensor_desc_t(n, L, S, idx.encode())
+    d._keep = (L, S)
+    return d
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())  # torch tensor
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None  # torch.cuda.Stream
+
+
+class Plan:
+    """Owner of a tc_plan_t*."""
+
+    def __init__(self, handle: int):
+        self.handle = handle
+
+    def __del__(self):
+        try:
+            tc_destroy(self)
+        except Exception:
+            pass
+
+
+def tc_plan(A, B, C, level: int = 0, variant="abc", stream=None, bs_block: int = 0, host_only: bool = False,
+            no_merge: bool = False) -> Plan:
+    """A, B, C: (labels, lengths, strides) triples or objects with .idx/.lens/.strides."""
+    lib = load_library()
+    ds = []
+    for T in (A, B, C):
+        if hasattr(T, "idx"):
+            ds.append(_desc(T.idx, T.lens, T.strides))
+        else:
+            ds.append(_desc(*T))
+    v = VARIANTS[variant] if isinstance(variant, str) else int(variant)
+    out = ctypes.c_void_p()
+    opts = tc_options_t(int(bs_block), int(bool(host_only)), int(bool(no_merge)))
+    rc = lib.tc_plan_ex(ctypes.byref(out), ctypes.byref(ds[0]), ctypes.byref(ds[1]), ctypes.byref(ds[2]), int(level), v,
+                        ctypes.byref(opts), _stream(stream))
+    if rc != 0:
+        raise TcError(rc, "tc_plan")
+    return Plan(out.value)
+
+
+def tc_plan_workspace_bytes(plan: Plan) -> int:
+    return int(load_library().tc_plan_workspace_bytes(plan.handle))
+
+
+def tc_contract(plan: Plan, alpha: float, A, B, beta: float, C, workspace=None, stream=None) -> None:
+    rc = load_library().tc_contract(plan.handle, float(alpha), _ptr(A), _ptr(B), float(beta), _ptr(C), _ptr(workspace), _stream(stream))
+    if rc != 0:
+        raise TcError(rc, "tc_contract")
+
+
+def tc_destroy(plan: Plan) -> None:
+    if plan.handle:
+        load_library().tc_destroy(plan.handle)
+        plan.handle = None
+
+
+def tc_plan_info(plan: Plan) -> dict:
+    info = tc_plan_info_t()
+    rc = load_library().tc_plan_info(plan.handle, ctypes.byref(info))
+    if rc != 0:
+        raise TcError(rc, "tc_plan_info")
+    d = {k: getattr(info, k) for k, _ in tc_plan_info_t._fields_}
+    for k in "IJP":
+        d[k] = d[k].decode()
+    return d
+
+
+def tc_plan_schedule(plan: Plan) -> list:
+    lib = load_library()
+    n = tc_plan_info(plan)["n_products"]
+    out = []
+    for i in range(n):
+        p = tc_product_t()
+        rc = lib.tc_plan_schedule(plan.handle, i, ctypes.byref(p))
+        if rc != 0:
+            raise TcError(rc, "tc_plan_schedule")
+        e = {"launch": p.launch}
+        for o, cnt in (("a", p.n_a), ("b", p.n_b), ("c", p.n_c)):
+            e[o] = [(getattr(p, f"{o}_row")[t], getattr(p, f"{o}_col")[t], getattr(p, f"{o}_sign")[t]) for t in range(cnt)]
+        e["c_first"] = [p.c_first[t] for t in range(p.n_c)]
+        out.append(e)
+    return out
+
+
+def tc_plan_vector(plan: Plan, which: int):
+    """Planner output `which` (0..5 scatter vectors, 6..11 block scatter vectors) as a numpy int64 array."""
+    import numpy as np
+
+    lib = load_library()
+    n = lib.tc_plan_vector(plan.handle, int(which), None, 0)
+    if n < 0:
+        raise TcError(int(n), "tc_plan_vector")
+    out = np.zeros(max(int(n), 1), dtype=np.int64)
+    rc = lib.tc_plan_vector(plan.handle, int(which), out.ctypes.data, int(n))
+    if rc < 0:
+        raise TcError(int(rc), "tc_plan_vector")
+    return out[:int(n)]
+
+
+def contract(A_desc, B_desc, C_desc, A, B, C, alpha=1.0, beta=1.0, level=0, variant="abc", stream=None):
+    """Convenience: plan, allocate the workspace with torch, contract, destroy.  A, B, C are torch CUDA tensors (flat storage)."""
+    import torch
+
+    plan = tc_plan(A_desc, B_desc, C_desc, level, variant, stream)
+    try:
+        nbytes = tc_plan_workspace_bytes(plan)
+        ws = torch.empty(max(nbytes // 8, 1), dtype=torch.float64, device=C.device) if nbytes else None
+        tc_contract(plan, alpha, A, B, beta, C, ws, stream if stream is not None else torch.cuda.current_stream())
+    finally:
+        tc_destroy(plan)
+    return C

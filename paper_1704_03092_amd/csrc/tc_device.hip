@@ -1,0 +1,503 @@
+// Device side of libstrassen_tc (gfx950 / CDNA4 only).
+//
+//  planner kernels   scatter vectors and block scatter vectors of the matrix view (Sec. 2.3)
+//  fused kernel      the general primitive of Sec. 3, eq. (straprim1), generalised to <= 4 signed blocks per
+//                    operand and <= 4 signed destinations: gather blocks of A and B through the scatter
+//                    vectors, add them in registers, stage the sums in LDS (Sec. 4.1 "packing"), multiply
+//                    tiles on the FP64 matrix cores, add the tile to every destination block of C from
+//                    registers (Sec. 4.2).  Level 0 is the same kernel with one term and one destination.
+//  lincomb kernel    element-wise  dst_d = g_d * (sum_t c_t src_t) + f_d * dst_d  on matrix views; used for
+//                    the dense operand sums of the Naive variant and to accumulate a dense product M into the
+//                    blocks of C (AB and Naive variants), Sec. 4.1.
+//
+// Matrix-core instruction: v_mfma_f64_4x4x4_4b_f64.  One instruction multiplies four independent 4x4x4
+// blocks; measured on MI355X it sustains twice the rate of v_mfma_f64_16x16x4_f64.  Register layout (lane l):
+//   A operand: block (l/4)%4, row l%4, k = l/16        B operand: block (l/4)%4, column l%4, k = l/16
+//   D result : block (l/4)%4, column l%4, row l/16
+// A 16x16 output patch is covered by 4 instructions whose B operand has its four column blocks rotated by
+// s = 0..3 positions: block slot b of instruction s multiplies row block b by column block (b + s) % 4.
+#include <hip/hip_runtime.h>
+
+#include "tc_internal.h"
+
+namespace tc {
+
+namespace {
+
+constexpr int TM = 128;      // tile rows (free bundle I)
+constexpr int TN = 128;      // tile columns (free bundle J)
+constexpr int KT = 16;       // contracted entries per pipeline step
+constexpr int NTHREADS = 256;
+constexpr int GROUP_M = 8;   // tile rows per rasterisation group
+
+// LDS tile layout: element (k, x) of a KT x 128 tile lives at k * PITCH + x.  Matrix-core instruction q of a k-step
+// takes k = 4 * (lane / 16) + q, so one fragment load touches rows k and k + 4 in each half-wave; with PITCH = 132
+// those rows start 16 bank-pairs apart and the load is conflict-free, every fragment address is one per-lane base
+// plus a compile-time offset, and the transposing store (16 lanes with consecutive k) sees 2-way conflicts at worst.
+constexpr int PITCH = 132;
+constexpr int TILE = KT * PITCH;
+
+__device__ __forceinline__ const double* pick_src(int space, const double* user, const double* W, int64_t off) {
+    return (space == 0 ? user : W) + off;
+}
+
+template <int NT>
+struct FusedSmem {
+    double a[2][TILE];
+    double b[2][TILE];
+    int64_t a_rs[NT][TM];      // row scatter of this tile's rows, per term (kSentinel where padded)
+    int64_t b_cs[NT][TN];      // column scatter of this tile's columns, per term
+    int64_t a_cs[2][NT][KT];   // column scatter of the current / next k-step
+    int64_t b_rs[2][NT][KT];
+};
+
+// Issue the loads of 8 elements of one term of the A (or B) tile for one k-step.
+//   MODE 0: lanes run along the 128 free entries (x), each thread covers k = k0 + 2e
+//   MODE 1: lanes run along the 16 contracted entries (k), each thread covers x = x0 + 16e
+// CHECKED: entries of the zero padding (negative offset) read element 0 and are zeroed when the term is consumed.
+template <int MODE, bool CHECKED>
+__device__ __forceinline__ void issue_term(double (&ld)[8], unsigned& padmask, const double* __restrict__ base,
+                                           const int64_t* __restrict__ fixed_tab /* [128] */,
+                                           const int64_t* __restrict__ step_tab /* [KT] */, int tid) {
+    padmask = 0;
+    if (MODE == 0) {
+        const int64_t fx = fixed_tab[tid & 127];
+        const int64_t* st = step_tab + (tid >> 7);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int64_t off = fx + st[2 * e];
+            if (CHECKED) {
+                padmask |= (off < 0 ? 1u : 0u) << e;
+                ld[e] = base[off < 0 ? 0 : off];
+            } else {
+                ld[e] = base[off];
+            }
+        }
+    } else {
+        const int64_t fk = step_tab[tid & 15];
+        const int64_t* ft = fixed_tab + (tid >> 4);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int64_t off = fk + ft[16 * e];
+            if (CHECKED) {
+                padmask |= (off < 0 ? 1u : 0u) << e;
+                ld[e] = base[off < 0 ? 0 : off];
+            } else {
+                ld[e] = base[off];
+            }
+        }
+    }
+}
+
+// v = coef * ld (first term) or v += coef * ld : the operand sum of Sec. 4.1, formed in registers
+template <bool CHECKED>
+__device__ __forceinline__ void consume_term(double (&v)[8], const double (&ld)[8], unsigned padmask, bool first, double coef) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const double x = (CHECKED && ((padmask >> e) & 1u)) ? 0.0 : ld[e];
+        v[e] = first ? coef * x : __builtin_fma(coef, x, v[e]);
+    }
+}
+
+template <int MODE>
+__device__ __forceinline__ void stage_tile(double* __restrict__ tile /* [TILE] */, const double (&v)[8], int tid) {
+    if (MODE == 0) {
+        double* dst = tile + (tid >> 7) * PITCH + (tid & 127);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dst[2 * e * PITCH] = v[e];
+    } else {
+        double* dst = tile + (tid & 15) * PITCH + (tid >> 4);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dst[16 * e] = v[e];
+    }
+}
+
+__device__ __forceinline__ int64_t min64(int64_t a, int64_t b) { return a < b ? a : b; }
+
+template <int AMODE, int BMODE, int NT>
+__global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __restrict__ prods, int first, int tiles_m, int tiles_n,
+                                                            const double* __restrict__ Au, const double* __restrict__ Bu,
+                                                            double* __restrict__ Cu, double* __restrict__ W, double alpha, double beta) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    FusedSmem<NT>& S = *reinterpret_cast<FusedSmem<NT>*>(smem_raw);
+    const int tid = threadIdx.x;
+
+    // ---- which tile: spread consecutive logical ids over one XCD (block b runs on XCD b % 8), then walk
+    //      GROUP_M tile rows at a time so that co-resident workgroups share A and B panels in that XCD's L2 ----
+    const int total = gridDim.x, bid = blockIdx.x;
+    const int q8 = total >> 3, r8 = total & 7, xcd = bid & 7;
+    const int lid = xcd * q8 + (xcd < r8 ? xcd : r8) + (bid >> 3);
+    const int per_prod = tiles_m * tiles_n;
+    const int pidx = lid / per_prod;
+    int rem = lid - pidx * per_prod;
+    const int gsz = GROUP_M * tiles_n;
+    const int grp = rem / gsz;
+    const int gm0 = grp * GROUP_M;
+    const int gh = (tiles_m - gm0) < GROUP_M ? (tiles_m - gm0) : GROUP_M;
+    rem -= grp * gsz;
+    const int tm = gm0 + rem % gh, tn = rem / gh;
+    const Product& P = prods[first + pidx];
+    const int64_t i0 = (int64_t)tm * TM, j0 = (int64_t)tn * TN;
+    const int nA = P.A.nterms, nB = P.B.nterms;
+    const int nk = (int)((P.kb + KT - 1) / KT);
+
+    // ---- tile-fixed scatter tables; how much of the tile and of the k range is free of zero padding ----
+    int64_t klimit = P.kb;       // k entries that are real in every term of both operands
+    bool tile_full = true;       // every row and column of the tile is real in every term
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        if (t < nA) {
+            klimit = min64(klimit, P.A.cs_len - P.A.coff[t]);
+            tile_full = tile_full && (i0 + TM <= min64(P.mb, P.A.rs_len - P.A.roff[t]));
+        }
+        if (t < nB) {
+            klimit = min64(klimit, P.B.rs_len - P.B.roff[t]);
+            tile_full = tile_full && (j0 + TN <= min64(P.nb, P.B.cs_len - P.B.coff[t]));
+        }
+    }
+    const int kfull = tile_full ? (int)(klimit / KT) : 0;  // k-steps [0, kfull) need no checks
+    for (int e = tid; e < NT * TM; e += NTHREADS) {
+        const int t = e / TM, x = e % TM;
+        const int64_t gi = i0 + x;
+        int64_t val = kSentinel;
+        if (t < nA && gi < P.mb && P.A.roff[t] + gi < P.A.rs_len) val = P.A.rs[P.A.roff[t] + gi];
+        S.a_rs[t][x] = val;
+        const int64_t gj = j0 + x;
+        val = kSentinel;
+        if (t < nB && gj < P.nb && P.B.coff[t] + gj < P.B.cs_len) val = P.B.cs[P.B.coff[t] + gj];
+        S.b_cs[t][x] = val;
+    }
+    // Threads 0..16*NT-1 fetch the column scatter entries of A for a k-step (one per term and k), threads
+    // 128..128+16*NT-1 the row scatter entries of B; two k-steps ahead of the tile that uses them.
+    const int64_t* ent_ptr = nullptr;
+    int64_t ent_limit = 0;  // k entries that exist for this thread's term
+    int64_t* ent_dst = nullptr;
+    {
+        const bool isB = tid >= 128;
+        const int q = tid & 127, t = q >> 4, kl = q & 15;
+        if (t < NT) {
+            const Operand& op = isB ? P.B : P.A;
+            ent_dst = isB ? &S.b_rs[0][t][kl] : &S.a_cs[0][t][kl];
+            if (t < op.nterms) {
+                const int64_t off0 = isB ? op.roff[t] : op.coff[t];
+                ent_ptr = (isB ? op.rs : op.cs) + off0 + kl;
+                ent_limit = min64(P.kb, (isB ? op.rs_len : op.cs_len) - off0) - kl;
+            }
+        }
+        if (ent_dst) {
+            ent_dst[0] = (0 < ent_limit) ? ent_ptr[0] : kSentinel;
+            ent_dst[NT * KT] = (KT < ent_limit) ? ent_ptr[KT] : kSentinel;
+        }
+    }
+    __syncthreads();
+
+    const double* Abase = pick_src(P.A.space, Au, W, P.A.base_off);
+    const double* Bbase = pick_src(P.B.space, Bu, W, P.B.base_off);
+
+    double va[8], vb[8], la[8], lb[8];
+    unsigned pa = 0, pb = 0;
+    // ---- prologue: stage k-step 0 ----
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        if (t < nA) {
+            issue_term<AMODE, true>(la, pa, Abase, S.a_rs[t], S.a_cs[0][t], tid);
+            consume_term<true>(va, la, pa, t == 0, P.A.coef[t]);
+        }
+        if (t < nB) {
+            issue_term<BMODE, true>(lb, pb, Bbase, S.b_cs[t], S.b_rs[0][t], tid);
+            consume_term<true>(vb, lb, pb, t == 0, P.B.coef[t]);
+        }
+    }
+    stage_tile<AMODE>(&S.a[0][0], va, tid);
+    stage_tile<BMODE>(&S.b[0][0], vb, tid);
+    __syncthreads();
+
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l16 = lane & 15, lk = lane >> 4;
+    // per-lane fragment bases; everything else in a fragment address is a compile-time offset
+    const double* fa = &S.a[0][0] + 4 * lk * PITCH + wm * 64 + l16;
+    const double* fb[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) fb[s] = &S.b[0][0] + 4 * lk * PITCH + wn * 64 + ((l16 + 4 * s) & 15);
+    double acc[4][4][4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int y = 0; y < 4; ++y)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc[x][y][s] = 0.0;
+
+    for (int step = 0; step < nk; ++step) {
+        const int cur = step & 1, nxt = cur ^ 1;
+        const bool more = step + 1 < nk;
+        const bool fast = step + 1 < kfull;  // the k-step being gathered has no padding anywhere
+        int64_t next_entry = kSentinel;
+        const int64_t k2 = (int64_t)(step + 2) * KT;
+        if (k2 < ent_limit) next_entry = ent_ptr[k2];
+
+        const int toff = cur * TILE;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            // The terms of the next k-step are gathered while the matrix cores work on this one: term t is issued
+            // at quarter t * (4 / NT) and added to the running sum one slot later, when its loads have landed.
+            if (more && kk % (4 / NT) == 0) {
+                const int t = kk / (4 / NT);
+                if (fast) {
+                    if (t > 0) {
+                        if (t - 1 < nA) consume_term<false>(va, la, 0, t == 1, P.A.coef[t - 1]);
+                        if (t - 1 < nB) consume_term<false>(vb, lb, 0, t == 1, P.B.coef[t - 1]);
+                    }
+                    if (t < nA) issue_term<AMODE, false>(la, pa, Abase, S.a_rs[t], S.a_cs[nxt][t], tid);
+                    if (t < nB) issue_term<BMODE, false>(lb, pb, Bbase, S.b_cs[t], S.b_rs[nxt][t], tid);
+                } else {
+                    if (t > 0) {
+                        if (t - 1 < nA) consume_term<true>(va, la, pa, t == 1, P.A.coef[t - 1]);
+                        if (t - 1 < nB) consume_term<true>(vb, lb, pb, t == 1, P.B.coef[t - 1]);
+                    }
+                    if (t < nA) issue_term<AMODE, true>(la, pa, Abase, S.a_rs[t], S.a_cs[nxt][t], tid);
+                    if (t < nB) issue_term<BMODE, true>(lb, pb, Bbase, S.b_cs[t], S.b_rs[nxt][t], tid);
+                }
+            }
+            double af[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) af[x] = fa[toff + kk * PITCH + x * 16];
+#pragma unroll
+            for (int y = 0; y < 4; ++y) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const double bf = fb[s][toff + kk * PITCH + y * 16];
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) acc[x][y][s] = __builtin_amdgcn_mfma_f64_4x4x4f64(af[x], bf, acc[x][y][s], 0, 0, 0);
+                }
+            }
+        }
+        if (more) {
+            if (NT - 1 < nA) consume_term<true>(va, la, pa, NT == 1, P.A.coef[NT - 1]);
+            if (NT - 1 < nB) consume_term<true>(vb, lb, pb, NT == 1, P.B.coef[NT - 1]);
+            stage_tile<AMODE>(&S.a[nxt][0], va, tid);
+            stage_tile<BMODE>(&S.b[nxt][0], vb, tid);
+        }
+        if (ent_dst && step + 2 < nk) ent_dst[cur * NT * KT] = next_entry;
+        __syncthreads();
+    }
+
+    // ---- epilogue: add alpha * tile to every destination block of C (Sec. 4.2) ----
+    // the operand tiles are dead: reuse their LDS for the destinations' scatter tables
+    int64_t(*c_rs)[TM] = reinterpret_cast<int64_t(*)[TM]>(&S.a[0][0]);
+    int64_t(*c_cs)[TN] = reinterpret_cast<int64_t(*)[TN]>(&S.b[0][0]);
+    const int nC = P.C.nterms;
+    for (int e = tid; e < NT * TM; e += NTHREADS) {
+        const int d = e / TM, x = e % TM;
+        const int64_t gi = i0 + x, gj = j0 + x;
+        int64_t val = kSentinel;
+        if (d < nC && gi < P.mb && P.C.roff[d] + gi < P.C.rs_len) val = P.C.rs[P.C.roff[d] + gi];
+        c_rs[d][x] = val;
+        val = kSentinel;
+        if (d < nC && gj < P.nb && P.C.coff[d] + gj < P.C.cs_len) val = P.C.cs[P.C.coff[d] + gj];
+        c_cs[d][x] = val;
+    }
+    __syncthreads();
+    double* Cbase = (P.C.space == 0 ? Cu : W) + P.C.base_off;
+    const int dj = lane & 3, dblk = (lane >> 2) & 3, di = lane >> 4;
+#pragma unroll
+    for (int d = 0; d < NT; ++d) {
+        if (d >= nC) break;
+        const double g = P.C.coef[d];
+        const double f = P.overwrite ? 0.0 : (((P.first_mask >> d) & 1u) ? beta : 1.0);
+        int64_t rsv[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) rsv[x] = c_rs[d][wm * 64 + x * 16 + dblk * 4 + di];
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int64_t csv = c_cs[d][wn * 64 + y * 16 + ((dblk + s) & 3) * 4 + dj];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const int64_t off = rsv[x] + csv;
+                    if (off >= 0) {
+                        const double v = g * (alpha * acc[x][y][s]);
+                        Cbase[off] = (f == 0.0) ? v : __builtin_fma(f, Cbase[off], v);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// element-wise linear combination on matrix views
+// ---------------------------------------------------------------------------------------------------------
+template <bool ROWS_FAST>
+__global__ __launch_bounds__(256) void lincomb_kernel(const Product* __restrict__ prods, int index, const double* __restrict__ srcU,
+                                                      double* __restrict__ Cu, double* __restrict__ W, double beta, int slow_per_block) {
+    const Product& P = prods[index];
+    // a block covers 256 entries of the fast direction and slow_per_block of the slow one
+    const int64_t fast = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t slow0 = (int64_t)blockIdx.y * slow_per_block;
+    const int64_t nfast = ROWS_FAST ? P.mb : P.nb, nslow = ROWS_FAST ? P.nb : P.mb;
+    if (fast >= nfast) return;
+    const double* src = (P.A.space == 0 ? srcU : W) + P.A.base_off;
+    double* dst = (P.C.space == 0 ? Cu : W) + P.C.base_off;
+    const int nS = P.A.nterms, nD = P.C.nterms;
+    int64_t sfix[kMaxTerms], dfix[kMaxTerms];
+#pragma unroll
+    for (int t = 0; t < kMaxTerms; ++t) {
+        sfix[t] = dfix[t] = kSentinel;
+        if (t < nS) {
+            const int64_t g = (ROWS_FAST ? P.A.roff[t] : P.A.coff[t]) + fast;
+            const int64_t len = ROWS_FAST ? P.A.rs_len : P.A.cs_len;
+            if (g < len) sfix[t] = (ROWS_FAST ? P.A.rs : P.A.cs)[g];
+        }
+        if (t < nD) {
+            const int64_t g = (ROWS_FAST ? P.C.roff[t] : P.C.coff[t]) + fast;
+            const int64_t len = ROWS_FAST ? P.C.rs_len : P.C.cs_len;
+            if (g < len) dfix[t] = (ROWS_FAST ? P.C.rs : P.C.cs)[g];
+        }
+    }
+    for (int e = 0; e < slow_per_block; ++e) {
+        const int64_t sl = slow0 + e;
+        if (sl >= nslow) break;
+        double v = 0.0;
+#pragma unroll
+        for (int t = 0; t < kMaxTerms; ++t) {
+            if (t >= nS) break;
+            const int64_t g = (ROWS_FAST ? P.A.coff[t] : P.A.roff[t]) + sl;
+            const int64_t len = ROWS_FAST ? P.A.cs_len : P.A.rs_len;
+            if (g < len && sfix[t] >= 0) v = __builtin_fma(P.A.coef[t], src[sfix[t] + (ROWS_FAST ? P.A.cs : P.A.rs)[g]], v);
+        }
+#pragma unroll
+        for (int d = 0; d < kMaxTerms; ++d) {
+            if (d >= nD) break;
+            const int64_t g = (ROWS_FAST ? P.C.coff[d] : P.C.roff[d]) + sl;
+            const int64_t len = ROWS_FAST ? P.C.cs_len : P.C.rs_len;
+            if (g < len && dfix[d] >= 0) {
+                const int64_t off = dfix[d] + (ROWS_FAST ? P.C.cs : P.C.rs)[g];
+                const double f = P.overwrite ? 0.0 : (((P.first_mask >> d) & 1u) ? beta : 1.0);
+                const double gv = P.C.coef[d] * v;
+                dst[off] = (f == 0.0) ? gv : __builtin_fma(f, dst[off], gv);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// planner kernels (Sec. 2.3, "Block Scatter Matrix View")
+// ---------------------------------------------------------------------------------------------------------
+// scat[i] = sum_d i_d * stride_d   where   i = sum_d i_d * prod_{l<d} len_l   (first index of the bundle fastest)
+__global__ __launch_bounds__(256) void scatter_kernel(const BundleDesc* __restrict__ descs, int64_t* __restrict__ store) {
+    const BundleDesc& b = descs[blockIdx.y];
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < b.total; i += (int64_t)gridDim.x * blockDim.x) {
+        int64_t rest = i, loc = 0;
+        for (int d = 0; d < b.ndim; ++d) {
+            const int64_t len = b.len[d];
+            const int64_t digit = rest % len;
+            rest /= len;
+            loc += digit * b.stride[d];
+        }
+        store[b.out_off + i] = loc;
+    }
+}
+
+// bs[q] = common difference of the entries of block q, 0 if they are not equally spaced; a block holding a
+// single entry is recorded as regular with stride 1.
+__global__ __launch_bounds__(256) void block_scatter_kernel(const BundleDesc* __restrict__ descs, int bs_block, int64_t* __restrict__ store) {
+    const BundleDesc& b = descs[blockIdx.y];
+    const int64_t nblk = (b.total + bs_block - 1) / bs_block;
+    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < nblk; q += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t lo = q * bs_block;
+        const int64_t hi = (lo + bs_block < b.total) ? lo + bs_block : b.total;
+        const int64_t* v = store + b.out_off;
+        int64_t s = (hi - lo >= 2) ? v[lo + 1] - v[lo] : 1;
+        for (int64_t e = lo + 1; e < hi; ++e)
+            if (v[e] - v[e - 1] != s) s = 0;
+        store[b.bs_off + q] = s;
+    }
+}
+
+template <int AMODE, int BMODE, int NT>
+int launch_fused_t(const Product* prods, int first, int count, int tiles_m, int tiles_n, const double* A, const double* B, double* C,
+                   double* W, double alpha, double beta, hipStream_t stream) {
+    static bool configured = false;
+    const size_t smem = sizeof(FusedSmem<NT>);
+    auto kern = fused_kernel<AMODE, BMODE, NT>;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return (int)e;
+        configured = true;
+    }
+    const int64_t blocks = (int64_t)count * tiles_m * tiles_n;
+    if (blocks <= 0 || blocks > 0x7fffffff) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), smem, stream, prods, first, tiles_m, tiles_n, A, B, C, W, alpha, beta);
+    return (int)hipGetLastError();
+}
+
+template <int NT>
+int launch_fused_modes(const FusedConfig& cfg, const Product* prods, int first, int count, int tiles_m, int tiles_n, const double* A,
+                       const double* B, double* C, double* W, double alpha, double beta, hipStream_t stream) {
+    switch (cfg.a_mode * 2 + cfg.b_mode) {
+        case 0: return launch_fused_t<0, 0, NT>(prods, first, count, tiles_m, tiles_n, A, B, C, W, alpha, beta, stream);
+        case 1: return launch_fused_t<0, 1, NT>(prods, first, count, tiles_m, tiles_n, A, B, C, W, alpha, beta, stream);
+        case 2: return launch_fused_t<1, 0, NT>(prods, first, count, tiles_m, tiles_n, A, B, C, W, alpha, beta, stream);
+        default: return launch_fused_t<1, 1, NT>(prods, first, count, tiles_m, tiles_n, A, B, C, W, alpha, beta, stream);
+    }
+}
+
+}  // namespace
+
+int dev_malloc(void** p, size_t bytes) { return (int)hipMalloc(p, bytes); }
+int dev_free(void* p) { return (int)hipFree(p); }
+int dev_upload(void* dst, const void* src, size_t bytes, void* stream) {
+    // the source is pageable host memory owned by the plan: the copy is complete when this returns
+    (void)stream;
+    return (int)hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice);
+}
+int dev_download(void* dst, const void* src, size_t bytes) { return (int)hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost); }
+int dev_stream_sync(void* stream) { return (int)hipStreamSynchronize((hipStream_t)stream); }
+
+int launch_planner(const BundleDesc* descs_dev, int nvec, int64_t max_total, int bs_block, int64_t* store_dev, void* stream) {
+    hipStream_t st = (hipStream_t)stream;
+    int64_t bx = (max_total + 255) / 256;
+    if (bx > 4096) bx = 4096;
+    hipLaunchKernelGGL(scatter_kernel, dim3((unsigned)bx, (unsigned)nvec), dim3(256), 0, st, descs_dev, store_dev);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+    int64_t nblk = (max_total + bs_block - 1) / bs_block;
+    bx = (nblk + 255) / 256;
+    if (bx > 4096) bx = 4096;
+    hipLaunchKernelGGL(block_scatter_kernel, dim3((unsigned)bx, (unsigned)nvec), dim3(256), 0, st, descs_dev, bs_block, store_dev);
+    return (int)hipGetLastError();
+}
+
+int launch_fused(const FusedConfig& cfg, const Product* prods_dev, int first, int count, int64_t mb, int64_t nb, const double* A,
+                 const double* B, double* C, double* W, double alpha, double beta, void* stream) {
+    const int64_t tiles_m = (mb + TM - 1) / TM, tiles_n = (nb + TN - 1) / TN;
+    if (tiles_m <= 0 || tiles_n <= 0 || tiles_m > (1 << 20) || tiles_n > (1 << 20)) return (int)hipErrorInvalidValue;
+    hipStream_t st = (hipStream_t)stream;
+    switch (cfg.max_terms) {
+        case 1: return launch_fused_modes<1>(cfg, prods_dev, first, count, (int)tiles_m, (int)tiles_n, A, B, C, W, alpha, beta, st);
+        case 2: return launch_fused_modes<2>(cfg, prods_dev, first, count, (int)tiles_m, (int)tiles_n, A, B, C, W, alpha, beta, st);
+        case 4: return launch_fused_modes<4>(cfg, prods_dev, first, count, (int)tiles_m, (int)tiles_n, A, B, C, W, alpha, beta, st);
+        default: return (int)hipErrorInvalidValue;
+    }
+}
+
+int launch_lincomb(const Product* prods_dev, int index, int64_t mb, int64_t nb, int lanes_along_rows, const double* A, const double* B,
+                   double* C, double* W, int src_role, double beta, void* stream) {
+    hipStream_t st = (hipStream_t)stream;
+    const double* src = src_role == 0 ? A : B;
+    const int64_t nfast = lanes_along_rows ? mb : nb, nslow = lanes_along_rows ? nb : mb;
+    if (nfast <= 0 || nslow <= 0) return 0;
+    int64_t per = 16;
+    while ((nslow + per - 1) / per > 65535) per *= 2;
+    const int64_t gx = (nfast + 255) / 256, gy = (nslow + per - 1) / per;
+    if (gx > 0x7fffffff || per > (1 << 30)) return (int)hipErrorInvalidValue;
+    if (lanes_along_rows)
+        hipLaunchKernelGGL(lincomb_kernel<true>, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, st, prods_dev, index, src, C, W, beta, (int)per);
+    else
+        hipLaunchKernelGGL(lincomb_kernel<false>, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, st, prods_dev, index, src, C, W, beta, (int)per);
+    return (int)hipGetLastError();
+}
+
+}  // namespace tc

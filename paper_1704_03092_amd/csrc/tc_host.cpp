@@ -1,0 +1,617 @@
+// Host side of libstrassen_tc: argument validation, bundle classification and ordering, Strassen schedule,
+// launch program, and the C ABI declared in include/strassen_tc.h.  All arithmetic on tensor data happens in
+// tc_device.hip; this file only decides what to launch.
+#include "strassen_tc.h"
+#include "tc_internal.h"
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+namespace {
+
+using tc::BundleDesc;
+using tc::Operand;
+using tc::Product;
+
+// The seven products of one-level Strassen (Sec. 2.2, eq. (allops)); quadrants numbered X0 X1 / X2 X3.
+// Row r:  M_r = (sum_q kU[r][q] A_q) (sum_q kV[r][q] B_q);   C_q += kW[r][q] M_r.
+const int kU[7][4] = {{1, 0, 0, 1}, {0, 0, 1, 1}, {1, 0, 0, 0}, {0, 0, 0, 1}, {1, 1, 0, 0}, {-1, 0, 1, 0}, {0, 1, 0, -1}};
+const int kV[7][4] = {{1, 0, 0, 1}, {1, 0, 0, 0}, {0, 1, 0, -1}, {-1, 0, 1, 0}, {0, 0, 0, 1}, {1, 1, 0, 0}, {0, 0, 1, 1}};
+const int kW[7][4] = {{1, 0, 0, 1}, {0, 0, 1, -1}, {0, 1, 0, 1}, {1, 0, 1, 0}, {-1, 1, 0, 0}, {0, 0, 0, 1}, {1, 0, 0, 0}};
+
+struct Dim {
+    char label;
+    int64_t len;
+    int64_t sA, sB, sC;  // stride in each tensor that carries the label (0 where absent)
+};
+
+enum StepKind { STEP_FUSED = 0, STEP_LINCOMB = 1 };
+
+struct Step {
+    StepKind kind;
+    int first, count;     // device products [first, first + count)
+    tc::FusedConfig cfg;  // STEP_FUSED
+    int64_t rows, cols;   // extents
+    int lanes_along_rows; // STEP_LINCOMB
+    int src_role;         // STEP_LINCOMB: which caller tensor a space-0 source refers to (0 = A, 1 = B)
+};
+
+// vector ids inside the plan's store
+enum { V_RSA = 0, V_CSA, V_RSB, V_CSB, V_RSC, V_CSC, V_RSM, V_CSM, V_RSTA, V_CSTA, V_RSTB, V_CSTB, V_COUNT };
+
+int64_t round_up(int64_t x, int64_t q) { return (x + q - 1) / q * q; }
+
+}  // namespace
+
+struct tc_plan {
+    int64_t m = 1, n = 1, k = 1;
+    int level_requested = 0, level = 0, variant = TC_VARIANT_ABC, bs_block = 16;
+    bool host_only = false;
+    int a_mode = 0, b_mode = 0, c_mode = 0;
+    int64_t mb = 0, nb = 0, kb = 0;
+    std::vector<Dim> I, J, P;
+    std::vector<tc_product_t> sched;  // block-level view of the products, for inspection
+    std::vector<Product> prods;       // device descriptors (host copy)
+    std::vector<Step> steps;
+    int n_launches = 0;
+    size_t workspace_bytes = 0;
+    int64_t wsM = 0, wsTA = 0, wsTB = 0;  // offsets (elements) of the temporaries inside the workspace
+    // device
+    std::vector<BundleDesc> bundles;      // V_COUNT entries (temporaries may be unused: total = 0)
+    int64_t store_entries = 0;
+    int64_t* store_dev = nullptr;         // scatter vectors followed by block scatter vectors
+    BundleDesc* bundles_dev = nullptr;
+    Product* prods_dev = nullptr;
+};
+
+namespace {
+
+int check_desc(const tc_tensor_desc_t* T) {
+    if (!T) return TC_ERR_NULL;
+    if (T->ndim < 0 || T->ndim > TC_MAX_NDIM) return TC_ERR_NDIM;
+    if (T->ndim > 0 && (!T->len || !T->stride || !T->idx)) return TC_ERR_NULL;
+    for (int d = 0; d < T->ndim; ++d) {
+        if (T->len[d] < 0) return TC_ERR_LENGTH;
+        if (T->stride[d] < 0) return TC_ERR_STRIDE;
+        if (T->len[d] > 1 && T->stride[d] == 0) return TC_ERR_STRIDE;
+        for (int e = 0; e < d; ++e)
+            if (T->idx[e] == T->idx[d]) return TC_ERR_LABEL;
+    }
+    return TC_OK;
+}
+
+int find(const tc_tensor_desc_t* T, char c) {
+    for (int d = 0; d < T->ndim; ++d)
+        if (T->idx[d] == c) return d;
+    return -1;
+}
+
+// Sufficient condition for the elements of C to be pairwise distinct: sorted by stride, every dimension
+// steps over the whole extent of the ones before it.
+bool distinct_elements(const tc_tensor_desc_t* T) {
+    std::vector<std::pair<int64_t, int64_t>> d;  // (stride, len)
+    for (int i = 0; i < T->ndim; ++i)
+        if (T->len[i] > 1) d.push_back({T->stride[i], T->len[i]});
+    std::sort(d.begin(), d.end());
+    int64_t extent = 1;  // 1 + largest offset so far
+    for (auto& p : d) {
+        if (p.first < extent) return false;
+        extent += (p.second - 1) * p.first;
+    }
+    return true;
+}
+
+int64_t min_stride(const std::vector<Dim>& bundle, int which) {
+    int64_t best = INT64_MAX;
+    for (const Dim& d : bundle) {
+        if (d.len <= 1) continue;
+        int64_t s = which == 0 ? d.sA : which == 1 ? d.sB : d.sC;
+        best = std::min(best, s);
+    }
+    return best;
+}
+
+void order_bundle(std::vector<Dim>& bundle, int which) {
+    std::stable_sort(bundle.begin(), bundle.end(), [which](const Dim& x, const Dim& y) {
+        int64_t sx = which == 0 ? x.sA : which == 1 ? x.sB : x.sC;
+        int64_t sy = which == 0 ? y.sA : which == 1 ? y.sB : y.sC;
+        // dimensions of length 1 carry no information; keep them last
+        bool tx = x.len <= 1, ty = y.len <= 1;
+        if (tx != ty) return ty;
+        return sx < sy;
+    });
+}
+
+BundleDesc make_bundle(const std::vector<Dim>& bundle, int which) {
+    BundleDesc b;
+    std::memset(&b, 0, sizeof b);
+    b.ndim = (int)bundle.size();
+    b.total = 1;
+    for (int d = 0; d < b.ndim; ++d) {
+        b.len[d] = bundle[d].len;
+        b.stride[d] = which == 0 ? bundle[d].sA : which == 1 ? bundle[d].sB : bundle[d].sC;
+        b.total *= bundle[d].len;
+    }
+    return b;
+}
+
+BundleDesc make_dense(int64_t len, int64_t stride) {
+    BundleDesc b;
+    std::memset(&b, 0, sizeof b);
+    b.ndim = 1;
+    b.len[0] = len;
+    b.stride[0] = stride;
+    b.total = len;
+    return b;
+}
+
+void block_tables(int level, std::vector<std::vector<int>>& U, std::vector<std::vector<int>>& V, std::vector<std::vector<int>>& W) {
+    // L-level coefficients as the Kronecker product of the one-level triples, on the 2^L x 2^L block grid.
+    int g = 1 << level, R = 1;
+    for (int l = 0; l < level; ++l) R *= 7;
+    U.assign(R, std::vector<int>(g * g, 0));
+    V = U;
+    W = U;
+    for (int r = 0; r < R; ++r) {
+        int Q = 1;
+        for (int l = 0; l < level; ++l) Q *= 4;
+        for (int q = 0; q < Q; ++q) {
+            int cu = 1, cv = 1, cw = 1, br = 0, bc = 0, rr = r, qq = q;
+            // digit l of r (product at recursion depth) pairs with digit l of q (quadrant at that depth); least
+            // significant digit = innermost level
+            int rd[4], qd[4];
+            for (int l = 0; l < level; ++l) {
+                rd[l] = rr % 7;
+                rr /= 7;
+                qd[l] = qq % 4;
+                qq /= 4;
+            }
+            for (int l = level - 1; l >= 0; --l) {  // outermost first
+                cu *= kU[rd[l]][qd[l]];
+                cv *= kV[rd[l]][qd[l]];
+                cw *= kW[rd[l]][qd[l]];
+                br = 2 * br + (qd[l] >> 1);
+                bc = 2 * bc + (qd[l] & 1);
+            }
+            U[r][br * g + bc] = cu;
+            V[r][br * g + bc] = cv;
+            W[r][br * g + bc] = cw;
+        }
+    }
+}
+
+void set_operand(Operand& op, const int64_t* rs, const int64_t* cs, int64_t rs_len, int64_t cs_len, int space, int64_t base_off) {
+    std::memset(&op, 0, sizeof op);
+    op.rs = rs;
+    op.cs = cs;
+    op.rs_len = rs_len;
+    op.cs_len = cs_len;
+    op.space = space;
+    op.base_off = base_off;
+}
+
+void add_term(Operand& op, int64_t roff, int64_t coff, double coef) {
+    op.roff[op.nterms] = roff;
+    op.coff[op.nterms] = coff;
+    op.coef[op.nterms] = coef;
+    ++op.nterms;
+}
+
+int terms_class(int n) { return n <= 1 ? 1 : n <= 2 ? 2 : 4; }
+
+int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const tc_tensor_desc_t* C, int level, int variant,
+               const tc_options_t* opts, void* stream) {
+    int rc;
+    if ((rc = check_desc(A)) || (rc = check_desc(B)) || (rc = check_desc(C))) return rc;
+    if (level < 0 || level > 2) return TC_ERR_LEVEL;
+    if (variant != TC_VARIANT_NAIVE && variant != TC_VARIANT_AB && variant != TC_VARIANT_ABC) return TC_ERR_VARIANT;
+    p->bs_block = 16;
+    bool no_merge = false;
+    if (opts) {
+        if (opts->bs_block < 0 || opts->bs_block > (1 << 20)) return TC_ERR_STATE;
+        if (opts->bs_block > 0) p->bs_block = opts->bs_block;
+        p->host_only = opts->host_only != 0;
+        no_merge = opts->no_merge != 0;
+    }
+    // ---- bundles (Sec. 2.3): every label in exactly two tensors ----
+    const tc_tensor_desc_t* T[3] = {A, B, C};
+    for (int t = 0; t < 3; ++t) {
+        for (int d = 0; d < T[t]->ndim; ++d) {
+            char c = T[t]->idx[d];
+            int ia = find(A, c), ib = find(B, c), ic = find(C, c);
+            if ((ia >= 0) + (ib >= 0) + (ic >= 0) != 2) return TC_ERR_LABEL;
+            int64_t len = T[t]->len[d];
+            if ((ia >= 0 && A->len[ia] != len) || (ib >= 0 && B->len[ib] != len) || (ic >= 0 && C->len[ic] != len)) return TC_ERR_LENGTH;
+        }
+    }
+    if (!distinct_elements(C)) return TC_ERR_STRIDE;
+    for (int d = 0; d < A->ndim; ++d) {
+        char c = A->idx[d];
+        int ib = find(B, c), ic = find(C, c);
+        Dim dim{c, A->len[d], A->stride[d], ib >= 0 ? B->stride[ib] : 0, ic >= 0 ? C->stride[ic] : 0};
+        (ic >= 0 ? p->I : p->P).push_back(dim);
+    }
+    for (int d = 0; d < B->ndim; ++d) {
+        char c = B->idx[d];
+        int ic = find(C, c);
+        if (ic >= 0) p->J.push_back(Dim{c, B->len[d], 0, B->stride[d], C->stride[ic]});
+    }
+    p->m = p->n = p->k = 1;
+    for (auto& d : p->I) p->m *= d.len;
+    for (auto& d : p->J) p->n *= d.len;
+    for (auto& d : p->P) p->k *= d.len;
+
+    // ---- which way does each operand run contiguously, and the order inside each bundle ----
+    // The order inside a bundle is free as long as both tensors sharing it use the same one (Sec. 2.3); it is
+    // chosen so that the operand whose smallest stride lies in that bundle is read along it.
+    p->a_mode = min_stride(p->P, 0) < min_stride(p->I, 0) ? 1 : 0;
+    p->b_mode = min_stride(p->P, 1) < min_stride(p->J, 1) ? 1 : 0;
+    p->c_mode = min_stride(p->J, 2) < min_stride(p->I, 2) ? 1 : 0;  // 1: C runs contiguously along its columns
+    order_bundle(p->I, p->a_mode == 0 ? 0 : 2);
+    order_bundle(p->J, p->b_mode == 0 ? 1 : 2);
+    order_bundle(p->P, p->a_mode == 1 ? 0 : (p->b_mode == 1 ? 1 : 0));
+
+    // ---- Strassen partition of the matrix view (Sec. 3) ----
+    p->level_requested = level;
+    p->variant = variant;
+    while (level > 0 && std::min(p->m, std::min(p->n, p->k)) < (1 << level)) --level;
+    p->level = level;
+    const int g = 1 << level;
+    // Block extents: the matrix view is cut at multiples of the extent; the last block of each direction may be
+    // short (or empty) and is completed with zeros (Sec. 3, last paragraph: zero padding of the whole bundle).
+    auto extent = [g](int64_t len) { return g == 1 ? len : round_up((len + g - 1) / g, 16); };
+    p->mb = extent(p->m);
+    p->nb = extent(p->n);
+    p->kb = extent(p->k);
+
+    // ---- vectors in the device store ----
+    p->bundles.resize(V_COUNT);
+    p->bundles[V_RSA] = make_bundle(p->I, 0);
+    p->bundles[V_CSA] = make_bundle(p->P, 0);
+    p->bundles[V_RSB] = make_bundle(p->P, 1);
+    p->bundles[V_CSB] = make_bundle(p->J, 1);
+    p->bundles[V_RSC] = make_bundle(p->I, 2);
+    p->bundles[V_CSC] = make_bundle(p->J, 2);
+    const bool empty = p->m == 0 || p->n == 0;
+    const bool use_M = !empty && p->k > 0 && level > 0 && variant != TC_VARIANT_ABC;
+    const bool use_T = use_M && variant == TC_VARIANT_NAIVE;
+    p->bundles[V_RSM] = make_dense(use_M ? p->mb : 0, 1);
+    p->bundles[V_CSM] = make_dense(use_M ? p->nb : 0, p->mb);
+    p->bundles[V_RSTA] = make_dense(use_T ? p->mb : 0, 1);
+    p->bundles[V_CSTA] = make_dense(use_T ? p->kb : 0, p->mb);
+    p->bundles[V_RSTB] = make_dense(use_T ? p->kb : 0, 1);
+    p->bundles[V_CSTB] = make_dense(use_T ? p->nb : 0, p->kb);
+    int64_t off = 0;
+    for (auto& b : p->bundles) {
+        b.out_off = off;
+        off += b.total;
+    }
+    for (auto& b : p->bundles) {
+        b.bs_off = off;
+        off += (b.total + p->bs_block - 1) / p->bs_block;
+    }
+    p->store_entries = off;
+    if (use_M) {
+        int64_t w = 0;
+        p->wsM = w;
+        w += p->mb * p->nb;
+        if (use_T) {
+            p->wsTA = w;
+            w += p->mb * p->kb;
+            p->wsTB = w;
+            w += p->kb * p->nb;
+        }
+        p->workspace_bytes = (size_t)w * sizeof(double);
+    }
+
+    if (!p->host_only) {
+        if (tc::dev_malloc((void**)&p->store_dev, sizeof(int64_t) * (size_t)std::max<int64_t>(p->store_entries, 1))) return TC_ERR_HIP;
+        if (tc::dev_malloc((void**)&p->bundles_dev, sizeof(BundleDesc) * V_COUNT)) return TC_ERR_HIP;
+        if (tc::dev_upload(p->bundles_dev, p->bundles.data(), sizeof(BundleDesc) * V_COUNT, stream)) return TC_ERR_HIP;
+        int64_t max_total = 0;
+        for (auto& b : p->bundles) max_total = std::max(max_total, b.total);
+        if (max_total > 0 && tc::launch_planner(p->bundles_dev, V_COUNT, max_total, p->bs_block, p->store_dev, stream)) return TC_ERR_HIP;
+    }
+    auto vec = [p](int id) -> const int64_t* { return p->store_dev ? p->store_dev + p->bundles[id].out_off : nullptr; };
+
+    // ---- schedule ----
+    if (empty) return TC_OK;  // nothing to do at run time
+    if (p->k == 0) {
+        // C := beta * C : one element-wise pass with no source term
+        Product pr;
+        std::memset(&pr, 0, sizeof pr);
+        set_operand(pr.A, nullptr, nullptr, 0, 0, 0, 0);
+        set_operand(pr.B, nullptr, nullptr, 0, 0, 0, 0);
+        set_operand(pr.C, vec(V_RSC), vec(V_CSC), p->m, p->n, 0, 0);
+        add_term(pr.C, 0, 0, 1.0);
+        pr.mb = p->m;
+        pr.nb = p->n;
+        pr.first_mask = 1;
+        p->prods.push_back(pr);
+        p->steps.push_back(Step{STEP_LINCOMB, 0, 1, {}, p->m, p->n, p->c_mode == 0 ? 1 : 0, 0});
+    } else {
+        std::vector<std::vector<int>> U, V, W;
+        block_tables(level, U, V, W);
+        const int R = (int)U.size();
+        std::vector<char> touched(g * g, 0);
+        struct Pending {
+            Product pr;
+            tc_product_t view;
+        };
+        std::vector<Pending> list;
+        for (int r = 0; r < R; ++r) {
+            Pending e;
+            std::memset(&e.pr, 0, sizeof e.pr);
+            std::memset(&e.view, 0, sizeof e.view);
+            set_operand(e.pr.A, vec(V_RSA), vec(V_CSA), p->m, p->k, 0, 0);
+            set_operand(e.pr.B, vec(V_RSB), vec(V_CSB), p->k, p->n, 0, 0);
+            set_operand(e.pr.C, vec(V_RSC), vec(V_CSC), p->m, p->n, 0, 0);
+            e.pr.mb = p->mb;
+            e.pr.nb = p->nb;
+            e.pr.kb = p->kb;
+            for (int bi = 0; bi < g; ++bi)
+                for (int bk = 0; bk < g; ++bk)
+                    if (U[r][bi * g + bk] && bi * p->mb < p->m && bk * p->kb < p->k) {
+                        add_term(e.pr.A, bi * p->mb, bk * p->kb, U[r][bi * g + bk]);
+                        e.view.a_row[e.view.n_a] = bi, e.view.a_col[e.view.n_a] = bk, e.view.a_sign[e.view.n_a] = U[r][bi * g + bk], ++e.view.n_a;
+                    }
+            for (int bk = 0; bk < g; ++bk)
+                for (int bj = 0; bj < g; ++bj)
+                    if (V[r][bk * g + bj] && bk * p->kb < p->k && bj * p->nb < p->n) {
+                        add_term(e.pr.B, bk * p->kb, bj * p->nb, V[r][bk * g + bj]);
+                        e.view.b_row[e.view.n_b] = bk, e.view.b_col[e.view.n_b] = bj, e.view.b_sign[e.view.n_b] = V[r][bk * g + bj], ++e.view.n_b;
+                    }
+            for (int bi = 0; bi < g; ++bi)
+                for (int bj = 0; bj < g; ++bj)
+                    if (W[r][bi * g + bj] && bi * p->mb < p->m && bj * p->nb < p->n) {
+                        add_term(e.pr.C, bi * p->mb, bj * p->nb, W[r][bi * g + bj]);
+                        e.view.c_row[e.view.n_c] = bi, e.view.c_col[e.view.n_c] = bj, e.view.c_sign[e.view.n_c] = W[r][bi * g + bj], ++e.view.n_c;
+                    }
+            // a product whose operand sum or destination set lies wholly in the zero padding contributes nothing
+            if (e.view.n_a == 0 || e.view.n_b == 0 || e.view.n_c == 0) continue;
+            list.push_back(e);
+        }
+        // Products whose destination sets are disjoint may share one launch (ABC); otherwise one launch each.
+        std::vector<int> phase(list.size(), 0);
+        int nphase = 0;
+        const bool merge = (variant == TC_VARIANT_ABC || level == 0) && !no_merge;
+        {
+            std::vector<std::vector<char>> used;  // per phase: blocks written, and operand class
+            std::vector<int> pclass;
+            for (size_t e = 0; e < list.size(); ++e) {
+                const tc_product_t& v = list[e].view;
+                int cls = terms_class(std::max(v.n_a, std::max(v.n_b, v.n_c)));
+                int chosen = -1;
+                if (merge) {
+                    for (int ph = 0; ph < nphase && chosen < 0; ++ph) {
+                        bool ok = pclass[ph] == cls;
+                        for (int d = 0; d < v.n_c && ok; ++d) ok = !used[ph][v.c_row[d] * g + v.c_col[d]];
+                        if (ok) chosen = ph;
+                    }
+                }
+                if (chosen < 0) {
+                    chosen = nphase++;
+                    used.push_back(std::vector<char>(g * g, 0));
+                    pclass.push_back(cls);
+                }
+                for (int d = 0; d < v.n_c; ++d) used[chosen][v.c_row[d] * g + v.c_col[d]] = 1;
+                phase[e] = chosen;
+            }
+        }
+        // emit in phase order; the first product (in that order) to write a block of C applies beta to it
+        const bool fusedC = (variant == TC_VARIANT_ABC || level == 0);
+        const tc::FusedConfig user_cfg_base{p->a_mode, p->b_mode, 1};
+        for (int ph = 0; ph < nphase; ++ph) {
+            int first_dev = (int)p->prods.size(), count = 0, cls = 1;
+            for (size_t e = 0; e < list.size(); ++e) {
+                if (phase[e] != ph) continue;
+                Pending& q = list[e];
+                uint32_t first_mask = 0;
+                for (int d = 0; d < q.view.n_c; ++d) {
+                    char& t = touched[q.view.c_row[d] * g + q.view.c_col[d]];
+                    if (!t) first_mask |= 1u << d, q.view.c_first[d] = 1;
+                    t = 1;
+                }
+                q.view.launch = (int)p->steps.size();
+                cls = std::max(cls, terms_class(std::max(q.view.n_a, std::max(q.view.n_b, q.view.n_c))));
+                if (fusedC) {
+                    q.pr.first_mask = first_mask;
+                    p->prods.push_back(q.pr);
+                    ++count;
+                } else {
+                    // temporaries: dense, column-major, one block extent each
+                    Product acc;  // M -> destinations of C
+                    std::memset(&acc, 0, sizeof acc);
+                    set_operand(acc.A, vec(V_RSM), vec(V_CSM), p->mb, p->nb, 1, p->wsM);
+                    add_term(acc.A, 0, 0, 1.0);
+                    acc.C = q.pr.C;
+                    acc.mb = p->mb;
+                    acc.nb = p->nb;
+                    acc.first_mask = first_mask;
+                    Product mul = q.pr;  // (sum A)(sum B) -> M
+                    set_operand(mul.C, vec(V_RSM), vec(V_CSM), p->mb, p->nb, 1, p->wsM);
+                    add_term(mul.C, 0, 0, 1.0);
+                    mul.first_mask = 1;
+                    mul.overwrite = 1;
+                    tc::FusedConfig cfg = user_cfg_base;
+                    if (variant == TC_VARIANT_NAIVE) {
+                        Product sa, sb;  // operand sums -> TA, TB
+                        std::memset(&sa, 0, sizeof sa);
+                        std::memset(&sb, 0, sizeof sb);
+                        sa.A = q.pr.A;
+                        set_operand(sa.C, vec(V_RSTA), vec(V_CSTA), p->mb, p->kb, 1, p->wsTA);
+                        add_term(sa.C, 0, 0, 1.0);
+                        sa.mb = p->mb, sa.nb = p->kb, sa.first_mask = 1, sa.overwrite = 1;
+                        sb.A = q.pr.B;
+                        set_operand(sb.C, vec(V_RSTB), vec(V_CSTB), p->kb, p->nb, 1, p->wsTB);
+                        add_term(sb.C, 0, 0, 1.0);
+                        sb.mb = p->kb, sb.nb = p->nb, sb.first_mask = 1, sb.overwrite = 1;
+                        int i0 = (int)p->prods.size();
+                        p->prods.push_back(sa);
+                        p->prods.push_back(sb);
+                        p->steps.push_back(Step{STEP_LINCOMB, i0, 1, {}, p->mb, p->kb, p->a_mode == 0 ? 1 : 0, 0});
+                        p->steps.push_back(Step{STEP_LINCOMB, i0 + 1, 1, {}, p->kb, p->nb, p->b_mode == 1 ? 1 : 0, 1});
+                        set_operand(mul.A, vec(V_RSTA), vec(V_CSTA), p->mb, p->kb, 1, p->wsTA);
+                        add_term(mul.A, 0, 0, 1.0);
+                        set_operand(mul.B, vec(V_RSTB), vec(V_CSTB), p->kb, p->nb, 1, p->wsTB);
+                        add_term(mul.B, 0, 0, 1.0);
+                        cfg = tc::FusedConfig{0, 1, 1};
+                    } else {
+                        cfg.max_terms = terms_class(std::max(q.view.n_a, q.view.n_b));
+                    }
+                    int i1 = (int)p->prods.size();
+                    p->prods.push_back(mul);
+                    p->prods.push_back(acc);
+                    q.view.launch = (int)p->steps.size();
+                    p->steps.push_back(Step{STEP_FUSED, i1, 1, cfg, p->mb, p->nb, 0, 0});
+                    p->steps.push_back(Step{STEP_LINCOMB, i1 + 1, 1, {}, p->mb, p->nb, p->c_mode == 0 ? 1 : 0, 0});
+                }
+                p->sched.push_back(q.view);
+            }
+            if (fusedC && count > 0) {
+                tc::FusedConfig cfg = user_cfg_base;
+                cfg.max_terms = cls;
+                p->steps.push_back(Step{STEP_FUSED, first_dev, count, cfg, p->mb, p->nb, 0, 0});
+            }
+        }
+    }
+    p->n_launches = (int)p->steps.size();
+    if (!p->host_only && !p->prods.empty()) {
+        if (tc::dev_malloc((void**)&p->prods_dev, sizeof(Product) * p->prods.size())) return TC_ERR_HIP;
+        if (tc::dev_upload(p->prods_dev, p->prods.data(), sizeof(Product) * p->prods.size(), stream)) return TC_ERR_HIP;
+    }
+    if (!p->host_only && tc::dev_stream_sync(stream)) return TC_ERR_HIP;
+    return TC_OK;
+}
+
+void release(tc_plan_t* p) {
+    if (!p) return;
+    if (p->store_dev) tc::dev_free(p->store_dev);
+    if (p->bundles_dev) tc::dev_free(p->bundles_dev);
+    if (p->prods_dev) tc::dev_free(p->prods_dev);
+    delete p;
+}
+
+void copy_labels(char* out, const std::vector<Dim>& b) {
+    size_t i = 0;
+    for (; i < b.size() && i < TC_MAX_NDIM; ++i) out[i] = b[i].label;
+    out[i] = 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tc_plan_ex(tc_plan_t** plan_out, const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const tc_tensor_desc_t* C, int level,
+               int variant, const tc_options_t* opts, void* stream) {
+    if (!plan_out) return TC_ERR_NULL;
+    *plan_out = nullptr;
+    tc_plan_t* p = nullptr;
+    try {
+        p = new tc_plan_t();
+        int rc = build_plan(p, A, B, C, level, variant, opts, stream);
+        if (rc != TC_OK) {
+            release(p);
+            return rc;
+        }
+    } catch (...) {
+        release(p);
+        return TC_ERR_HIP;
+    }
+    *plan_out = p;
+    return TC_OK;
+}
+
+int tc_plan(tc_plan_t** plan_out, const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const tc_tensor_desc_t* C, int level,
+            int variant, void* stream) {
+    return tc_plan_ex(plan_out, A, B, C, level, variant, nullptr, stream);
+}
+
+size_t tc_plan_workspace_bytes(const tc_plan_t* plan) { return plan ? plan->workspace_bytes : 0; }
+
+int tc_contract(const tc_plan_t* plan, double alpha, const double* A_dev, const double* B_dev, double beta, double* C_dev,
+                void* workspace_dev, void* stream) {
+    if (!plan) return TC_ERR_NULL;
+    if (plan->host_only) return TC_ERR_STATE;
+    if (plan->steps.empty()) return TC_OK;  // an empty free bundle: nothing to write
+    if (!C_dev) return TC_ERR_NULL;
+    if (plan->k > 0 && (!A_dev || !B_dev)) return TC_ERR_NULL;
+    if (plan->workspace_bytes > 0 && !workspace_dev) return TC_ERR_WORKSPACE;
+    double* W = (double*)workspace_dev;
+    for (const Step& s : plan->steps) {
+        int err;
+        if (s.kind == STEP_FUSED)
+            err = tc::launch_fused(s.cfg, plan->prods_dev, s.first, s.count, s.rows, s.cols, A_dev, B_dev, C_dev, W, alpha, beta, stream);
+        else
+            err = tc::launch_lincomb(plan->prods_dev, s.first, s.rows, s.cols, s.lanes_along_rows, A_dev, B_dev, C_dev, W, s.src_role, beta,
+                                     stream);
+        if (err) return TC_ERR_HIP;
+    }
+    return TC_OK;
+}
+
+int tc_destroy(tc_plan_t* plan) {
+    release(plan);
+    return TC_OK;
+}
+
+const char* tc_strerror(int status) {
+    switch (status) {
+        case TC_OK: return "success";
+        case TC_ERR_NULL: return "required pointer argument is NULL";
+        case TC_ERR_NDIM: return "tensor dimensionality out of range";
+        case TC_ERR_LABEL: return "index label repeated in a tensor or not present in exactly two tensors";
+        case TC_ERR_LENGTH: return "negative length or one label with two lengths";
+        case TC_ERR_STRIDE: return "negative or zero stride, or elements of C may overlap";
+        case TC_ERR_LEVEL: return "Strassen level must be 0, 1 or 2";
+        case TC_ERR_VARIANT: return "unknown variant";
+        case TC_ERR_WORKSPACE: return "workspace required but NULL";
+        case TC_ERR_HIP: return "HIP runtime call failed";
+        case TC_ERR_STATE: return "plan cannot run (host-only) or option out of range";
+        case TC_ERR_RANGE: return "index or capacity out of range";
+        default: return "unknown status";
+    }
+}
+
+int tc_plan_info(const tc_plan_t* plan, tc_plan_info_t* out) {
+    if (!plan || !out) return TC_ERR_NULL;
+    std::memset(out, 0, sizeof *out);
+    out->m = plan->m, out->n = plan->n, out->k = plan->k;
+    out->level_requested = plan->level_requested;
+    out->level = plan->level;
+    out->variant = plan->variant;
+    out->n_products = (int)plan->sched.size();
+    out->n_launches = plan->n_launches;
+    out->bs_block = plan->bs_block;
+    out->a_mode = plan->a_mode, out->b_mode = plan->b_mode;
+    out->mb = plan->mb, out->nb = plan->nb, out->kb = plan->kb;
+    copy_labels(out->I, plan->I);
+    copy_labels(out->J, plan->J);
+    copy_labels(out->P, plan->P);
+    return TC_OK;
+}
+
+int tc_plan_schedule(const tc_plan_t* plan, int index, tc_product_t* out) {
+    if (!plan || !out) return TC_ERR_NULL;
+    if (index < 0 || index >= (int)plan->sched.size()) return TC_ERR_RANGE;
+    *out = plan->sched[index];
+    return TC_OK;
+}
+
+int64_t tc_plan_vector(const tc_plan_t* plan, int which, int64_t* host_out, int64_t capacity) {
+    if (!plan) return TC_ERR_NULL;
+    if (which < 0 || which >= 12) return TC_ERR_RANGE;
+    const BundleDesc& b = plan->bundles[which % 6];
+    int64_t count = which < 6 ? b.total : (b.total + plan->bs_block - 1) / plan->bs_block;
+    if (!host_out) return count;
+    if (plan->host_only || !plan->store_dev) return TC_ERR_STATE;
+    int64_t ncopy = std::min(count, capacity);
+    if (ncopy > 0 && tc::dev_download(host_out, plan->store_dev + (which < 6 ? b.out_off : b.bs_off), sizeof(int64_t) * (size_t)ncopy))
+        return TC_ERR_HIP;
+    return count;
+}
+
+}  // extern "C"

@@ -1,0 +1,151 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, rejects malformed problems,
+and its host-side schedule (inspected through host-only plans) satisfies Brent's equations."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1704_03092_amd as tc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    if not os.path.exists(tc.lib_path()):
+        tc.build()
+    tc.load_library()
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "strassen_tc.h")).read()
+    names = set(re.findall(r"\b(tc_[a-z_]+)\s*\(", hdr))
+    assert {"tc_plan", "tc_contract", "tc_destroy", "tc_plan_workspace_bytes", "tc_strerror"} <= names
+    lib = ctypes.CDLL(tc.lib_path())
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def _plan(A, B, C, level=0, variant="abc", **kw):
+    return tc.tc_plan(A, B, C, level, variant, host_only=True, **kw)
+
+
+def test_error_paths():
+    ok = (("ik", (4, 5), (1, 4)), ("kj", (5, 6), (1, 5)), ("ij", (4, 6), (1, 4)))
+    tc.tc_destroy(_plan(*ok))
+    cases = [
+        ((("ik", (4, 5), (1, 4)), ("kj", (5, 6), (1, 5)), ("ijk", (4, 6, 5), (1, 4, 24))), -3),  # k in all three
+        ((("ii", (4, 4), (1, 4)), ("ij", (4, 6), (1, 4)), ("j", (6,), (1,))), -3),  # repeated label
+        ((("ik", (4, 5), (1, 4)), ("kj", (5, 6), (1, 5)), ("il", (4, 6), (1, 4))), -3),  # j, l in one tensor only
+        ((("ik", (4, 5), (1, 4)), ("kj", (7, 6), (1, 7)), ("ij", (4, 6), (1, 4))), -4),  # k has two lengths
+        ((("ik", (4, -5), (1, 4)), ("kj", (-5, 6), (1, 5)), ("ij", (4, 6), (1, 4))), -4),  # negative length
+        ((("ik", (4, 5), (1, -4)), ("kj", (5, 6), (1, 5)), ("ij", (4, 6), (1, 4))), -5),  # negative stride
+        ((("ik", (4, 5), (0, 4)), ("kj", (5, 6), (1, 5)), ("ij", (4, 6), (1, 4))), -5),  # zero stride, len > 1
+        ((("ik", (4, 5), (1, 4)), ("kj", (5, 6), (1, 5)), ("ij", (4, 6), (1, 3))), -5),  # C overlaps itself
+    ]
+    for (A, B, C), status in cases:
+        with pytest.raises(tc.TcError) as e:
+            _plan(A, B, C)
+        assert e.value.status == status, (A, B, C)
+    with pytest.raises(tc.TcError) as e:
+        _plan(*ok, level=3)
+    assert e.value.status == -6
+    with pytest.raises(tc.TcError) as e:
+        _plan(*ok, variant=7)
+    assert e.value.status == -7
+    many = "abcdefghijklmnopq"  # 17 labels > TC_MAX_NDIM
+    with pytest.raises(tc.TcError) as e:
+        _plan((many, (1,) * 17, (1,) * 17), ("", (), ()), (many, (1,) * 17, (1,) * 17))
+    assert e.value.status == -2
+    # a host-only plan cannot run
+    p = _plan(*ok)
+    with pytest.raises(tc.TcError) as e:
+        tc.tc_contract(p, 1.0, 8, 8, 1.0, 8)
+    assert e.value.status == -10
+    assert "host-only" in tc.tc_strerror(-10)
+
+
+def test_plan_info_bundles_and_modes():
+    # the paper's example contraction C_abc += A_dca * B_db, generalized column-major
+    L = dict(a=4, b=8, c=2, d=8)
+    cm = lambda idx: (idx, tuple(L[x] for x in idx), tuple(int(np.prod([L[y] for y in idx[:i]])) for i in range(len(idx))))
+    p = _plan(cm("dca"), cm("db"), cm("abc"), bs_block=4)
+    info = tc.tc_plan_info(p)
+    assert (info["m"], info["n"], info["k"]) == (8, 8, 8)
+    assert sorted(info["I"]) == ["a", "c"] and info["J"] == "b" and info["P"] == "d"
+    assert info["bs_block"] == 4 and info["n_products"] == 1 and info["level"] == 0
+    assert info["a_mode"] == 1 and info["b_mode"] == 1  # d is the stride-1 index of both A and B
+    # level is lowered while a bundle is shorter than 2^level
+    p2 = _plan(("ik", (1, 64), (1, 1)), ("kj", (64, 64), (1, 64)), ("ij", (1, 64), (1, 1)), level=2)
+    assert tc.tc_plan_info(p2)["level"] == 0
+    p3 = _plan(("ik", (3, 64), (1, 3)), ("kj", (64, 64), (1, 64)), ("ij", (3, 64), (1, 3)), level=2)
+    assert tc.tc_plan_info(p3)["level"] == 1
+    assert tc.tc_plan_info(p3)["level_requested"] == 2
+
+
+@pytest.mark.parametrize("level", [1, 2])
+@pytest.mark.parametrize("variant", ["abc", "ab", "naive"])
+def test_schedule_satisfies_brent_equations(level, variant):
+    """The library's own product schedule, read back through the ABI, multiplies block matrices correctly."""
+    N = 64
+    g = 1 << level
+    p = _plan(("ik", (N, N), (1, N)), ("kj", (N, N), (1, N)), ("ij", (N, N), (1, N)), level=level, variant=variant)
+    info = tc.tc_plan_info(p)
+    assert info["level"] == level and info["n_products"] == 7 ** level
+    sched = tc.tc_plan_schedule(p)
+    T = np.zeros((g,) * 6, dtype=np.int64)
+    seen = set()
+    for e in sched:
+        for (ai, ak, sa) in e["a"]:
+            for (bk, bj, sb) in e["b"]:
+                for (ci, cj, sc) in e["c"]:
+                    T[ai, ak, bk, bj, ci, cj] += sa * sb * sc
+        for (ci, cj, _), first in zip(e["c"], e["c_first"]):
+            assert bool(first) == ((ci, cj) not in seen)
+            seen.add((ci, cj))
+    want = np.zeros_like(T)
+    for i in range(g):
+        for k in range(g):
+            for j in range(g):
+                want[i, k, k, j, i, j] = 1
+    assert np.array_equal(T, want)
+    assert len(seen) == g * g  # every block of C is written, each takes beta exactly once
+    na = sum(len(e["a"]) for e in sched)
+    nb = sum(len(e["b"]) for e in sched)
+    nc = sum(len(e["c"]) for e in sched)
+    assert (na, nb, nc) == ((12, 12, 12) if level == 1 else (144, 144, 144))
+    # products sharing a launch write disjoint blocks
+    by_launch = {}
+    for e in sched:
+        blocks = by_launch.setdefault(e["launch"], set())
+        for (ci, cj, _) in e["c"]:
+            assert (ci, cj) not in blocks
+            blocks.add((ci, cj))
+    ws = tc.tc_plan_workspace_bytes(p)
+    blk = info["mb"] * info["nb"], info["mb"] * info["kb"], info["kb"] * info["nb"]
+    assert ws == {"abc": 0, "ab": 8 * blk[0], "naive": 8 * sum(blk)}[variant]
+    if variant == "abc":
+        assert info["n_launches"] == (4 if level == 1 else len(by_launch))
+        assert info["n_launches"] < 7 ** level
+
+
+def test_schedule_prunes_blocks_in_the_padding():
+    # m = 20 at level 2: block extent 16 => block rows 2 and 3 are empty
+    p = _plan(("ik", (20, 64), (1, 20)), ("kj", (64, 64), (1, 64)), ("ij", (20, 64), (1, 20)), level=2)
+    info = tc.tc_plan_info(p)
+    assert info["mb"] == 16
+    for e in tc.tc_plan_schedule(p):
+        assert all(r < 2 for (r, _, _) in e["a"]) and all(r < 2 for (r, _, _) in e["c"])
+        assert e["a"] and e["b"] and e["c"]
+
+
+def test_empty_bundles():
+    p = _plan(("ik", (0, 5), (1, 1)), ("kj", (5, 6), (1, 5)), ("ij", (0, 6), (1, 1)))
+    assert tc.tc_plan_info(p)["n_launches"] == 0
+    p = _plan(("ik", (4, 0), (1, 4)), ("kj", (0, 6), (1, 1)), ("ij", (4, 6), (1, 4)), level=1)
+    assert tc.tc_plan_info(p)["n_launches"] == 1  # C := beta * C
+    p = _plan(("", (), ()), ("", (), ()), ("", (), ()))  # scalar times scalar
+    info = tc.tc_plan_info(p)
+    assert (info["m"], info["n"], info["k"]) == (1, 1, 1)

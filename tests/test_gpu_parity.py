@@ -1,0 +1,176 @@
+"""GPU parity: the HIP library (through its C ABI) against the classical CPU oracle, element by element,
+on seeded inputs.  Tolerance: ||C - C_ref||_F / (||A||_F ||B||_F) <= 1e-13 (level 0 and 1), 1e-12 (level 2);
+small-integer inputs must agree bit for bit."""
+import random
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from workloads import from_dense, strides_for_order
+
+pytestmark = pytest.mark.gpu
+
+TOL = {0: 1e-13, 1: 1e-13, 2: 1e-12}
+MODES = [(0, "abc"), (1, "abc"), (1, "ab"), (1, "naive"), (2, "abc"), (2, "ab"), (2, "naive")]
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_1704_03092_amd as tc
+
+    tc.load_library()
+    from gpu_util import run_gpu, logical
+
+    return run_gpu, logical
+
+
+def _check(gpu, A, B, C, alpha, beta, level, variant, exact=False, **kw):
+    run_gpu, logical = gpu
+    ref = C.copy()
+    oracle.contract_matrix(A, B, ref, alpha, beta)
+    print(f"case idx={C.idx}-{A.idx}-{B.idx} lens={C.lens}/{A.lens}/{B.lens} level={level} variant={variant} a={alpha} b={beta}", flush=True)
+    got_flat, info = run_gpu(A, B, C, alpha, beta, level, variant, **kw)
+    got = logical(C, got_flat)
+    # storage outside the tensor (padding between strides) must be untouched
+    mask = np.ones(C.data.shape, dtype=bool)
+    mask[(oracle.matrix_view(A, B, C)["rsC"][:, None] + oracle.matrix_view(A, B, C)["csC"][None, :]).ravel()] = False
+    assert np.array_equal(got_flat[mask], C.data[mask], equal_nan=True)
+    if exact:
+        assert np.array_equal(got, ref.view()), (level, variant)
+    else:
+        err = oracle.error_metric(got, ref.view(), oracle.tensor_norm(A), oracle.tensor_norm(B))
+        assert err <= TOL[level], (level, variant, err)
+    return info
+
+
+@pytest.mark.parametrize("level,variant", MODES)
+def test_small_gemm_all_modes(gpu, level, variant):
+    # spans several 128x128 tiles with ragged edges in every direction, odd sizes
+    for (m, n, k) in [(300, 275, 190), (129, 130, 33), (1, 1, 1), (5, 3, 2), (257, 64, 512)]:
+        c = workloads.Contraction("g", "ij", "ik", "kj", {"i": m, "j": n, "k": k}, seed=m * 7 + n)
+        A, B, C = c.tensors()
+        _check(gpu, A, B, C, 1.0, 1.0, level, variant)
+        Ai, Bi, Ci = c.tensors(kind="smallint")
+        _check(gpu, Ai, Bi, Ci, 2.0, -1.0, level, variant, exact=True)
+
+
+@pytest.mark.parametrize("level,variant", MODES)
+def test_alpha_beta_and_nan_poisoned_C(gpu, level, variant):
+    c = workloads.Contraction("g", "ij", "ik", "kj", {"i": 200, "j": 150, "k": 100}, seed=5)
+    A, B, C = c.tensors()
+    _check(gpu, A, B, C, -0.75, 0.5, level, variant)
+    C.data[:] = np.nan
+    run_gpu, logical = gpu
+    got_flat, _ = run_gpu(A, B, C, 1.5, 0.0, level, variant)
+    ref = from_dense("ij", np.zeros((200, 150)))
+    oracle.contract_matrix(A, B, ref, 1.5, 0.0)
+    err = oracle.error_metric(logical(C, got_flat), ref.view(), oracle.tensor_norm(A), oracle.tensor_norm(B))
+    assert err <= TOL[level]
+
+
+def _random_case(rng, kind="uniform"):
+    labels = list("abcdefghijkl")
+    rng.shuffle(labels)
+    nI, nJ, nP = rng.randint(0, 3), rng.randint(0, 3), rng.randint(0, 3)
+    I, J, P = labels[:nI], labels[nI:nI + nJ], labels[nI + nJ:nI + nJ + nP]
+    lengths = {c: rng.choice([1, 2, 3, 5, 7, 12, 17]) for c in I + J + P}
+    idxA, idxB, idxC = I + P, P + J, I + J
+    for s in (idxA, idxB, idxC):
+        rng.shuffle(s)
+    tens = []
+    for tid, idx in enumerate((idxA, idxB, idxC)):
+        lens = [lengths[c] for c in idx]
+        order = list(range(len(idx)))
+        rng.shuffle(order)
+        st = strides_for_order(lens, order, pad=rng.randint(0, 2))
+        tens.append(workloads.make_tensor("".join(idx), lengths, rng.randint(0, 10 ** 6), tid, kind, st))
+    return tens
+
+
+def test_random_contractions_random_layouts(gpu):
+    rng = random.Random(2024)
+    for trial in range(40):
+        A, B, C = _random_case(rng, "smallint" if trial % 2 else "uniform")
+        level, variant = MODES[trial % len(MODES)]
+        _check(gpu, A, B, C, rng.choice([1.0, -2.0]), rng.choice([0.0, 1.0, 3.0]), level, variant, exact=bool(trial % 2))
+
+
+def test_benchmark_index_strings_reduced_sizes(gpu):
+    cfgs = workloads.configs()
+    small = {
+        "cfg1": {x: 5 for x in "abcdef"},
+        "cfg3": {"a": 12, "b": 11, "e": 13, "f": 9, "i": 6, "j": 7},
+        "cfg4a": {"a": 13, "b": 21, "c": 12, "d": 17, "e": 9},
+        "cfg4b": {"a": 18, "b": 9, "c": 11, "d": 14, "e": 40},
+        "cfg5": {"a": 6, "b": 5, "c": 7, "d": 4, "e": 6, "f": 5, "g": 11, "h": 9},
+    }
+    for name, L in small.items():
+        cfg = workloads.scaled(cfgs[name], L)
+        for level, variant in [(0, "abc"), (1, "abc"), (1, "ab"), (2, "abc"), (2, "naive")]:
+            for layout in ("col", "row"):
+                A, B, C = cfg.tensors(layout=layout)
+                _check(gpu, A, B, C, cfg.alpha, cfg.beta, level, variant)
+
+
+def test_planner_vectors_match_oracle_and_paper_example(gpu):
+    import torch
+    import paper_1704_03092_amd as tc
+
+    # the paper's example, block size 4
+    L = dict(a=4, b=8, c=2, d=8)
+    A = workloads.make_tensor("dca", L, 1, 0)
+    B = workloads.make_tensor("db", L, 1, 1)
+    C = workloads.make_tensor("abc", L, 1, 2)
+    p = tc.tc_plan(A, B, C, 0, "abc", torch.cuda.current_stream(), bs_block=4)
+    info = tc.tc_plan_info(p)
+    assert info["I"] == "ac" and info["J"] == "b" and info["P"] == "d"
+    rsC, csC = tc.tc_plan_vector(p, 4), tc.tc_plan_vector(p, 5)
+    assert rsC[6] == 34 and csC[3] == 12  # LOC(C_{2,3,1}) = 34 + 12
+    assert list(rsC) == [0, 1, 2, 3, 32, 33, 34, 35]
+    assert list(tc.tc_plan_vector(p, 10)) == [1, 1] and list(tc.tc_plan_vector(p, 11)) == [4, 4]  # rbs_C, cbs_C
+    tc.tc_destroy(p)
+    # random tensors: all twelve vectors equal the oracle's, using the bundle orders the plan chose
+    rng = random.Random(77)
+    for _ in range(10):
+        A, B, C = _random_case(rng)
+        bs = rng.choice([1, 3, 4, 16])
+        p = tc.tc_plan(A, B, C, 0, "abc", torch.cuda.current_stream(), bs_block=bs)
+        info = tc.tc_plan_info(p)
+        v = oracle.matrix_view(A, B, C, orders=(list(info["I"]), list(info["J"]), list(info["P"])))
+        for which, key in enumerate(["rsA", "csA", "rsB", "csB", "rsC", "csC"]):
+            got = tc.tc_plan_vector(p, which)
+            assert np.array_equal(got, v[key]), key
+            assert np.array_equal(tc.tc_plan_vector(p, 6 + which), oracle.block_scatter(v[key], bs)), key
+        tc.tc_destroy(p)
+
+
+def test_degenerate_shapes(gpu):
+    run_gpu, logical = gpu
+    # empty contracted bundle: outer product; empty free bundles: dot product; k = 0: C := beta C; m = 0: no-op
+    A = workloads.make_tensor("i", {"i": 37}, 1, 0)
+    B = workloads.make_tensor("j", {"j": 41}, 1, 1)
+    C = workloads.make_tensor("ij", {"i": 37, "j": 41}, 1, 2)
+    _check(gpu, A, B, C, 2.0, 1.0, 0, "abc")
+    _check(gpu, A, B, C, 2.0, 1.0, 1, "ab")
+    A = workloads.make_tensor("k", {"k": 1000}, 2, 0)
+    B = workloads.make_tensor("k", {"k": 1000}, 2, 1)
+    C = workloads.make_tensor("", {}, 2, 2)
+    _check(gpu, A, B, C, 1.0, 0.5, 0, "abc")
+    _check(gpu, A, B, C, 1.0, 0.5, 2, "abc")
+    A = workloads.make_tensor("ik", {"i": 9, "k": 0}, 3, 0)
+    B = workloads.make_tensor("kj", {"j": 8, "k": 0}, 3, 1)
+    C = workloads.make_tensor("ij", {"i": 9, "j": 8}, 3, 2)
+    got, _ = run_gpu(A, B, C, 1.0, -2.0, 1, "abc")
+    assert np.array_equal(got, -2.0 * C.data)
+    got, _ = run_gpu(A, B, C, 1.0, 0.0, 0, "abc")
+    assert np.array_equal(got, np.zeros_like(C.data))
+    A = workloads.make_tensor("ik", {"i": 0, "k": 5}, 3, 0)
+    B = workloads.make_tensor("kj", {"j": 8, "k": 5}, 3, 1)
+    C = workloads.make_tensor("ij", {"i": 0, "j": 8}, 3, 2)
+    got, info = run_gpu(A, B, C, 1.0, 1.0, 1, "naive")
+    assert info["n_launches"] == 0
