@@ -27,7 +27,8 @@ namespace {
 constexpr int TM = 128;      // tile rows (free bundle I)
 constexpr int TN = 128;      // tile columns (free bundle J)
 constexpr int KT = 16;       // contracted entries per pipeline step
-constexpr int NTHREADS = 256;
+constexpr int NTHREADS = 512;  // 8 waves: 2 along the rows x 4 along the columns, each owning 64 x 32 outputs
+constexpr int NE = TM * KT / NTHREADS;  // elements of each operand tile a thread gathers per k-step (4)
 constexpr int GROUP_M = 8;   // tile rows per rasterisation group
 
 // LDS tile layout: element (k, x) of a KT x 128 tile lives at k * PITCH + x.  Matrix-core instruction q of a k-step
@@ -51,64 +52,54 @@ struct FusedSmem {
     int64_t b_rs[2][NT][KT];
 };
 
-// Issue the loads of 8 elements of one term of the A (or B) tile for one k-step.
-//   MODE 0: lanes run along the 128 free entries (x), each thread covers k = k0 + 2e
-//   MODE 1: lanes run along the 16 contracted entries (k), each thread covers x = x0 + 16e
-// CHECKED: entries of the zero padding (negative offset) read element 0 and are zeroed when the term is consumed.
-template <int MODE, bool CHECKED>
-__device__ __forceinline__ void issue_term(double (&ld)[8], unsigned& padmask, const double* __restrict__ base,
-                                           const int64_t* __restrict__ fixed_tab /* [128] */,
-                                           const int64_t* __restrict__ step_tab /* [KT] */, int tid) {
+// Each thread gathers NE = 4 elements of the A tile and 4 of the B tile per k-step, for every term.
+//   MODE 0: lanes run along the 128 free entries (x); element e of a thread is (x = tid % 128, k = tid / 128 + 4e)
+//   MODE 1: lanes run along the 16 contracted entries (k); element e is (k = tid % 16, x = tid / 16 + 32e)
+// The loads of a k-step are issued before the matrix-core work on the previous one and, after it, summed with
+// their signs (the operand sum of Sec. 4.1) and stored into the other LDS buffer.
+// CHECKED: entries of the zero padding (negative offset) read element 0 and count as zero.
+template <int MODE, int NT, bool CHECKED>
+__device__ __forceinline__ void issue_loads(double (&ld)[NT][NE], unsigned& padmask, const double* __restrict__ base,
+                                            const int64_t* __restrict__ fixed_tab /* [NT][128] */,
+                                            const int64_t* __restrict__ step_tab /* [NT][KT] */, int nterms, int tid) {
     padmask = 0;
-    if (MODE == 0) {
-        const int64_t fx = fixed_tab[tid & 127];
-        const int64_t* st = step_tab + (tid >> 7);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int64_t off = fx + st[2 * e];
-            if (CHECKED) {
-                padmask |= (off < 0 ? 1u : 0u) << e;
-                ld[e] = base[off < 0 ? 0 : off];
-            } else {
-                ld[e] = base[off];
-            }
-        }
-    } else {
-        const int64_t fk = step_tab[tid & 15];
-        const int64_t* ft = fixed_tab + (tid >> 4);
+    for (int t = 0; t < NT; ++t) {
+        if (t > 0 && t >= nterms) {  // absent term: contributes zeros (its coefficient is zero as well)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int64_t off = fk + ft[16 * e];
-            if (CHECKED) {
-                padmask |= (off < 0 ? 1u : 0u) << e;
-                ld[e] = base[off < 0 ? 0 : off];
-            } else {
-                ld[e] = base[off];
+            for (int e = 0; e < NE; ++e) ld[t][e] = 0.0;
+        } else {
+#pragma unroll
+            for (int e = 0; e < NE; ++e) {
+                int64_t off;
+                if (MODE == 0)
+                    off = fixed_tab[t * 128 + (tid & 127)] + step_tab[t * KT + (tid >> 7) + 4 * e];
+                else
+                    off = step_tab[t * KT + (tid & 15)] + fixed_tab[t * 128 + (tid >> 4) + 32 * e];
+                if (CHECKED) {
+                    padmask |= (off < 0 ? 1u : 0u) << (t * NE + e);
+                    ld[t][e] = base[off < 0 ? 0 : off];
+                } else {
+                    ld[t][e] = base[off];
+                }
             }
         }
     }
 }
 
-// v = coef * ld (first term) or v += coef * ld : the operand sum of Sec. 4.1, formed in registers
-template <bool CHECKED>
-__device__ __forceinline__ void consume_term(double (&v)[8], const double (&ld)[8], unsigned padmask, bool first, double coef) {
+template <int MODE, int NT, bool CHECKED>
+__device__ __forceinline__ void stage_sums(double* __restrict__ tile /* [TILE] */, const double (&ld)[NT][NE], unsigned padmask,
+                                           const double* __restrict__ coef, int tid) {
+    double* dst = (MODE == 0) ? tile + (tid >> 7) * PITCH + (tid & 127) : tile + (tid & 15) * PITCH + (tid >> 4);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const double x = (CHECKED && ((padmask >> e) & 1u)) ? 0.0 : ld[e];
-        v[e] = first ? coef * x : __builtin_fma(coef, x, v[e]);
-    }
-}
-
-template <int MODE>
-__device__ __forceinline__ void stage_tile(double* __restrict__ tile /* [TILE] */, const double (&v)[8], int tid) {
-    if (MODE == 0) {
-        double* dst = tile + (tid >> 7) * PITCH + (tid & 127);
+    for (int e = 0; e < NE; ++e) {
+        double v = 0.0;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) dst[2 * e * PITCH] = v[e];
-    } else {
-        double* dst = tile + (tid & 15) * PITCH + (tid >> 4);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) dst[16 * e] = v[e];
+        for (int t = 0; t < NT; ++t) {
+            const double x = (CHECKED && ((padmask >> (t * NE + e)) & 1u)) ? 0.0 : ld[t][e];
+            v = (t == 0) ? coef[0] * x : __builtin_fma(coef[t], x, v);
+        }
+        dst[(MODE == 0) ? 4 * e * PITCH : 32 * e] = v;
     }
 }
 
@@ -172,7 +163,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     const int64_t* ent_ptr = nullptr;
     int64_t ent_limit = 0;  // k entries that exist for this thread's term
     int64_t* ent_dst = nullptr;
-    {
+    if (tid < 256) {
         const bool isB = tid >= 128;
         const int q = tid & 127, t = q >> 4, kl = q & 15;
         if (t < NT) {
@@ -194,37 +185,28 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     const double* Abase = pick_src(P.A.space, Au, W, P.A.base_off);
     const double* Bbase = pick_src(P.B.space, Bu, W, P.B.base_off);
 
-    double va[8], vb[8], la[8], lb[8];
+    double la[NT][NE], lb[NT][NE];
     unsigned pa = 0, pb = 0;
     // ---- prologue: stage k-step 0 ----
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        if (t < nA) {
-            issue_term<AMODE, true>(la, pa, Abase, S.a_rs[t], S.a_cs[0][t], tid);
-            consume_term<true>(va, la, pa, t == 0, P.A.coef[t]);
-        }
-        if (t < nB) {
-            issue_term<BMODE, true>(lb, pb, Bbase, S.b_cs[t], S.b_rs[0][t], tid);
-            consume_term<true>(vb, lb, pb, t == 0, P.B.coef[t]);
-        }
-    }
-    stage_tile<AMODE>(&S.a[0][0], va, tid);
-    stage_tile<BMODE>(&S.b[0][0], vb, tid);
+    issue_loads<AMODE, NT, true>(la, pa, Abase, &S.a_rs[0][0], &S.a_cs[0][0][0], nA, tid);
+    issue_loads<BMODE, NT, true>(lb, pb, Bbase, &S.b_cs[0][0], &S.b_rs[0][0][0], nB, tid);
+    stage_sums<AMODE, NT, true>(&S.a[0][0], la, pa, P.A.coef, tid);
+    stage_sums<BMODE, NT, true>(&S.b[0][0], lb, pb, P.B.coef, tid);
     __syncthreads();
 
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave >> 2, wn = wave & 3;
     const int l16 = lane & 15, lk = lane >> 4;
     // per-lane fragment bases; everything else in a fragment address is a compile-time offset
     const double* fa = &S.a[0][0] + 4 * lk * PITCH + wm * 64 + l16;
     const double* fb[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) fb[s] = &S.b[0][0] + 4 * lk * PITCH + wn * 64 + ((l16 + 4 * s) & 15);
-    double acc[4][4][4];
+    for (int s = 0; s < 4; ++s) fb[s] = &S.b[0][0] + 4 * lk * PITCH + wn * 32 + ((l16 + 4 * s) & 15);
+    double acc[4][2][4];
 #pragma unroll
     for (int x = 0; x < 4; ++x)
 #pragma unroll
-        for (int y = 0; y < 4; ++y)
+        for (int y = 0; y < 2; ++y)
 #pragma unroll
             for (int s = 0; s < 4; ++s) acc[x][y][s] = 0.0;
 
@@ -235,35 +217,24 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         int64_t next_entry = kSentinel;
         const int64_t k2 = (int64_t)(step + 2) * KT;
         if (k2 < ent_limit) next_entry = ent_ptr[k2];
+        if (more) {
+            if (fast) {
+                issue_loads<AMODE, NT, false>(la, pa, Abase, &S.a_rs[0][0], &S.a_cs[nxt][0][0], nA, tid);
+                issue_loads<BMODE, NT, false>(lb, pb, Bbase, &S.b_cs[0][0], &S.b_rs[nxt][0][0], nB, tid);
+            } else {
+                issue_loads<AMODE, NT, true>(la, pa, Abase, &S.a_rs[0][0], &S.a_cs[nxt][0][0], nA, tid);
+                issue_loads<BMODE, NT, true>(lb, pb, Bbase, &S.b_cs[0][0], &S.b_rs[nxt][0][0], nB, tid);
+            }
+        }
 
         const int toff = cur * TILE;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            // The terms of the next k-step are gathered while the matrix cores work on this one: term t is issued
-            // at quarter t * (4 / NT) and added to the running sum one slot later, when its loads have landed.
-            if (more && kk % (4 / NT) == 0) {
-                const int t = kk / (4 / NT);
-                if (fast) {
-                    if (t > 0) {
-                        if (t - 1 < nA) consume_term<false>(va, la, 0, t == 1, P.A.coef[t - 1]);
-                        if (t - 1 < nB) consume_term<false>(vb, lb, 0, t == 1, P.B.coef[t - 1]);
-                    }
-                    if (t < nA) issue_term<AMODE, false>(la, pa, Abase, S.a_rs[t], S.a_cs[nxt][t], tid);
-                    if (t < nB) issue_term<BMODE, false>(lb, pb, Bbase, S.b_cs[t], S.b_rs[nxt][t], tid);
-                } else {
-                    if (t > 0) {
-                        if (t - 1 < nA) consume_term<true>(va, la, pa, t == 1, P.A.coef[t - 1]);
-                        if (t - 1 < nB) consume_term<true>(vb, lb, pb, t == 1, P.B.coef[t - 1]);
-                    }
-                    if (t < nA) issue_term<AMODE, true>(la, pa, Abase, S.a_rs[t], S.a_cs[nxt][t], tid);
-                    if (t < nB) issue_term<BMODE, true>(lb, pb, Bbase, S.b_cs[t], S.b_rs[nxt][t], tid);
-                }
-            }
             double af[4];
 #pragma unroll
             for (int x = 0; x < 4; ++x) af[x] = fa[toff + kk * PITCH + x * 16];
 #pragma unroll
-            for (int y = 0; y < 4; ++y) {
+            for (int y = 0; y < 2; ++y) {
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
                     const double bf = fb[s][toff + kk * PITCH + y * 16];
@@ -273,10 +244,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
             }
         }
         if (more) {
-            if (NT - 1 < nA) consume_term<true>(va, la, pa, NT == 1, P.A.coef[NT - 1]);
-            if (NT - 1 < nB) consume_term<true>(vb, lb, pb, NT == 1, P.B.coef[NT - 1]);
-            stage_tile<AMODE>(&S.a[nxt][0], va, tid);
-            stage_tile<BMODE>(&S.b[nxt][0], vb, tid);
+            stage_sums<AMODE, NT, true>(&S.a[nxt][0], la, pa, P.A.coef, tid);
+            stage_sums<BMODE, NT, true>(&S.b[nxt][0], lb, pb, P.B.coef, tid);
         }
         if (ent_dst && step + 2 < nk) ent_dst[cur * NT * KT] = next_entry;
         __syncthreads();
@@ -309,10 +278,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
 #pragma unroll
         for (int x = 0; x < 4; ++x) rsv[x] = c_rs[d][wm * 64 + x * 16 + dblk * 4 + di];
 #pragma unroll
-        for (int y = 0; y < 4; ++y) {
+        for (int y = 0; y < 2; ++y) {
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const int64_t csv = c_cs[d][wn * 64 + y * 16 + ((dblk + s) & 3) * 4 + dj];
+                const int64_t csv = c_cs[d][wn * 32 + y * 16 + ((dblk + s) & 3) * 4 + dj];
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
                     const int64_t off = rsv[x] + csv;
