@@ -42,24 +42,38 @@ __device__ __forceinline__ const double* pick_src(int space, const double* user,
     return (space == 0 ? user : W) + off;
 }
 
+// Scatter vectors are reached through pointers stored in the product descriptors; telling the compiler that they
+// point to global memory keeps their loads off the flat path (a pending flat load forces a full wait before the
+// next LDS access).
+typedef const __attribute__((address_space(1))) int64_t* gvec_t;
+__device__ __forceinline__ gvec_t as_global(const int64_t* p) { return (gvec_t)p; }
+
+// Non-matrix VALU instructions do not overlap with v_mfma_f64_4x4x4 on this chip (measured: every integer or
+// fp64 VALU instruction adds its full issue time), so the main loop is written to need as few of them as possible:
+// the gather tables hold ready-made byte addresses (one 64-bit add per loaded element), the k-step loop is
+// unrolled over the two LDS buffers so that every LDS address is a per-lane base plus a constant, and an
+// operand with a single +1 term is stored as loaded.
 template <int NT>
 struct FusedSmem {
     double a[2][TILE];
     double b[2][TILE];
-    int64_t a_rs[NT][TM];      // row scatter of this tile's rows, per term (kSentinel where padded)
-    int64_t b_cs[NT][TN];      // column scatter of this tile's columns, per term
-    int64_t a_cs[2][NT][KT];   // column scatter of the current / next k-step
-    int64_t b_rs[2][NT][KT];
+    int64_t a_fix[NT][TM];      // per term: address of row x of the A blocks (base + 8 * rscat), kSentinel where padded
+    int64_t b_fix[NT][TN];      // per term: address of column x of the B blocks (base + 8 * cscat)
+    int64_t a_step[2][NT][KT];  // per term: 8 * cscat_A of the 16 contracted entries of a k-step (two steps in flight)
+    int64_t b_step[2][NT][KT];  // per term: 8 * rscat_B
+    int64_t dump[2][NT][KT];    // where threads that own no table entry store theirs (keeps that store branch-free)
 };
+
+typedef const __attribute__((address_space(1))) double* gdbl_t;
 
 // Each thread gathers NE = 4 elements of the A tile and 4 of the B tile per k-step, for every term.
 //   MODE 0: lanes run along the 128 free entries (x); element e of a thread is (x = tid % 128, k = tid / 128 + 4e)
 //   MODE 1: lanes run along the 16 contracted entries (k); element e is (k = tid % 16, x = tid / 16 + 32e)
 // The loads of a k-step are issued before the matrix-core work on the previous one and, after it, summed with
 // their signs (the operand sum of Sec. 4.1) and stored into the other LDS buffer.
-// CHECKED: entries of the zero padding (negative offset) read element 0 and count as zero.
+// CHECKED: entries of the zero padding (negative table sum) read the operand's element 0 and count as zero.
 template <int MODE, int NT, bool CHECKED>
-__device__ __forceinline__ void issue_loads(double (&ld)[NT][NE], unsigned& padmask, const double* __restrict__ base,
+__device__ __forceinline__ void issue_loads(double (&ld)[NT][NE], unsigned& padmask, const double* __restrict__ safe,
                                             const int64_t* __restrict__ fixed_tab /* [NT][128] */,
                                             const int64_t* __restrict__ step_tab /* [NT][KT] */, int nterms, int tid) {
     padmask = 0;
@@ -71,16 +85,16 @@ __device__ __forceinline__ void issue_loads(double (&ld)[NT][NE], unsigned& padm
         } else {
 #pragma unroll
             for (int e = 0; e < NE; ++e) {
-                int64_t off;
+                int64_t addr;
                 if (MODE == 0)
-                    off = fixed_tab[t * 128 + (tid & 127)] + step_tab[t * KT + (tid >> 7) + 4 * e];
+                    addr = fixed_tab[t * 128 + (tid & 127)] + step_tab[t * KT + (tid >> 7) + 4 * e];
                 else
-                    off = step_tab[t * KT + (tid & 15)] + fixed_tab[t * 128 + (tid >> 4) + 32 * e];
+                    addr = step_tab[t * KT + (tid & 15)] + fixed_tab[t * 128 + (tid >> 4) + 32 * e];
                 if (CHECKED) {
-                    padmask |= (off < 0 ? 1u : 0u) << (t * NE + e);
-                    ld[t][e] = base[off < 0 ? 0 : off];
+                    padmask |= (addr < 0 ? 1u : 0u) << (t * NE + e);
+                    ld[t][e] = *(gdbl_t)(addr < 0 ? (int64_t)safe : addr);
                 } else {
-                    ld[t][e] = base[off];
+                    ld[t][e] = *(gdbl_t)addr;
                 }
             }
         }
@@ -88,16 +102,20 @@ __device__ __forceinline__ void issue_loads(double (&ld)[NT][NE], unsigned& padm
 }
 
 template <int MODE, int NT, bool CHECKED>
-__device__ __forceinline__ void stage_sums(double* __restrict__ tile /* [TILE] */, const double (&ld)[NT][NE], unsigned padmask,
-                                           const double* __restrict__ coef, int tid) {
-    double* dst = (MODE == 0) ? tile + (tid >> 7) * PITCH + (tid & 127) : tile + (tid & 15) * PITCH + (tid >> 4);
+__device__ __forceinline__ void stage_sums(double* __restrict__ dst, const double (&ld)[NT][NE], unsigned padmask,
+                                           const double* __restrict__ coef, bool plain) {
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
-        double v = 0.0;
+        double v;
+        if (NT == 1 && !CHECKED) {
+            v = plain ? ld[0][e] : coef[0] * ld[0][e];
+        } else {
+            v = 0.0;
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const double x = (CHECKED && ((padmask >> (t * NE + e)) & 1u)) ? 0.0 : ld[t][e];
-            v = (t == 0) ? coef[0] * x : __builtin_fma(coef[t], x, v);
+            for (int t = 0; t < NT; ++t) {
+                const double x = (CHECKED && ((padmask >> (t * NE + e)) & 1u)) ? 0.0 : ld[t][e];
+                v = (t == 0) ? coef[0] * x : __builtin_fma(coef[t], x, v);
+            }
         }
         dst[(MODE == 0) ? 4 * e * PITCH : 32 * e] = v;
     }
@@ -106,12 +124,119 @@ __device__ __forceinline__ void stage_sums(double* __restrict__ tile /* [TILE] *
 __device__ __forceinline__ int64_t min64(int64_t a, int64_t b) { return a < b ? a : b; }
 
 template <int AMODE, int BMODE, int NT>
+struct FusedState {
+    // How many k-steps ahead of the multiplication the gather runs.  Loads take longer than one k-step of
+    // matrix-core work to arrive, so with registers to spare (NT <= 2) two k-steps are kept in flight.
+    static constexpr int D = (NT <= 2) ? 2 : 1;
+    FusedSmem<NT>* S;
+    const Product* P;
+    int tid, nA, nB, nk, kfull;
+    bool plainA, plainB;       // single term with coefficient +1: staged as loaded
+    bool early;                // this wave issues its gather before the first quarter of matrix-core work, its
+                               // partner on the same SIMD after the second: one of the two always has MFMAs to issue
+    const double *safeA, *safeB;
+    // scatter entries of later k-steps
+    gvec_t ent_ptr;
+    int ent_limit;             // k entries that exist for this thread's term, counted from its own k
+    int64_t* ent_dst;
+    // per-lane LDS bases
+    const double* fa;
+    const double* fb[4];
+    double* sa;                // where this thread stages its A elements (buffer 0)
+    double* sb;
+    double acc[4][2][4];
+    double la[D][NT][NE], lb[D][NT][NE];
+    unsigned pa[D], pb[D];
+    bool setfast[D];           // the loads held in that register set were issued without padding checks
+
+    // gather of k-step `target` into register set SET (table slot = target % 2 = SLOT)
+    template <int SET, int SLOT>
+    __device__ __forceinline__ void issue(int target) {
+        if (target < nk) {
+            const bool fast = target < kfull;  // no padding anywhere in that k-step
+            setfast[SET] = fast;
+            if (fast) {
+                issue_loads<AMODE, NT, false>(la[SET], pa[SET], safeA, &S->a_fix[0][0], &S->a_step[SLOT][0][0], nA, tid);
+                issue_loads<BMODE, NT, false>(lb[SET], pb[SET], safeB, &S->b_fix[0][0], &S->b_step[SLOT][0][0], nB, tid);
+            } else {
+                issue_loads<AMODE, NT, true>(la[SET], pa[SET], safeA, &S->a_fix[0][0], &S->a_step[SLOT][0][0], nA, tid);
+                issue_loads<BMODE, NT, true>(lb[SET], pb[SET], safeB, &S->b_fix[0][0], &S->b_step[SLOT][0][0], nB, tid);
+            }
+        }
+    }
+
+    // operand sums of register set SET into LDS buffer BUF
+    template <int SET, int BUF>
+    __device__ __forceinline__ void stage() {
+        if (setfast[SET]) {
+            stage_sums<AMODE, NT, false>(sa + BUF * TILE, la[SET], 0, P->A.coef, plainA);
+            stage_sums<BMODE, NT, false>(sb + BUF * TILE, lb[SET], 0, P->B.coef, plainB);
+        } else {
+            stage_sums<AMODE, NT, true>(sa + BUF * TILE, la[SET], pa[SET], P->A.coef, false);
+            stage_sums<BMODE, NT, true>(sb + BUF * TILE, lb[SET], pb[SET], P->B.coef, false);
+        }
+    }
+
+    template <int CUR, int Q>
+    __device__ __forceinline__ void read_frags(double (&af)[4], double (&bf)[8]) {
+#pragma unroll
+        for (int x = 0; x < 4; ++x) af[x] = fa[CUR * TILE + Q * PITCH + x * 16];
+#pragma unroll
+        for (int y = 0; y < 2; ++y)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) bf[y * 4 + s] = fb[s][CUR * TILE + Q * PITCH + y * 16];
+    }
+
+    __device__ __forceinline__ void multiply(const double (&af)[4], const double (&bf)[8]) {
+#pragma unroll
+        for (int y = 0; y < 2; ++y)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                    acc[x][y][s] = __builtin_amdgcn_mfma_f64_4x4x4f64(af[x], bf[y * 4 + s], acc[x][y][s], 0, 0, 0);
+    }
+
+    // One k-step: gather k-step step + D, multiply the tiles of this step (LDS buffer CUR), stage k-step step + 1.
+    template <int CUR>
+    __device__ __forceinline__ void step_body(int step) {
+        constexpr int NXT = CUR ^ 1;
+        constexpr int ISET = (D == 2) ? CUR : 0;   // register set the gather of this step lands in
+        constexpr int SSET = (D == 2) ? NXT : 0;   // register set staged at the end of this step (k-step step + 1)
+        constexpr int SLOT = (D == 2) ? CUR : NXT;  // table slot holding the entries of k-step step + D
+        if (early) issue<ISET, SLOT>(step + D);
+        // table entry of k-step step + D + 1; unconditional load: ent_ptr always points at readable memory
+        const int kn = (step + D + 1) * KT;
+        const bool have = kn < ent_limit;
+        const int64_t raw_entry = ent_ptr[have ? kn : 0];
+
+        // matrix-core work; the fragments of quarter q + 1 are read from LDS while quarter q multiplies
+        double af[2][4], bf[2][8];
+        read_frags<CUR, 0>(af[0], bf[0]);
+        read_frags<CUR, 1>(af[1], bf[1]);
+        multiply(af[0], bf[0]);
+        read_frags<CUR, 2>(af[0], bf[0]);
+        multiply(af[1], bf[1]);
+        if (!early) issue<ISET, SLOT>(step + D);
+        read_frags<CUR, 3>(af[1], bf[1]);
+        multiply(af[0], bf[0]);
+        multiply(af[1], bf[1]);
+
+        if (step + 1 < nk) stage<SSET, NXT>();
+        ent_dst[(SLOT ^ 1) * NT * KT] = have ? raw_entry * 8 : kSentinel;  // every thread stores: no branch around the wait
+        __syncthreads();
+    }
+};
+
+template <int AMODE, int BMODE, int NT>
 __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __restrict__ prods, int first, int tiles_m, int tiles_n,
                                                             const double* __restrict__ Au, const double* __restrict__ Bu,
                                                             double* __restrict__ Cu, double* __restrict__ W, double alpha, double beta) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     FusedSmem<NT>& S = *reinterpret_cast<FusedSmem<NT>*>(smem_raw);
     const int tid = threadIdx.x;
+    typedef FusedState<AMODE, BMODE, NT> State;
+    constexpr int D = State::D;
 
     // ---- which tile: spread consecutive logical ids over one XCD (block b runs on XCD b % 8), then walk
     //      GROUP_M tile rows at a time so that co-resident workgroups share A and B panels in that XCD's L2 ----
@@ -130,9 +255,24 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     const Product& P = prods[first + pidx];
     const int64_t i0 = (int64_t)tm * TM, j0 = (int64_t)tn * TN;
     const int nA = P.A.nterms, nB = P.B.nterms;
-    const int nk = (int)((P.kb + KT - 1) / KT);
 
-    // ---- tile-fixed scatter tables; how much of the tile and of the k range is free of zero padding ----
+    State st;
+    st.S = &S;
+    st.P = &P;
+    st.tid = tid;
+    st.nA = nA;
+    st.nB = nB;
+    st.nk = (int)((P.kb + KT - 1) / KT);
+    st.plainA = nA == 1 && P.A.coef[0] == 1.0;
+    st.plainB = nB == 1 && P.B.coef[0] == 1.0;
+    const double* Abase = pick_src(P.A.space, Au, W, P.A.base_off);
+    const double* Bbase = pick_src(P.B.space, Bu, W, P.B.base_off);
+    st.safeA = Abase;
+    st.safeB = Bbase;
+#pragma unroll
+    for (int d = 0; d < D; ++d) st.pa[d] = st.pb[d] = 0, st.setfast[d] = false;
+
+    // ---- tile-fixed gather tables; how much of the tile and of the k range is free of zero padding ----
     int64_t klimit = P.kb;       // k entries that are real in every term of both operands
     bool tile_full = true;       // every row and column of the tile is real in every term
 #pragma unroll
@@ -146,109 +286,73 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
             tile_full = tile_full && (j0 + TN <= min64(P.nb, P.B.cs_len - P.B.coff[t]));
         }
     }
-    const int kfull = tile_full ? (int)(klimit / KT) : 0;  // k-steps [0, kfull) need no checks
+    st.kfull = tile_full ? (int)(klimit / KT) : 0;  // k-steps [0, kfull) need no checks
     for (int e = tid; e < NT * TM; e += NTHREADS) {
         const int t = e / TM, x = e % TM;
         const int64_t gi = i0 + x;
         int64_t val = kSentinel;
-        if (t < nA && gi < P.mb && P.A.roff[t] + gi < P.A.rs_len) val = P.A.rs[P.A.roff[t] + gi];
-        S.a_rs[t][x] = val;
+        if (t < nA && gi < P.mb && P.A.roff[t] + gi < P.A.rs_len) val = (int64_t)Abase + 8 * as_global(P.A.rs)[P.A.roff[t] + gi];
+        S.a_fix[t][x] = val;
         const int64_t gj = j0 + x;
         val = kSentinel;
-        if (t < nB && gj < P.nb && P.B.coff[t] + gj < P.B.cs_len) val = P.B.cs[P.B.coff[t] + gj];
-        S.b_cs[t][x] = val;
+        if (t < nB && gj < P.nb && P.B.coff[t] + gj < P.B.cs_len) val = (int64_t)Bbase + 8 * as_global(P.B.cs)[P.B.coff[t] + gj];
+        S.b_fix[t][x] = val;
     }
     // Threads 0..16*NT-1 fetch the column scatter entries of A for a k-step (one per term and k), threads
-    // 128..128+16*NT-1 the row scatter entries of B; two k-steps ahead of the tile that uses them.
-    const int64_t* ent_ptr = nullptr;
-    int64_t ent_limit = 0;  // k entries that exist for this thread's term
-    int64_t* ent_dst = nullptr;
+    // 128..128+16*NT-1 the row scatter entries of B, ahead of the gather that uses them.
+    st.ent_ptr = as_global(reinterpret_cast<const int64_t*>(&P));  // dummy target for threads without an entry
+    st.ent_limit = 0;
+    st.ent_dst = &S.dump[0][0][0];
     if (tid < 256) {
         const bool isB = tid >= 128;
         const int q = tid & 127, t = q >> 4, kl = q & 15;
         if (t < NT) {
             const Operand& op = isB ? P.B : P.A;
-            ent_dst = isB ? &S.b_rs[0][t][kl] : &S.a_cs[0][t][kl];
+            st.ent_dst = isB ? &S.b_step[0][t][kl] : &S.a_step[0][t][kl];
             if (t < op.nterms) {
                 const int64_t off0 = isB ? op.roff[t] : op.coff[t];
-                ent_ptr = (isB ? op.rs : op.cs) + off0 + kl;
-                ent_limit = min64(P.kb, (isB ? op.rs_len : op.cs_len) - off0) - kl;
+                st.ent_ptr = as_global(isB ? op.rs : op.cs) + off0 + kl;
+                st.ent_limit = (int)(min64(P.kb, (isB ? op.rs_len : op.cs_len) - off0) - kl);
             }
         }
-        if (ent_dst) {
-            ent_dst[0] = (0 < ent_limit) ? ent_ptr[0] : kSentinel;
-            ent_dst[NT * KT] = (KT < ent_limit) ? ent_ptr[KT] : kSentinel;
-        }
     }
-    __syncthreads();
-
-    const double* Abase = pick_src(P.A.space, Au, W, P.A.base_off);
-    const double* Bbase = pick_src(P.B.space, Bu, W, P.B.base_off);
-
-    double la[NT][NE], lb[NT][NE];
-    unsigned pa = 0, pb = 0;
-    // ---- prologue: stage k-step 0 ----
-    issue_loads<AMODE, NT, true>(la, pa, Abase, &S.a_rs[0][0], &S.a_cs[0][0][0], nA, tid);
-    issue_loads<BMODE, NT, true>(lb, pb, Bbase, &S.b_cs[0][0], &S.b_rs[0][0][0], nB, tid);
-    stage_sums<AMODE, NT, true>(&S.a[0][0], la, pa, P.A.coef, tid);
-    stage_sums<BMODE, NT, true>(&S.b[0][0], lb, pb, P.B.coef, tid);
+    auto write_entry = [&](int kstep, int slot) {
+        st.ent_dst[slot * NT * KT] = (kstep * KT < st.ent_limit) ? 8 * st.ent_ptr[kstep * KT] : kSentinel;
+    };
+    write_entry(0, 0);
+    write_entry(1, 1);
     __syncthreads();
 
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
     const int l16 = lane & 15, lk = lane >> 4;
-    // per-lane fragment bases; everything else in a fragment address is a compile-time offset
-    const double* fa = &S.a[0][0] + 4 * lk * PITCH + wm * 64 + l16;
-    const double* fb[4];
+    st.early = wm == 0;
+    // per-lane bases; everything else in an LDS address is a compile-time offset
+    st.fa = &S.a[0][0] + 4 * lk * PITCH + wm * 64 + l16;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) fb[s] = &S.b[0][0] + 4 * lk * PITCH + wn * 32 + ((l16 + 4 * s) & 15);
-    double acc[4][2][4];
+    for (int s = 0; s < 4; ++s) st.fb[s] = &S.b[0][0] + 4 * lk * PITCH + wn * 32 + ((l16 + 4 * s) & 15);
+    st.sa = &S.a[0][0] + ((AMODE == 0) ? (tid >> 7) * PITCH + (tid & 127) : (tid & 15) * PITCH + (tid >> 4));
+    st.sb = &S.b[0][0] + ((BMODE == 0) ? (tid >> 7) * PITCH + (tid & 127) : (tid & 15) * PITCH + (tid >> 4));
+
+    // ---- prologue: k-step 0 into LDS buffer 0; with D = 2 the gather of k-step 1 is left in flight ----
+    st.template issue<0, 0>(0);
+    st.template stage<0, 0>();
+    if (D == 2) {
+        st.template issue<1, 1>(1);
+        __syncthreads();  // every thread has read the entries of k-step 0
+        write_entry(2, 0);
+    }
 #pragma unroll
     for (int x = 0; x < 4; ++x)
 #pragma unroll
         for (int y = 0; y < 2; ++y)
 #pragma unroll
-            for (int s = 0; s < 4; ++s) acc[x][y][s] = 0.0;
+            for (int s = 0; s < 4; ++s) st.acc[x][y][s] = 0.0;
+    __syncthreads();
 
-    for (int step = 0; step < nk; ++step) {
-        const int cur = step & 1, nxt = cur ^ 1;
-        const bool more = step + 1 < nk;
-        const bool fast = step + 1 < kfull;  // the k-step being gathered has no padding anywhere
-        int64_t next_entry = kSentinel;
-        const int64_t k2 = (int64_t)(step + 2) * KT;
-        if (k2 < ent_limit) next_entry = ent_ptr[k2];
-        if (more) {
-            if (fast) {
-                issue_loads<AMODE, NT, false>(la, pa, Abase, &S.a_rs[0][0], &S.a_cs[nxt][0][0], nA, tid);
-                issue_loads<BMODE, NT, false>(lb, pb, Bbase, &S.b_cs[0][0], &S.b_rs[nxt][0][0], nB, tid);
-            } else {
-                issue_loads<AMODE, NT, true>(la, pa, Abase, &S.a_rs[0][0], &S.a_cs[nxt][0][0], nA, tid);
-                issue_loads<BMODE, NT, true>(lb, pb, Bbase, &S.b_cs[0][0], &S.b_rs[nxt][0][0], nB, tid);
-            }
-        }
-
-        const int toff = cur * TILE;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            double af[4];
-#pragma unroll
-            for (int x = 0; x < 4; ++x) af[x] = fa[toff + kk * PITCH + x * 16];
-#pragma unroll
-            for (int y = 0; y < 2; ++y) {
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    const double bf = fb[s][toff + kk * PITCH + y * 16];
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) acc[x][y][s] = __builtin_amdgcn_mfma_f64_4x4x4f64(af[x], bf, acc[x][y][s], 0, 0, 0);
-                }
-            }
-        }
-        if (more) {
-            stage_sums<AMODE, NT, true>(&S.a[nxt][0], la, pa, P.A.coef, tid);
-            stage_sums<BMODE, NT, true>(&S.b[nxt][0], lb, pb, P.B.coef, tid);
-        }
-        if (ent_dst && step + 2 < nk) ent_dst[cur * NT * KT] = next_entry;
-        __syncthreads();
+    for (int step = 0; step < st.nk; step += 2) {
+        st.template step_body<0>(step);
+        if (step + 1 < st.nk) st.template step_body<1>(step + 1);
     }
 
     // ---- epilogue: add alpha * tile to every destination block of C (Sec. 4.2) ----
@@ -260,10 +364,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         const int d = e / TM, x = e % TM;
         const int64_t gi = i0 + x, gj = j0 + x;
         int64_t val = kSentinel;
-        if (d < nC && gi < P.mb && P.C.roff[d] + gi < P.C.rs_len) val = P.C.rs[P.C.roff[d] + gi];
+        if (d < nC && gi < P.mb && P.C.roff[d] + gi < P.C.rs_len) val = as_global(P.C.rs)[P.C.roff[d] + gi];
         c_rs[d][x] = val;
         val = kSentinel;
-        if (d < nC && gj < P.nb && P.C.coff[d] + gj < P.C.cs_len) val = P.C.cs[P.C.coff[d] + gj];
+        if (d < nC && gj < P.nb && P.C.coff[d] + gj < P.C.cs_len) val = as_global(P.C.cs)[P.C.coff[d] + gj];
         c_cs[d][x] = val;
     }
     __syncthreads();
@@ -286,7 +390,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
                 for (int x = 0; x < 4; ++x) {
                     const int64_t off = rsv[x] + csv;
                     if (off >= 0) {
-                        const double v = g * (alpha * acc[x][y][s]);
+                        const double v = g * (alpha * st.acc[x][y][s]);
                         Cbase[off] = (f == 0.0) ? v : __builtin_fma(f, Cbase[off], v);
                     }
                 }
