@@ -26,17 +26,24 @@ namespace {
 
 constexpr int TM = 128;      // tile rows (free bundle I)
 constexpr int TN = 128;      // tile columns (free bundle J)
-constexpr int KT = 16;       // contracted entries per pipeline step
 constexpr int NTHREADS = 512;  // 8 waves: 2 along the rows x 4 along the columns, each owning 64 x 32 outputs
-constexpr int NE = TM * KT / NTHREADS;  // elements of each operand tile a thread gathers per k-step (4)
 constexpr int GROUP_M = 8;   // tile rows per rasterisation group
 
-// LDS tile layout: element (k, x) of a KT x 128 tile lives at k * PITCH + x.  Matrix-core instruction q of a k-step
-// takes k = 4 * (lane / 16) + q, so one fragment load touches rows k and k + 4 in each half-wave; with PITCH = 132
-// those rows start 16 bank-pairs apart and the load is conflict-free, every fragment address is one per-lane base
-// plus a compile-time offset, and the transposing store (16 lanes with consecutive k) sees 2-way conflicts at worst.
+// Contracted entries per pipeline step.  A gathered element needs more than 16 entries' worth of matrix-core
+// work to arrive, so the step is made as deep as the registers allow: 32 for one or two terms per operand.
+template <int NT>
+struct Cfg {
+    static constexpr int KT = (NT <= 2) ? 32 : 16;
+    static constexpr int NE = TM * KT / NTHREADS;  // elements of each operand tile a thread gathers per k-step
+    static constexpr int NQ = KT / 4;              // matrix-core instruction groups ("quarters") per k-step
+};
+
+// LDS tile layout: element (k, x) of a KT x 128 tile lives at k * PITCH + x.  Instruction group q of a k-step
+// takes k = 16 * (q / 4) + 4 * (lane / 16) + q % 4, so one fragment load touches rows k and k + 4 in each half-wave;
+// with PITCH = 132 those rows start 16 bank-pairs apart and the load is conflict-free, every fragment address is one
+// per-lane base plus a compile-time offset, and the transposing store (lanes with consecutive k) sees 2-way
+// conflicts at worst.
 constexpr int PITCH = 132;
-constexpr int TILE = KT * PITCH;
 
 __device__ __forceinline__ const double* pick_src(int space, const double* user, const double* W, int64_t off) {
     return (space == 0 ? user : W) + off;
@@ -47,6 +54,7 @@ __device__ __forceinline__ const double* pick_src(int space, const double* user,
 // next LDS access).
 typedef const __attribute__((address_space(1))) int64_t* gvec_t;
 __device__ __forceinline__ gvec_t as_global(const int64_t* p) { return (gvec_t)p; }
+typedef const __attribute__((address_space(1))) double* gdbl_t;
 
 // Non-matrix VALU instructions do not overlap with v_mfma_f64_4x4x4 on this chip (measured: every integer or
 // fp64 VALU instruction adds its full issue time), so the main loop is written to need as few of them as possible:
@@ -55,27 +63,28 @@ __device__ __forceinline__ gvec_t as_global(const int64_t* p) { return (gvec_t)p
 // operand with a single +1 term is stored as loaded.
 template <int NT>
 struct FusedSmem {
+    static constexpr int KT = Cfg<NT>::KT;
+    static constexpr int TILE = KT * PITCH;
     double a[2][TILE];
     double b[2][TILE];
     int64_t a_fix[NT][TM];      // per term: address of row x of the A blocks (base + 8 * rscat), kSentinel where padded
     int64_t b_fix[NT][TN];      // per term: address of column x of the B blocks (base + 8 * cscat)
-    int64_t a_step[2][NT][KT];  // per term: 8 * cscat_A of the 16 contracted entries of a k-step (two steps in flight)
+    int64_t a_step[2][NT][KT];  // per term: 8 * cscat_A of the contracted entries of a k-step (two steps in flight)
     int64_t b_step[2][NT][KT];  // per term: 8 * rscat_B
     int64_t dump[2][NT][KT];    // where threads that own no table entry store theirs (keeps that store branch-free)
 };
 
-typedef const __attribute__((address_space(1))) double* gdbl_t;
-
-// Each thread gathers NE = 4 elements of the A tile and 4 of the B tile per k-step, for every term.
+// Each thread gathers NE elements of the A tile and NE of the B tile per k-step, for every term.
 //   MODE 0: lanes run along the 128 free entries (x); element e of a thread is (x = tid % 128, k = tid / 128 + 4e)
-//   MODE 1: lanes run along the 16 contracted entries (k); element e is (k = tid % 16, x = tid / 16 + 32e)
-// The loads of a k-step are issued before the matrix-core work on the previous one and, after it, summed with
+//   MODE 1: lanes run along the contracted entries (k); element e is (k = tid % KT, x = tid / KT + (512 / KT) e)
+// The loads of a k-step are issued during the matrix-core work on the previous one and, after it, summed with
 // their signs (the operand sum of Sec. 4.1) and stored into the other LDS buffer.
 // CHECKED: entries of the zero padding (negative table sum) read the operand's element 0 and count as zero.
 template <int MODE, int NT, bool CHECKED>
-__device__ __forceinline__ void issue_loads(double (&ld)[NT][NE], unsigned& padmask, const double* __restrict__ safe,
+__device__ __forceinline__ void issue_loads(double (&ld)[NT][Cfg<NT>::NE], unsigned& padmask, const double* __restrict__ safe,
                                             const int64_t* __restrict__ fixed_tab /* [NT][128] */,
                                             const int64_t* __restrict__ step_tab /* [NT][KT] */, int nterms, int tid) {
+    constexpr int KT = Cfg<NT>::KT, NE = Cfg<NT>::NE;
     padmask = 0;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
@@ -89,7 +98,7 @@ __device__ __forceinline__ void issue_loads(double (&ld)[NT][NE], unsigned& padm
                 if (MODE == 0)
                     addr = fixed_tab[t * 128 + (tid & 127)] + step_tab[t * KT + (tid >> 7) + 4 * e];
                 else
-                    addr = step_tab[t * KT + (tid & 15)] + fixed_tab[t * 128 + (tid >> 4) + 32 * e];
+                    addr = step_tab[t * KT + (tid % KT)] + fixed_tab[t * 128 + (tid / KT) + (NTHREADS / KT) * e];
                 if (CHECKED) {
                     padmask |= (addr < 0 ? 1u : 0u) << (t * NE + e);
                     ld[t][e] = *(gdbl_t)(addr < 0 ? (int64_t)safe : addr);
@@ -102,8 +111,9 @@ __device__ __forceinline__ void issue_loads(double (&ld)[NT][NE], unsigned& padm
 }
 
 template <int MODE, int NT, bool CHECKED>
-__device__ __forceinline__ void stage_sums(double* __restrict__ dst, const double (&ld)[NT][NE], unsigned padmask,
+__device__ __forceinline__ void stage_sums(double* __restrict__ dst, const double (&ld)[NT][Cfg<NT>::NE], unsigned padmask,
                                            const double* __restrict__ coef, bool plain) {
+    constexpr int KT = Cfg<NT>::KT, NE = Cfg<NT>::NE;
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
         double v;
@@ -117,7 +127,7 @@ __device__ __forceinline__ void stage_sums(double* __restrict__ dst, const doubl
                 v = (t == 0) ? coef[0] * x : __builtin_fma(coef[t], x, v);
             }
         }
-        dst[(MODE == 0) ? 4 * e * PITCH : 32 * e] = v;
+        dst[(MODE == 0) ? 4 * e * PITCH : (NTHREADS / KT) * e] = v;
     }
 }
 
@@ -125,15 +135,13 @@ __device__ __forceinline__ int64_t min64(int64_t a, int64_t b) { return a < b ? 
 
 template <int AMODE, int BMODE, int NT>
 struct FusedState {
-    // How many k-steps ahead of the multiplication the gather runs.  Loads take longer than one k-step of
-    // matrix-core work to arrive, so with registers to spare (NT <= 2) two k-steps are kept in flight.
-    static constexpr int D = (NT <= 2) ? 2 : 1;
+    static constexpr int KT = Cfg<NT>::KT, NE = Cfg<NT>::NE, NQ = Cfg<NT>::NQ, TILE = KT * PITCH;
     FusedSmem<NT>* S;
     const Product* P;
     int tid, nA, nB, nk, kfull;
     bool plainA, plainB;       // single term with coefficient +1: staged as loaded
-    bool early;                // this wave issues its gather before the first quarter of matrix-core work, its
-                               // partner on the same SIMD after the second: one of the two always has MFMAs to issue
+    bool early;                // this wave issues its gather before the matrix-core work of a k-step, its partner on
+                               // the same SIMD a quarter of the way in: one of the two always has MFMAs to issue
     const double *safeA, *safeB;
     // scatter entries of later k-steps
     gvec_t ent_ptr;
@@ -145,46 +153,46 @@ struct FusedState {
     double* sa;                // where this thread stages its A elements (buffer 0)
     double* sb;
     double acc[4][2][4];
-    double la[D][NT][NE], lb[D][NT][NE];
-    unsigned pa[D], pb[D];
-    bool setfast[D];           // the loads held in that register set were issued without padding checks
+    double la[NT][NE], lb[NT][NE];
+    unsigned pa, pb;
+    bool issued_fast;          // the loads in flight were issued without padding checks
 
-    // gather of k-step `target` into register set SET (table slot = target % 2 = SLOT)
-    template <int SET, int SLOT>
+    // gather of k-step `target` (table slot SLOT = target % 2)
+    template <int SLOT>
     __device__ __forceinline__ void issue(int target) {
         if (target < nk) {
-            const bool fast = target < kfull;  // no padding anywhere in that k-step
-            setfast[SET] = fast;
-            if (fast) {
-                issue_loads<AMODE, NT, false>(la[SET], pa[SET], safeA, &S->a_fix[0][0], &S->a_step[SLOT][0][0], nA, tid);
-                issue_loads<BMODE, NT, false>(lb[SET], pb[SET], safeB, &S->b_fix[0][0], &S->b_step[SLOT][0][0], nB, tid);
+            issued_fast = target < kfull;  // no padding anywhere in that k-step
+            if (issued_fast) {
+                issue_loads<AMODE, NT, false>(la, pa, safeA, &S->a_fix[0][0], &S->a_step[SLOT][0][0], nA, tid);
+                issue_loads<BMODE, NT, false>(lb, pb, safeB, &S->b_fix[0][0], &S->b_step[SLOT][0][0], nB, tid);
             } else {
-                issue_loads<AMODE, NT, true>(la[SET], pa[SET], safeA, &S->a_fix[0][0], &S->a_step[SLOT][0][0], nA, tid);
-                issue_loads<BMODE, NT, true>(lb[SET], pb[SET], safeB, &S->b_fix[0][0], &S->b_step[SLOT][0][0], nB, tid);
+                issue_loads<AMODE, NT, true>(la, pa, safeA, &S->a_fix[0][0], &S->a_step[SLOT][0][0], nA, tid);
+                issue_loads<BMODE, NT, true>(lb, pb, safeB, &S->b_fix[0][0], &S->b_step[SLOT][0][0], nB, tid);
             }
         }
     }
 
-    // operand sums of register set SET into LDS buffer BUF
-    template <int SET, int BUF>
+    // operand sums of the loads in flight into LDS buffer BUF
+    template <int BUF>
     __device__ __forceinline__ void stage() {
-        if (setfast[SET]) {
-            stage_sums<AMODE, NT, false>(sa + BUF * TILE, la[SET], 0, P->A.coef, plainA);
-            stage_sums<BMODE, NT, false>(sb + BUF * TILE, lb[SET], 0, P->B.coef, plainB);
+        if (issued_fast) {
+            stage_sums<AMODE, NT, false>(sa + BUF * TILE, la, 0, P->A.coef, plainA);
+            stage_sums<BMODE, NT, false>(sb + BUF * TILE, lb, 0, P->B.coef, plainB);
         } else {
-            stage_sums<AMODE, NT, true>(sa + BUF * TILE, la[SET], pa[SET], P->A.coef, false);
-            stage_sums<BMODE, NT, true>(sb + BUF * TILE, lb[SET], pb[SET], P->B.coef, false);
+            stage_sums<AMODE, NT, true>(sa + BUF * TILE, la, pa, P->A.coef, false);
+            stage_sums<BMODE, NT, true>(sb + BUF * TILE, lb, pb, P->B.coef, false);
         }
     }
 
     template <int CUR, int Q>
     __device__ __forceinline__ void read_frags(double (&af)[4], double (&bf)[8]) {
+        constexpr int ROW = 16 * (Q / 4) + (Q % 4);
 #pragma unroll
-        for (int x = 0; x < 4; ++x) af[x] = fa[CUR * TILE + Q * PITCH + x * 16];
+        for (int x = 0; x < 4; ++x) af[x] = fa[CUR * TILE + ROW * PITCH + x * 16];
 #pragma unroll
         for (int y = 0; y < 2; ++y)
 #pragma unroll
-            for (int s = 0; s < 4; ++s) bf[y * 4 + s] = fb[s][CUR * TILE + Q * PITCH + y * 16];
+            for (int s = 0; s < 4; ++s) bf[y * 4 + s] = fb[s][CUR * TILE + ROW * PITCH + y * 16];
     }
 
     __device__ __forceinline__ void multiply(const double (&af)[4], const double (&bf)[8]) {
@@ -197,33 +205,36 @@ struct FusedState {
                     acc[x][y][s] = __builtin_amdgcn_mfma_f64_4x4x4f64(af[x], bf[y * 4 + s], acc[x][y][s], 0, 0, 0);
     }
 
-    // One k-step: gather k-step step + D, multiply the tiles of this step (LDS buffer CUR), stage k-step step + 1.
+    // instruction groups Q .. NQ-1 of the k-step in LDS buffer CUR; the fragments of group Q are in af/bf[Q % 2] and
+    // those of group Q + 1 are read while group Q multiplies
+    template <int CUR, int Q, int SLOT>
+    __device__ __forceinline__ void groups(double (&af)[2][4], double (&bf)[2][8], int step) {
+        if constexpr (Q < NQ) {
+            if constexpr (Q + 1 < NQ) read_frags<CUR, Q + 1>(af[(Q + 1) & 1], bf[(Q + 1) & 1]);
+            multiply(af[Q & 1], bf[Q & 1]);
+            if constexpr (Q + 1 == NQ / 4) {
+                if (!early) issue<SLOT>(step + 1);
+            }
+            groups<CUR, Q + 1, SLOT>(af, bf, step);
+        }
+    }
+
+    // One k-step: gather k-step step + 1, multiply the tiles of this step (LDS buffer CUR), stage k-step step + 1.
     template <int CUR>
     __device__ __forceinline__ void step_body(int step) {
         constexpr int NXT = CUR ^ 1;
-        constexpr int ISET = (D == 2) ? CUR : 0;   // register set the gather of this step lands in
-        constexpr int SSET = (D == 2) ? NXT : 0;   // register set staged at the end of this step (k-step step + 1)
-        constexpr int SLOT = (D == 2) ? CUR : NXT;  // table slot holding the entries of k-step step + D
-        if (early) issue<ISET, SLOT>(step + D);
-        // table entry of k-step step + D + 1; unconditional load: ent_ptr always points at readable memory
-        const int kn = (step + D + 1) * KT;
+        if (early) issue<NXT>(step + 1);
+        // table entry of k-step step + 2; unconditional load: ent_ptr always points at readable memory
+        const int kn = (step + 2) * KT;
         const bool have = kn < ent_limit;
         const int64_t raw_entry = ent_ptr[have ? kn : 0];
 
-        // matrix-core work; the fragments of quarter q + 1 are read from LDS while quarter q multiplies
         double af[2][4], bf[2][8];
         read_frags<CUR, 0>(af[0], bf[0]);
-        read_frags<CUR, 1>(af[1], bf[1]);
-        multiply(af[0], bf[0]);
-        read_frags<CUR, 2>(af[0], bf[0]);
-        multiply(af[1], bf[1]);
-        if (!early) issue<ISET, SLOT>(step + D);
-        read_frags<CUR, 3>(af[1], bf[1]);
-        multiply(af[0], bf[0]);
-        multiply(af[1], bf[1]);
+        groups<CUR, 0, NXT>(af, bf, step);
 
-        if (step + 1 < nk) stage<SSET, NXT>();
-        ent_dst[(SLOT ^ 1) * NT * KT] = have ? raw_entry * 8 : kSentinel;  // every thread stores: no branch around the wait
+        if (step + 1 < nk) stage<NXT>();
+        ent_dst[CUR * NT * KT] = have ? raw_entry * 8 : kSentinel;  // every thread stores: no branch around the wait
         __syncthreads();
     }
 };
@@ -236,7 +247,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     FusedSmem<NT>& S = *reinterpret_cast<FusedSmem<NT>*>(smem_raw);
     const int tid = threadIdx.x;
     typedef FusedState<AMODE, BMODE, NT> State;
-    constexpr int D = State::D;
+    constexpr int KT = State::KT;
 
     // ---- which tile: spread consecutive logical ids over one XCD (block b runs on XCD b % 8), then walk
     //      GROUP_M tile rows at a time so that co-resident workgroups share A and B panels in that XCD's L2 ----
@@ -269,8 +280,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     const double* Bbase = pick_src(P.B.space, Bu, W, P.B.base_off);
     st.safeA = Abase;
     st.safeB = Bbase;
-#pragma unroll
-    for (int d = 0; d < D; ++d) st.pa[d] = st.pb[d] = 0, st.setfast[d] = false;
+    st.pa = st.pb = 0;
+    st.issued_fast = false;
 
     // ---- tile-fixed gather tables; how much of the tile and of the k range is free of zero padding ----
     int64_t klimit = P.kb;       // k entries that are real in every term of both operands
@@ -298,14 +309,14 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         if (t < nB && gj < P.nb && P.B.coff[t] + gj < P.B.cs_len) val = (int64_t)Bbase + 8 * as_global(P.B.cs)[P.B.coff[t] + gj];
         S.b_fix[t][x] = val;
     }
-    // Threads 0..16*NT-1 fetch the column scatter entries of A for a k-step (one per term and k), threads
-    // 128..128+16*NT-1 the row scatter entries of B, ahead of the gather that uses them.
+    // Threads 0..KT*NT-1 fetch the column scatter entries of A for a k-step (one per term and k), threads
+    // 256..256+KT*NT-1 the row scatter entries of B, two k-steps ahead of the tile that uses them.
     st.ent_ptr = as_global(reinterpret_cast<const int64_t*>(&P));  // dummy target for threads without an entry
     st.ent_limit = 0;
     st.ent_dst = &S.dump[0][0][0];
-    if (tid < 256) {
-        const bool isB = tid >= 128;
-        const int q = tid & 127, t = q >> 4, kl = q & 15;
+    {
+        const bool isB = tid >= 256;
+        const int q = tid & 255, t = q / KT, kl = q % KT;
         if (t < NT) {
             const Operand& op = isB ? P.B : P.A;
             st.ent_dst = isB ? &S.b_step[0][t][kl] : &S.a_step[0][t][kl];
@@ -316,11 +327,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
             }
         }
     }
-    auto write_entry = [&](int kstep, int slot) {
-        st.ent_dst[slot * NT * KT] = (kstep * KT < st.ent_limit) ? 8 * st.ent_ptr[kstep * KT] : kSentinel;
-    };
-    write_entry(0, 0);
-    write_entry(1, 1);
+    st.ent_dst[0] = (0 < st.ent_limit) ? 8 * st.ent_ptr[0] : kSentinel;
+    st.ent_dst[NT * KT] = (KT < st.ent_limit) ? 8 * st.ent_ptr[KT] : kSentinel;
     __syncthreads();
 
     const int lane = tid & 63, wave = tid >> 6;
@@ -331,17 +339,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     st.fa = &S.a[0][0] + 4 * lk * PITCH + wm * 64 + l16;
 #pragma unroll
     for (int s = 0; s < 4; ++s) st.fb[s] = &S.b[0][0] + 4 * lk * PITCH + wn * 32 + ((l16 + 4 * s) & 15);
-    st.sa = &S.a[0][0] + ((AMODE == 0) ? (tid >> 7) * PITCH + (tid & 127) : (tid & 15) * PITCH + (tid >> 4));
-    st.sb = &S.b[0][0] + ((BMODE == 0) ? (tid >> 7) * PITCH + (tid & 127) : (tid & 15) * PITCH + (tid >> 4));
+    st.sa = &S.a[0][0] + ((AMODE == 0) ? (tid >> 7) * PITCH + (tid & 127) : (tid % KT) * PITCH + (tid / KT));
+    st.sb = &S.b[0][0] + ((BMODE == 0) ? (tid >> 7) * PITCH + (tid & 127) : (tid % KT) * PITCH + (tid / KT));
 
-    // ---- prologue: k-step 0 into LDS buffer 0; with D = 2 the gather of k-step 1 is left in flight ----
-    st.template issue<0, 0>(0);
-    st.template stage<0, 0>();
-    if (D == 2) {
-        st.template issue<1, 1>(1);
-        __syncthreads();  // every thread has read the entries of k-step 0
-        write_entry(2, 0);
-    }
+    // ---- prologue: k-step 0 into LDS buffer 0 ----
+    st.template issue<0>(0);
+    st.template stage<0>();
 #pragma unroll
     for (int x = 0; x < 4; ++x)
 #pragma unroll
@@ -494,6 +497,7 @@ int launch_fused_t(const Product* prods, int first, int count, int tiles_m, int 
                    double* W, double alpha, double beta, hipStream_t stream) {
     static bool configured = false;
     const size_t smem = sizeof(FusedSmem<NT>);
+    static_assert(sizeof(FusedSmem<NT>) <= 160 * 1024, "LDS budget of one CU");
     auto kern = fused_kernel<AMODE, BMODE, NT>;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
