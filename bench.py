@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of libstrassen_tc on one MI355X.
+
+Workload: the square fp64 GEMM-shaped contraction C[i,j] += A[i,k] * B[k,j] with m = n = k = 16384 (the largest
+single-GPU case of the second benchmark configuration), seeded uniform[-1,1) data, generalized column-major.
+A step is one pass of the whole hot path on inputs resident in HBM: tc_plan (bundle classification, scatter and
+block scatter vectors, Strassen schedule), tc_contract (gather + operand sums, FP64 matrix-core tiles,
+multi-destination update) and tc_destroy, for the headline mode (one-level ABC Strassen).  The other modes
+(classical, AB, Naive, two-level) are timed the same way and listed under config.modes.
+
+Prints ONE JSON line: effective GFLOPS = 2 m n k / t (classical flop count for every mode), the roofline figure of
+the dominant kernel, and the CPU oracle timed on a bounded row panel of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP64_MFMA_PEAK_TFLOPS = 78.6  # MI355X published dense FP64 matrix peak
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--size", type=int, default=16384, help="m = n = k of the square contraction")
+    ap.add_argument("--level", type=int, default=1)
+    ap.add_argument("--variant", default="abc")
+    ap.add_argument("--modes", default="0abc,1abc,1ab,1naive,2abc,2ab,2naive", help="other modes to time (level+variant)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import paper_1704_03092_amd as tc
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    tc.load_library()  # no fallback: fails if the HIP library is missing
+    torch.cuda.set_device(0)
+    N = args.size
+    cfg = workloads.gemm(N)
+    m, n, k = cfg.mnk()
+    flops = 2.0 * m * n * k
+    A, B, C = cfg.tensors()
+    dA = torch.from_numpy(A.data).to("cuda")
+    dB = torch.from_numpy(B.data).to("cuda")
+    dC0 = torch.from_numpy(C.data).to("cuda")
+    dC = dC0.clone()
+    st = torch.cuda.current_stream()
+    ws_cache = {}
+
+    def workspace(nbytes):
+        if nbytes == 0:
+            return None
+        if nbytes not in ws_cache:
+            ws_cache.clear()
+            ws_cache[nbytes] = torch.empty(nbytes // 8, dtype=torch.float64, device="cuda")
+        return ws_cache[nbytes]
+
+    def one_step(level, variant, alpha=cfg.alpha, beta=cfg.beta):
+        plan = tc.tc_plan(A, B, C, level, variant, st)
+        ws = workspace(tc.tc_plan_workspace_bytes(plan))
+        tc.tc_contract(plan, alpha, dA, dB, beta, dC, ws, st)
+        info = tc.tc_plan_info(plan)
+        tc.tc_destroy(plan)
+        return info
+
+    def time_mode(level, variant, steps, warmup):
+        """(wall ms per step incl. plan, event ms per tc_contract, plan info)"""
+        dC.copy_(dC0)
+        for _ in range(warmup):
+            info = one_step(level, variant)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            info = one_step(level, variant)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        # kernel time alone: HIP events on the launch stream around tc_contract of a prepared plan
+        plan = tc.tc_plan(A, B, C, level, variant, st)
+        ws = workspace(tc.tc_plan_workspace_bytes(plan))
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for e0, e1 in evs:
+            e0.record(st)
+            tc.tc_contract(plan, cfg.alpha, dA, dB, cfg.beta, dC, ws, st)
+            e1.record(st)
+        torch.cuda.synchronize()
+        tc.tc_destroy(plan)
+        ev_ms = sum(e0.elapsed_time(e1) for e0, e1 in evs) / steps
+        return wall_ms, ev_ms, info
+
+    # ---- headline mode ----
+    wall_ms, ev_ms, info = time_mode(args.level, args.variant, args.steps, args.warmup)
+    value = flops / (wall_ms * 1e-3) * 1e-9
+
+    # ---- parity of the timed configuration on sampled rows (the oracle computes them one by one) ----
+    import oracle
+
+    rng = np.random.default_rng(7)
+    g = 1 << info["level"]
+    rows = sorted(set([0, m - 1] + [b * info["mb"] + d for b in range(g) for d in (-1, 0, 1) if 0 <= b * info["mb"] + d < m]
+                      + list(rng.integers(0, m, size=24))))
+    rows = np.array(rows, dtype=np.int64)
+    dC.copy_(dC0)
+    one_step(args.level, args.variant)
+    torch.cuda.synchronize()
+    got = dC.view(n, m).t()[torch.from_numpy(rows).to("cuda")].cpu().numpy()  # column-major storage: element (i, j) at i + j * m
+    ref = oracle.contract_rows(A, B, C, rows, cfg.alpha, cfg.beta, orders=(["i"], ["j"], ["k"]))
+    normA_rows = oracle.fro(A.view()[rows, :])
+    parity = oracle.error_metric(got, ref, normA_rows, oracle.fro(B.data))
+
+    # ---- roofline of the dominant kernel (fused gather + MFMA + update): executed flops / launch duration ----
+    # (ABC and level 0 launch only that kernel; for AB / Naive the event time also contains the element-wise passes)
+    nlaunch_fused = info["n_launches"] if (args.variant == "abc" or info["level"] == 0) else info["n_products"]
+    executed = flops * (7.0 / 8.0) ** info["level"]
+    achieved = executed / (ev_ms * 1e-3) * 1e-12
+    roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / FP64_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                "kernel": "fused_kernel", "launches_per_contract": nlaunch_fused,
+                "flops_per_launch": executed / nlaunch_fused, "avg_launch_ms": round(ev_ms / nlaunch_fused, 4)}
+
+    # ---- the other modes ----
+    modes = {}
+    for md in [x for x in args.modes.split(",") if x]:
+        lv, var = int(md[0]), md[1:]
+        w, e, inf = time_mode(lv, var, max(2, args.steps // 2 + 1), 1)
+        modes[md] = {"ms_per_step": round(w, 3), "contract_ms": round(e, 3), "eff_gflops": round(flops / w * 1e-6, 1),
+                     "frac_peak_eff": round(flops / w * 1e-9 / FP64_MFMA_PEAK_TFLOPS, 4), "launches": inf["n_launches"]}
+
+    # ---- CPU oracle on a bounded row panel of the same workload ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        t0 = time.perf_counter()
+        oracle.contract_rows(A, B, C, np.arange(256, dtype=np.int64), cfg.alpha, cfg.beta)
+        probe = time.perf_counter() - t0
+        nrows = int(min(m, 8192, max(256, 256 * 12.0 / max(probe, 1e-3))))  # about 12 s of CPU work
+        nrows -= nrows % 32
+        t0 = time.perf_counter()
+        oracle.contract_rows(A, B, C, np.arange(nrows, dtype=np.int64), cfg.alpha, cfg.beta)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(2.0 * nrows * n * k / dt * 1e-9, 2), "unit": "GFLOPS", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"rows 0..{nrows - 1} of the {m}x{n}x{k} contraction (all n and k), tiled classical loop nest, {dt:.1f} s"}
+
+    out = {
+        "metric": "effective fp64 GFLOPS (2mnk/t)", "value": round(value, 1), "unit": "GFLOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(wall_ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"cfg2 square contraction ij-ik-kj, m=n=k={N}, uniform[-1,1), alpha=1 beta=1, column-major",
+                   "level": info["level"], "variant": args.variant, "step": "tc_plan + tc_contract + tc_destroy",
+                   "contract_ms": round(ev_ms, 3), "frac_fp64_mfma_peak_effective": round(value * 1e-3 / FP64_MFMA_PEAK_TFLOPS, 4),
+                   "parity_sampled_rows": float(f"{parity:.3e}"), "parity_rows": int(len(rows)), "modes": modes},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -76,8 +76,15 @@ def _load():
         lib.orc_matvec.argtypes = [vp, vp, vp, i64, i64, vp, vp]
         lib.orc_matvec_t.restype = ci
         lib.orc_matvec_t.argtypes = [vp, vp, vp, i64, i64, vp, vp]
+        lib.orc_num_threads.restype = ci
+        lib.orc_num_threads.argtypes = []
         _lib = lib
     return _lib
+
+
+def num_threads() -> int:
+    """Threads the tiled oracle runs on."""
+    return int(_load().orc_num_threads())
 
 
 def _i64(a) -> np.ndarray:

@@ -22,6 +22,7 @@
  * Pins: tests/test_oracle_*.py (numpy einsum / matmul, brute force, the paper's
  * worked layout example, invariants).
  */
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -29,6 +30,9 @@
 enum { ORC_OK = 0, ORC_ERR_LABEL = -1, ORC_ERR_LENGTH = -2, ORC_ERR_NDIM = -3, ORC_ERR_ALLOC = -4 };
 
 #define ORC_MAXD 32
+
+/* threads the OpenMP loops below will use */
+int orc_num_threads(void) { return omp_get_max_threads(); }
 
 static int find_label(const char *idx, int nd, char c)
 {
