@@ -255,16 +255,23 @@ int orc_contract_rows(const double *A, const double *B, const double *C0,
     return err ? ORC_ERR_ALLOC : ORC_OK;
 }
 
-/* y[i] = sum_j T[rs[i] + cs[j]] * x[j] */
+/* y[i] = sum_j T[rs[i] + cs[j]] * x[j]   (each y[i] is one running sum over j = 0..n-1 in order; rows are
+ * processed in chunks so that the inner loop runs along the rows, which is the contiguous direction of the
+ * column-major layouts used here) */
 int orc_matvec(const double *T, const int64_t *rs, const int64_t *cs, int64_t m, int64_t n, const double *x, double *y)
 {
-#pragma omp parallel for schedule(static)
-    for (int64_t i = 0; i < m; ++i) {
-        double s = 0.0;
-        const double *row = T + rs[i];
-        for (int64_t j = 0; j < n; ++j)
-            s += row[cs[j]] * x[j];
-        y[i] = s;
+    const int64_t CH = 512;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t i0 = 0; i0 < m; i0 += CH) {
+        int64_t i1 = i0 + CH < m ? i0 + CH : m;
+        for (int64_t i = i0; i < i1; ++i)
+            y[i] = 0.0;
+        for (int64_t j = 0; j < n; ++j) {
+            const double *col = T + cs[j];
+            const double xj = x[j];
+            for (int64_t i = i0; i < i1; ++i)
+                y[i] += col[rs[i]] * xj;
+        }
     }
     return ORC_OK;
 }

@@ -28,16 +28,34 @@ def lib_path() -> str:
 
 
 def build(verbose: bool = False) -> str:
-    """Compile the HIP library for gfx950 with hipcc (cross-compiles without a GPU)."""
-    src = [os.path.join(_HERE, "csrc", f) for f in ("tc_host.cpp", "tc_device.hip")]
+    """Compile the HIP library for gfx950 with hipcc (cross-compiles without a GPU); translation units in parallel."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    names = ["tc_host.cpp", "tc_device.hip", "tc_fused_nt1.hip", "tc_fused_nt2.hip", "tc_fused_nt4.hip"]
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I" + os.path.join(_ROOT, "include"), "-o", _LIB] + src
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+    objdir = os.path.join(_HERE, "csrc", "_build")
+    os.makedirs(objdir, exist_ok=True)
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+
+    def compile_one(name):
+        obj = os.path.join(objdir, name + ".o")
+        cmd = [hipcc] + flags + ["-I" + os.path.join(_ROOT, "include"), "-c", "-o", obj, os.path.join(_HERE, "csrc", name)]
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+        if res.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {name}:\n" + out)
+        return obj, out
+
+    with ThreadPoolExecutor(max_workers=min(len(names), int(os.environ.get("MAX_JOBS", "8")))) as ex:
+        results = list(ex.map(compile_one, names))
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", _LIB] + [o for o, _ in results]
+    res = subprocess.run(link, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out)
+        raise RuntimeError("hipcc link failed:\n" + res.stdout)
+    if verbose:
+        for _, out in results:
+            if out.strip():
+                print(out)
     global _lib
     _lib = None
     return _LIB

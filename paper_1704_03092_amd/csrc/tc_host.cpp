@@ -51,6 +51,7 @@ struct tc_plan {
     int level_requested = 0, level = 0, variant = TC_VARIANT_ABC, bs_block = 16;
     bool host_only = false;
     int a_mode = 0, b_mode = 0, c_mode = 0;
+    int a_vec = 0, b_vec = 0;
     int64_t mb = 0, nb = 0, kb = 0;
     std::vector<Dim> I, J, P;
     std::vector<tc_product_t> sched;  // block-level view of the products, for inspection
@@ -112,6 +113,27 @@ int64_t min_stride(const std::vector<Dim>& bundle, int which) {
         best = std::min(best, s);
     }
     return best;
+}
+
+// Pairs (2q, 2q+1) of consecutive entries of `lane` (the bundle the gather lanes run along) are contiguous in
+// memory, and every pair starts at an even element offset, iff the bundle's fastest dimension has stride 1 and
+// even length and every other stride of the tensor (rest of that bundle and the whole other bundle) is even.
+bool pairs_contiguous(const std::vector<Dim>& lane, const std::vector<Dim>& other, int which) {
+    auto stride = [which](const Dim& d) { return which == 0 ? d.sA : which == 1 ? d.sB : d.sC; };
+    bool first = true;
+    for (const Dim& d : lane) {
+        if (d.len <= 1) continue;
+        if (first) {
+            if (stride(d) != 1 || d.len % 2 != 0) return false;
+            first = false;
+        } else if (stride(d) % 2 != 0) {
+            return false;
+        }
+    }
+    if (first) return false;  // the bundle has a single entry: nothing to pair
+    for (const Dim& d : other)
+        if (d.len > 1 && stride(d) % 2 != 0) return false;
+    return true;
 }
 
 void order_bundle(std::vector<Dim>& bundle, int which) {
@@ -253,6 +275,9 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     order_bundle(p->I, p->a_mode == 0 ? 0 : 2);
     order_bundle(p->J, p->b_mode == 0 ? 1 : 2);
     order_bundle(p->P, p->a_mode == 1 ? 0 : (p->b_mode == 1 ? 1 : 0));
+
+    p->a_vec = p->a_mode == 0 ? pairs_contiguous(p->I, p->P, 0) : pairs_contiguous(p->P, p->I, 0);
+    p->b_vec = p->b_mode == 0 ? pairs_contiguous(p->J, p->P, 1) : pairs_contiguous(p->P, p->J, 1);
 
     // ---- Strassen partition of the matrix view (Sec. 3) ----
     p->level_requested = level;
@@ -403,7 +428,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         }
         // emit in phase order; the first product (in that order) to write a block of C applies beta to it
         const bool fusedC = (variant == TC_VARIANT_ABC || level == 0);
-        const tc::FusedConfig user_cfg_base{p->a_mode, p->b_mode, 1};
+        const tc::FusedConfig user_cfg_base{p->a_mode, p->b_mode, 1, p->a_vec, p->b_vec, 0, 0};
         for (int ph = 0; ph < nphase; ++ph) {
             int first_dev = (int)p->prods.size(), count = 0, cls = 1;
             for (size_t e = 0; e < list.size(); ++e) {
@@ -458,7 +483,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
                         add_term(mul.A, 0, 0, 1.0);
                         set_operand(mul.B, vec(V_RSTB), vec(V_CSTB), p->kb, p->nb, 1, p->wsTB);
                         add_term(mul.B, 0, 0, 1.0);
-                        cfg = tc::FusedConfig{0, 1, 1};
+                        cfg = tc::FusedConfig{0, 1, 1, 1, 1, 1, 1};  // dense temporaries: block extents are multiples of 16
                     } else {
                         cfg.max_terms = terms_class(std::max(q.view.n_a, q.view.n_b));
                     }

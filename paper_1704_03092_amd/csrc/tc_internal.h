@@ -47,6 +47,8 @@ struct BundleDesc {
 struct FusedConfig {
     int a_mode, b_mode;   // 0: lanes run along the free bundle when gathering, 1: along the contracted bundle
     int max_terms;        // 1, 2 or 4: which instantiation to launch
+    int a_vec, b_vec;     // consecutive entry pairs along the lane direction are contiguous and evenly placed
+    int a_space, b_space; // 0: caller's tensor, 1: workspace (for the pointer alignment check)
 };
 
 // ---- device entry points (tc_device.hip); each returns a hipError_t cast to int ----

@@ -1,0 +1,136 @@
+"""GPU parity at the full sizes of the five benchmark configurations, in the launch configuration bench.py times.
+
+Small and medium cases are compared element by element with the full classical oracle.  For the three largest
+(cfg2 at 16384, cfg3, cfg5) the oracle computes sampled rows of the matrix view one by one (rows at every Strassen
+block edge, the first and last row, and random ones; all columns), which is exactly the error metric of the
+sub-contraction on those rows, and a Freivalds estimate covers the whole of C.
+
+Tolerance: ||C - C_ref||_F / (||A||_F ||B||_F) <= 1e-13 (level 0 and 1), 1e-12 (level 2)."""
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL = {0: 1e-13, 1: 1e-13, 2: 1e-12}
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_1704_03092_amd as tc
+
+    tc.load_library()
+    return tc
+
+
+def _modes(cfg):
+    return [(l, v) for (l, v) in cfg.modes]
+
+
+def _run_modes(tc, cfg, sampled):
+    import torch
+
+    t0 = time.time()
+    A, B, C = cfg.tensors()
+    m, n, k = cfg.mnk()
+    print(f"[{cfg.name}] m={m} n={n} k={k} inputs generated in {time.time() - t0:.1f}s", flush=True)
+    dA, dB, dC0 = (torch.from_numpy(T.data).to("cuda") for T in (A, B, C))
+    st = torch.cuda.current_stream()
+    nA, nB = oracle.tensor_norm(A), oracle.tensor_norm(B)
+    view = None
+    ref_rows = {}
+    full_ref = None
+    for level, variant in _modes(cfg):
+        plan = tc.tc_plan(A, B, C, level, variant, st)
+        info = tc.tc_plan_info(plan)
+        orders = (list(info["I"]), list(info["J"]), list(info["P"]))
+        if view is None:
+            view = oracle.matrix_view(A, B, C, orders=orders)
+        nbytes = tc.tc_plan_workspace_bytes(plan)
+        ws = torch.full((max(nbytes // 8, 1),), float("nan"), dtype=torch.float64, device="cuda") if nbytes else None
+        dC = dC0.clone()
+        print(f"[{cfg.name}] level {level} {variant}: launching ({info['n_launches']} launches)", flush=True)
+        tc.tc_contract(plan, cfg.alpha, dA, dB, cfg.beta, dC, ws, st)  # warm-up + result
+        torch.cuda.synchronize()
+        got_flat = dC.cpu().numpy()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        tc.tc_contract(plan, cfg.alpha, dA, dB, cfg.beta, dC, ws, st)
+        e1.record(st)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        tc.tc_destroy(plan)
+        del dC, ws
+        Cg = workloads.Tensor(C.idx, C.lens, C.strides, got_flat)
+        if sampled:
+            g = 1 << info["level"]
+            rng = np.random.default_rng(11)
+            rows = {0, m - 1}
+            for b in range(4):  # edges of the 2x2 and 4x4 partitions
+                for ext in (info["mb"], -(-m // 4 + 15) // 16 * 16):
+                    for d in (-1, 0, 1):
+                        r = b * ext + d
+                        if 0 <= r < m:
+                            rows.add(r)
+            rows |= set(int(x) for x in rng.integers(0, m, size=200))
+            rows = np.array(sorted(rows), dtype=np.int64)
+            key = tuple(rows)
+            if key not in ref_rows:
+                t0 = time.time()
+                ref_rows[key] = oracle.contract_rows(A, B, C, rows, cfg.alpha, cfg.beta, view=view)
+                print(f"[{cfg.name}] oracle: {len(rows)} rows in {time.time() - t0:.1f}s", flush=True)
+            got = got_flat[view["rsC"][rows][:, None] + view["csC"][None, :]]
+            normA_rows = oracle.fro(A.data[view["rsA"][rows][:, None] + view["csA"][None, :]])
+            err = oracle.error_metric(got, ref_rows[key], normA_rows, nB)
+            t0 = time.time()
+            est = oracle.freivalds(Cg, A, B, C, cfg.alpha, cfg.beta, trials=2, seed=level * 10 + len(variant), view=view) / (nA * nB)
+            print(f"[{cfg.name}] level {level} {variant}: {ms:.2f} ms = {cfg.flops() / ms * 1e-9:.1f} TFLOP/s effective; "
+                  f"rows err {err:.2e}; Freivalds estimate of the whole-C metric {est:.2e} ({time.time() - t0:.1f}s)", flush=True)
+            assert est <= TOL[level], (cfg.name, level, variant, est)
+        else:
+            if full_ref is None:
+                t0 = time.time()
+                full_ref = C.copy()
+                oracle.contract_matrix(A, B, full_ref, cfg.alpha, cfg.beta, orders=orders)
+                print(f"[{cfg.name}] full oracle in {time.time() - t0:.1f}s", flush=True)
+            err = oracle.error_metric(Cg.view(), full_ref.view(), nA, nB)
+            print(f"[{cfg.name}] level {level} {variant}: {ms:.3f} ms = {cfg.flops() / ms * 1e-9:.2f} TFLOP/s effective; err {err:.2e}",
+                  flush=True)
+        assert err <= TOL[level], (cfg.name, level, variant, err)
+
+
+def test_cfg1(gpu):
+    _run_modes(gpu, workloads.configs()["cfg1"], sampled=False)
+
+
+@pytest.mark.parametrize("N", [4096, 10001])
+def test_cfg2_full_oracle(gpu, N):
+    _run_modes(gpu, workloads.configs()[f"cfg2_{N}"], sampled=False)
+
+
+@pytest.mark.parametrize("N", [8192, 16384])
+def test_cfg2_sampled(gpu, N):
+    _run_modes(gpu, workloads.configs()[f"cfg2_{N}"], sampled=True)
+
+
+def test_cfg3(gpu):
+    _run_modes(gpu, workloads.configs()["cfg3"], sampled=True)
+
+
+def test_cfg4a(gpu):
+    _run_modes(gpu, workloads.configs()["cfg4a"], sampled=False)
+
+
+def test_cfg4b(gpu):
+    _run_modes(gpu, workloads.configs()["cfg4b"], sampled=False)
+
+
+def test_cfg5(gpu):
+    _run_modes(gpu, workloads.configs()["cfg5"], sampled=True)
