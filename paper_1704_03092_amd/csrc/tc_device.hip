@@ -132,7 +132,7 @@ int launch_planner(const BundleDesc* descs_dev, int nvec, int64_t max_total, int
 namespace fused {
 constexpr int kTile = 128;
 template <int NT>
-int launch_nt(int a_mode, int b_mode, int vec, const Product* prods, int first, int count, int tiles_m, int tiles_n, const double* A,
+int launch_nt(int a_mode, int b_mode, int vec, int c_mode, const Product* prods, int first, int count, int tiles_m, int tiles_n, const double* A,
               const double* B, double* C, double* W, double alpha, double beta, hipStream_t stream);
 }  // namespace fused
 
@@ -148,9 +148,9 @@ int launch_fused(const FusedConfig& cfg, const Product* prods_dev, int first, in
     if (cfg.b_vec && aligned(cfg.b_space == 0 ? (const void*)B : (const void*)W)) vec |= 2;
     const int tm = (int)tiles_m, tn = (int)tiles_n;
     switch (cfg.max_terms) {
-        case 1: return fused::launch_nt<1>(cfg.a_mode, cfg.b_mode, vec, prods_dev, first, count, tm, tn, A, B, C, W, alpha, beta, st);
-        case 2: return fused::launch_nt<2>(cfg.a_mode, cfg.b_mode, vec, prods_dev, first, count, tm, tn, A, B, C, W, alpha, beta, st);
-        case 4: return fused::launch_nt<4>(cfg.a_mode, cfg.b_mode, vec, prods_dev, first, count, tm, tn, A, B, C, W, alpha, beta, st);
+        case 1: return fused::launch_nt<1>(cfg.a_mode, cfg.b_mode, vec, cfg.c_mode, prods_dev, first, count, tm, tn, A, B, C, W, alpha, beta, st);
+        case 2: return fused::launch_nt<2>(cfg.a_mode, cfg.b_mode, vec, cfg.c_mode, prods_dev, first, count, tm, tn, A, B, C, W, alpha, beta, st);
+        case 4: return fused::launch_nt<4>(cfg.a_mode, cfg.b_mode, vec, cfg.c_mode, prods_dev, first, count, tm, tn, A, B, C, W, alpha, beta, st);
         default: return (int)hipErrorInvalidValue;
     }
 }

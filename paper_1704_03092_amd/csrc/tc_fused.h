@@ -44,6 +44,7 @@ struct Cfg {
 // with PITCH = 132 those rows start 16 bank-pairs apart and the load is conflict-free, and every fragment address
 // is one per-lane base plus a compile-time offset.
 constexpr int PITCH = 132;
+constexpr int OPITCH = 130;  // row pitch of the output tile staged in LDS by the epilogue
 
 // Scatter vectors are reached through pointers stored in the product descriptors; telling the compiler that they
 // point to global memory keeps their loads off the flat path (a pending flat load forces a full wait before the
@@ -309,7 +310,7 @@ struct State {
 template <int AMODE, int BMODE, int NT, bool VA, bool VB>
 __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __restrict__ prods, int first, int tiles_m, int tiles_n,
                                                             const double* __restrict__ Au, const double* __restrict__ Bu,
-                                                            double* __restrict__ Cu, double* __restrict__ W, double alpha, double beta) {
+                                                            double* __restrict__ Cu, double* __restrict__ W, double alpha, double beta, int c_mode) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     Smem<NT>& S = *reinterpret_cast<Smem<NT>*>(smem_raw);
     const int tid = threadIdx.x;
@@ -434,9 +435,15 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     }
 
     // ---- epilogue: add alpha * tile to every destination block of C (Sec. 4.2) ----
-    // the operand tiles are dead: reuse their LDS for the destinations' scatter tables
-    int64_t(*c_rs)[TM] = reinterpret_cast<int64_t(*)[TM]>(&S.a[0][0]);
-    int64_t(*c_cs)[TN] = reinterpret_cast<int64_t(*)[TN]>(&S.b[0][0]);
+    // The accumulators hold 4x4 blocks scattered over the tile; they are transposed through LDS (the operand buffers
+    // are dead) so that each wave-wide access to C covers 64 consecutive entries of C's contiguous direction.
+    // The gather tables' LDS is reused for the destinations' scatter tables.
+    constexpr int NPASS = (sizeof(S.a) + sizeof(S.b) >= (size_t)TN * OPITCH * sizeof(double)) ? 1 : 2;
+    constexpr int CP = TN / NPASS;  // tile columns staged per pass
+    static_assert(sizeof(S.a) + sizeof(S.b) >= (size_t)CP * OPITCH * sizeof(double), "output staging does not fit");
+    int64_t(*c_rs)[TM] = reinterpret_cast<int64_t(*)[TM]>(&S.a_fix[0][0]);
+    int64_t(*c_cs)[TN] = reinterpret_cast<int64_t(*)[TN]>(&S.b_fix[0][0]);
+    double* otile = &S.a[0][0];  // [CP columns][OPITCH], rows fastest
     const int nC = P.C.nterms;
     for (int e = tid; e < NT * TM; e += NTHREADS) {
         const int d = e / TM, x = e % TM;
@@ -448,28 +455,62 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         if (d < nC && gj < P.nb && P.C.coff[d] + gj < P.C.cs_len) val = as_global(P.C.cs)[P.C.coff[d] + gj];
         c_cs[d][x] = val;
     }
-    __syncthreads();
     double* Cbase = (P.C.space == 0 ? Cu : W) + P.C.base_off;
     const int dj = lane & 3, dblk = (lane >> 2) & 3, di = lane >> 4;
+#pragma unroll 1
+    for (int pass = 0; pass < NPASS; ++pass) {
+        if (pass > 0) __syncthreads();  // the previous pass has been read out
+        if (wn / (4 / NPASS) == pass) {
+            const int cw = (wn % (4 / NPASS)) * 32;
 #pragma unroll
-    for (int d = 0; d < NT; ++d) {
-        if (d >= nC) break;
-        const double g = P.C.coef[d];
-        const double f = P.overwrite ? 0.0 : (((P.first_mask >> d) & 1u) ? beta : 1.0);
-        int64_t rsv[4];
+            for (int y = 0; y < 2; ++y)
 #pragma unroll
-        for (int x = 0; x < 4; ++x) rsv[x] = c_rs[d][wm * 64 + x * 16 + dblk * 4 + di];
+                for (int s = 0; s < 4; ++s)
 #pragma unroll
-        for (int y = 0; y < 2; ++y) {
+                    for (int x = 0; x < 4; ++x)
+                        otile[(cw + y * 16 + ((dblk + s) & 3) * 4 + dj) * OPITCH + wm * 64 + x * 16 + dblk * 4 + di] = alpha * st.acc[x][y][s];
+        }
+        __syncthreads();
+        for (int d = 0; d < nC; ++d) {
+            const double g = P.C.coef[d];
+            const double f = P.overwrite ? 0.0 : (((P.first_mask >> d) & 1u) ? beta : 1.0);
+            constexpr int BATCH = CP / 4;  // elements per thread, destination and pass: all their loads are issued together
+            static_assert(BATCH == TM / (NTHREADS / CP), "both thread mappings cover the pass");
+            if (c_mode == 0) {
+                // lanes along the rows: thread = (row r, column group cg), columns cg + 4 j
+                const int r = tid & 127, cg = tid >> 7;
+                const int64_t rsd = c_rs[d][r];
+                for (int j0b = 0; j0b < CP / 4; j0b += BATCH) {
+                    int64_t off[BATCH];
+                    double cur[BATCH];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const int64_t csv = c_cs[d][wn * 32 + y * 16 + ((dblk + s) & 3) * 4 + dj];
+                    for (int b = 0; b < BATCH; ++b) {
+                        off[b] = rsd + c_cs[d][pass * CP + cg + 4 * (j0b + b)];
+                        cur[b] = (f != 0.0 && off[b] >= 0) ? Cbase[off[b]] : 0.0;
+                    }
 #pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    const int64_t off = rsv[x] + csv;
-                    if (off >= 0) {
-                        const double v = g * (alpha * st.acc[x][y][s]);
-                        Cbase[off] = (f == 0.0) ? v : __builtin_fma(f, Cbase[off], v);
+                    for (int b = 0; b < BATCH; ++b) {
+                        const double v = g * otile[(cg + 4 * (j0b + b)) * OPITCH + r];
+                        if (off[b] >= 0) Cbase[off[b]] = (f == 0.0) ? v : __builtin_fma(f, cur[b], v);
+                    }
+                }
+            } else {
+                // lanes along the columns: thread = (column c, row group rg), rows rg + RS j
+                constexpr int RS = NTHREADS / CP;
+                const int c = tid % CP, rg = tid / CP;
+                const int64_t csd = c_cs[d][pass * CP + c];
+                for (int j0b = 0; j0b < TM / RS; j0b += BATCH) {
+                    int64_t off[BATCH];
+                    double cur[BATCH];
+#pragma unroll
+                    for (int b = 0; b < BATCH; ++b) {
+                        off[b] = c_rs[d][rg + RS * (j0b + b)] + csd;
+                        cur[b] = (f != 0.0 && off[b] >= 0) ? Cbase[off[b]] : 0.0;
+                    }
+#pragma unroll
+                    for (int b = 0; b < BATCH; ++b) {
+                        const double v = g * otile[c * OPITCH + rg + RS * (j0b + b)];
+                        if (off[b] >= 0) Cbase[off[b]] = (f == 0.0) ? v : __builtin_fma(f, cur[b], v);
                     }
                 }
             }
@@ -479,7 +520,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
 
 template <int AMODE, int BMODE, int NT, bool VA, bool VB>
 int launch_one(const Product* prods, int first, int count, int tiles_m, int tiles_n, const double* A, const double* B, double* C,
-               double* W, double alpha, double beta, hipStream_t stream) {
+               double* W, double alpha, double beta, int c_mode, hipStream_t stream) {
     static bool configured = false;
     static_assert(sizeof(Smem<NT>) <= 160 * 1024, "LDS budget of one CU");
     const size_t smem = sizeof(Smem<NT>);
@@ -491,22 +532,22 @@ int launch_one(const Product* prods, int first, int count, int tiles_m, int tile
     }
     const int64_t blocks = (int64_t)count * tiles_m * tiles_n;
     if (blocks <= 0 || blocks > 0x7fffffff) return (int)hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), smem, stream, prods, first, tiles_m, tiles_n, A, B, C, W, alpha, beta);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), smem, stream, prods, first, tiles_m, tiles_n, A, B, C, W, alpha, beta, c_mode);
     return (int)hipGetLastError();
 }
 
 // vec: bit 0 = pair-wise gather of A, bit 1 = of B
 template <int NT>
-int launch_nt(int a_mode, int b_mode, int vec, const Product* prods, int first, int count, int tiles_m, int tiles_n, const double* A,
+int launch_nt(int a_mode, int b_mode, int vec, int c_mode, const Product* prods, int first, int count, int tiles_m, int tiles_n, const double* A,
               const double* B, double* C, double* W, double alpha, double beta, hipStream_t stream);
 
 #define TC_FUSED_CASE(AM, BM, VA, VB) \
     case ((AM) * 8 + (BM) * 4 + (VA) * 2 + (VB)): \
-        return launch_one<AM, BM, NT, (VA) != 0, (VB) != 0>(prods, first, count, tiles_m, tiles_n, A, B, C, W, alpha, beta, stream);
+        return launch_one<AM, BM, NT, (VA) != 0, (VB) != 0>(prods, first, count, tiles_m, tiles_n, A, B, C, W, alpha, beta, c_mode, stream);
 
 #define TC_FUSED_DEFINE_LAUNCH(NTV)                                                                                                  \
     template <>                                                                                                                      \
-    int launch_nt<NTV>(int a_mode, int b_mode, int vec, const Product* prods, int first, int count, int tiles_m, int tiles_n,        \
+    int launch_nt<NTV>(int a_mode, int b_mode, int vec, int c_mode, const Product* prods, int first, int count, int tiles_m, int tiles_n,        \
                        const double* A, const double* B, double* C, double* W, double alpha, double beta, hipStream_t stream) {      \
         constexpr int NT = NTV;                                                                                                      \
         switch (a_mode * 8 + b_mode * 4 + (vec & 1) * 2 + ((vec >> 1) & 1)) {                                                        \

@@ -428,7 +428,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         }
         // emit in phase order; the first product (in that order) to write a block of C applies beta to it
         const bool fusedC = (variant == TC_VARIANT_ABC || level == 0);
-        const tc::FusedConfig user_cfg_base{p->a_mode, p->b_mode, 1, p->a_vec, p->b_vec, 0, 0};
+        const tc::FusedConfig user_cfg_base{p->a_mode, p->b_mode, 1, p->a_vec, p->b_vec, 0, 0, p->c_mode};
         for (int ph = 0; ph < nphase; ++ph) {
             int first_dev = (int)p->prods.size(), count = 0, cls = 1;
             for (size_t e = 0; e < list.size(); ++e) {
@@ -462,6 +462,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
                     mul.first_mask = 1;
                     mul.overwrite = 1;
                     tc::FusedConfig cfg = user_cfg_base;
+                    cfg.c_mode = 0;  // M is dense with contiguous rows
                     if (variant == TC_VARIANT_NAIVE) {
                         Product sa, sb;  // operand sums -> TA, TB
                         std::memset(&sa, 0, sizeof sa);
@@ -483,7 +484,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
                         add_term(mul.A, 0, 0, 1.0);
                         set_operand(mul.B, vec(V_RSTB), vec(V_CSTB), p->kb, p->nb, 1, p->wsTB);
                         add_term(mul.B, 0, 0, 1.0);
-                        cfg = tc::FusedConfig{0, 1, 1, 1, 1, 1, 1};  // dense temporaries: block extents are multiples of 16
+                        cfg = tc::FusedConfig{0, 1, 1, 1, 1, 1, 1, 0};  // dense temporaries: block extents are multiples of 16
                     } else {
                         cfg.max_terms = terms_class(std::max(q.view.n_a, q.view.n_b));
                     }

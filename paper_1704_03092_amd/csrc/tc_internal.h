@@ -49,6 +49,7 @@ struct FusedConfig {
     int max_terms;        // 1, 2 or 4: which instantiation to launch
     int a_vec, b_vec;     // consecutive entry pairs along the lane direction are contiguous and evenly placed
     int a_space, b_space; // 0: caller's tensor, 1: workspace (for the pointer alignment check)
+    int c_mode;           // 0: the destination is contiguous along its rows (free bundle I), 1: along its columns
 };
 
 // ---- device entry points (tc_device.hip); each returns a hipError_t cast to int ----
