@@ -37,6 +37,9 @@ struct Cfg {
     static constexpr int KT = (NT <= 2) ? 32 : 16;
     static constexpr int NE = TM * KT / NTHREADS;  // elements of each operand tile a thread gathers per k-step
     static constexpr int NQ = KT / 4;              // matrix-core instruction groups per k-step
+    // The second wave of a SIMD issues its gather after this many groups, when its partner's burst of loads has
+    // drained from the CU's address pipeline (a burst lasts longer the more terms there are); measured optimum.
+    static constexpr int LATE = (NT == 1) ? 3 : (NT == 2) ? 4 : 3;
 };
 
 // LDS tile layout: element (k, x) of a KT x 128 tile lives at k * PITCH + x.  Instruction group q of a k-step
@@ -210,7 +213,7 @@ struct State {
     int tid, nA, nB, nk, kfull;
     bool plainA, plainB;       // single term with coefficient +1: staged as loaded
     bool early;                // this wave issues its gather before the matrix-core work of a k-step, its partner on
-                               // the same SIMD a quarter of the way in: one of the two always has MFMAs to issue
+                               // the same SIMD after Cfg::LATE groups: one of the two always has MFMAs to issue
     const double *safeA, *safeB;
     // scatter entries of later k-steps
     gvec_t ent_ptr;
@@ -280,7 +283,7 @@ struct State {
         if constexpr (Q < NQ) {
             if constexpr (Q + 1 < NQ) read_frags<CUR, Q + 1>(af[(Q + 1) & 1], bf[(Q + 1) & 1]);
             multiply(af[Q & 1], bf[Q & 1]);
-            if constexpr (Q + 1 == NQ / 4) {
+            if constexpr (Q + 1 == Cfg<NT>::LATE) {
                 if (!early) issue<SLOT>(step + 1);
             }
             groups<CUR, Q + 1, SLOT>(af, bf, step);
