@@ -131,9 +131,9 @@ int launch_planner(const BundleDesc* descs_dev, int nvec, int64_t max_total, int
 
 namespace fused {
 constexpr int kTile = 128;
-template <int NT>
-int launch_nt(int a_mode, int b_mode, int vec, int c_mode, const Product* prods, int first, int count, int tiles_m, int tiles_n, const double* A,
-              const double* B, double* C, double* W, double alpha, double beta, hipStream_t stream);
+template <int NTA, int NTB, bool EXACT>
+int launch_family(int a_mode, int b_mode, int vec, int c_mode, const Product* prods, int first, int count, int tiles_m, int tiles_n,
+                  const double* A, const double* B, double* C, double* W, double alpha, double beta, hipStream_t stream);
 }  // namespace fused
 
 int launch_fused(const FusedConfig& cfg, const Product* prods_dev, int first, int count, int64_t mb, int64_t nb, const double* A,
@@ -147,12 +147,17 @@ int launch_fused(const FusedConfig& cfg, const Product* prods_dev, int first, in
     if (cfg.a_vec && aligned(cfg.a_space == 0 ? (const void*)A : (const void*)W)) vec |= 1;
     if (cfg.b_vec && aligned(cfg.b_space == 0 ? (const void*)B : (const void*)W)) vec |= 2;
     const int tm = (int)tiles_m, tn = (int)tiles_n;
-    switch (cfg.max_terms) {
-        case 1: return fused::launch_nt<1>(cfg.a_mode, cfg.b_mode, vec, cfg.c_mode, prods_dev, first, count, tm, tn, A, B, C, W, alpha, beta, st);
-        case 2: return fused::launch_nt<2>(cfg.a_mode, cfg.b_mode, vec, cfg.c_mode, prods_dev, first, count, tm, tn, A, B, C, W, alpha, beta, st);
-        case 4: return fused::launch_nt<4>(cfg.a_mode, cfg.b_mode, vec, cfg.c_mode, prods_dev, first, count, tm, tn, A, B, C, W, alpha, beta, st);
+#define TC_FAMILY(NA, NB, EX) \
+    return fused::launch_family<NA, NB, EX>(cfg.a_mode, cfg.b_mode, vec, cfg.c_mode, prods_dev, first, count, tm, tn, A, B, C, W, alpha, beta, st)
+    switch (cfg.nta * 8 + cfg.ntb) {
+        case 0: TC_FAMILY(4, 4, false);
+        case 1 * 8 + 1: TC_FAMILY(1, 1, true);
+        case 1 * 8 + 2: TC_FAMILY(1, 2, true);
+        case 2 * 8 + 1: TC_FAMILY(2, 1, true);
+        case 2 * 8 + 2: TC_FAMILY(2, 2, true);
         default: return (int)hipErrorInvalidValue;
     }
+#undef TC_FAMILY
 }
 
 int launch_lincomb(const Product* prods_dev, int index, int64_t mb, int64_t nb, int lanes_along_rows, const double* A, const double* B,

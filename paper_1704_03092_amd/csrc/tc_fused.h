@@ -29,18 +29,7 @@ constexpr int TM = 128;        // tile rows (free bundle I)
 constexpr int TN = 128;        // tile columns (free bundle J)
 constexpr int NTHREADS = 512;  // 8 waves: 2 along the rows x 4 along the columns, each owning 64 x 32 outputs
 constexpr int GROUP_M = 8;     // tile rows per rasterisation group
-
-// Contracted entries per pipeline step.  A gathered element needs more than 16 entries' worth of matrix-core
-// work to arrive, so the step is made as deep as the registers allow: 32 for one or two terms per operand.
-template <int NT>
-struct Cfg {
-    static constexpr int KT = (NT <= 2) ? 32 : 16;
-    static constexpr int NE = TM * KT / NTHREADS;  // elements of each operand tile a thread gathers per k-step
-    static constexpr int NQ = KT / 4;              // matrix-core instruction groups per k-step
-    // The second wave of a SIMD issues its gather after this many groups, when its partner's burst of loads has
-    // drained from the CU's address pipeline (a burst lasts longer the more terms there are); measured optimum.
-    static constexpr int LATE = (NT == 1) ? 3 : (NT == 2) ? 4 : 3;
-};
+constexpr int MAXC = 4;        // destinations of a product
 
 // LDS tile layout: element (k, x) of a KT x 128 tile lives at k * PITCH + x.  Instruction group q of a k-step
 // takes k = 16 * (q / 4) + 4 * (lane / 16) + q % 4, so one fragment load touches rows k and k + 4 in each half-wave;
@@ -48,6 +37,42 @@ struct Cfg {
 // is one per-lane base plus a compile-time offset.
 constexpr int PITCH = 132;
 constexpr int OPITCH = 130;  // row pitch of the output tile staged in LDS by the epilogue
+
+// One kernel family per (NTA, NTB) = terms of the operand sums of A and B.
+//   EXACT : every product of the launch has exactly NTA and NTB terms.  The term loops are compile-time and the
+//           gather of TWO k-steps is in flight (D = 2): measured under load, a gathered element takes about 7000
+//           cycles to arrive, more than the matrix-core work of one k-step, so the loads of k-step s + 2 are issued
+//           during k-step s and their sum is stored to LDS during k-step s + 1, long after they have landed.
+//   !EXACT: up to NTA / NTB terms, counted at run time (the 3- and 4-term sums of two-level schedules); one k-step
+//           of gather in flight, stored at the end of the step it was issued in.
+// The register sets of the loads in flight bound the k-step depth KT: 32 for single terms, 16 otherwise.
+template <int NTA_, int NTB_, bool EXACT_>
+struct Cfg {
+    static constexpr int NTA = NTA_, NTB = NTB_;
+    static constexpr bool EXACT = EXACT_;
+#ifndef TC_D2
+#define TC_D2 (EXACT && NTA == 1 && NTB == 1)
+#define TC_KT32 EXACT
+#define TC_IL1 4
+#endif
+    static constexpr int D = TC_D2 ? 2 : 1;
+    static constexpr int KT = TC_KT32 ? 32 : 16;
+    static constexpr int NE = TM * KT / NTHREADS;  // elements of each operand tile (and term) a thread gathers per k-step
+    static constexpr int NQ = KT / 4;              // matrix-core instruction groups per k-step
+    static constexpr int TILE = KT * PITCH;
+    // Schedule inside a k-step, in instruction groups completed.  The two waves of a SIMD do their loads and LDS
+    // stores at different times so that one of them always has MFMAs to issue: the first ("early") wave issues its
+    // gather before group 0, its partner after ISSUE_LATE groups, when the first burst of loads has drained from
+    // the CU's address pipeline.
+#ifndef TC_SCHED8
+#define TC_SCHED8 4, 6, 3
+#define TC_SCHED4 2, 3, 1
+#endif
+    static constexpr int kSched8[3] = {TC_SCHED8}, kSched4[3] = {TC_SCHED4};  // ISSUE_LATE, STAGE_EARLY, STAGE_LATE
+    static constexpr int ISSUE_LATE = (D == 2) ? (NQ == 8 ? kSched8[0] : kSched4[0]) : (NQ == 8 ? TC_IL1 : 3);
+    static constexpr int STAGE_EARLY = (D == 2) ? (NQ == 8 ? kSched8[1] : kSched4[1]) : NQ;
+    static constexpr int STAGE_LATE = (D == 2) ? (NQ == 8 ? kSched8[2] : kSched4[2]) : NQ;
+};
 
 // Scatter vectors are reached through pointers stored in the product descriptors; telling the compiler that they
 // point to global memory keeps their loads off the flat path (a pending flat load forces a full wait before the
@@ -58,17 +83,18 @@ typedef const __attribute__((address_space(1))) double* gdbl_t;
 typedef double double2_t __attribute__((ext_vector_type(2)));
 typedef const __attribute__((address_space(1))) double2_t* gdbl2_t;
 
-template <int NT>
+template <class CF>
 struct Smem {
-    static constexpr int KT = Cfg<NT>::KT;
-    static constexpr int TILE = KT * PITCH;
-    double a[2][TILE];
-    double b[2][TILE];
-    int64_t a_fix[NT][TM];      // per term: address of row x of the A blocks (base + 8 * rscat), kSentinel where padded
-    int64_t b_fix[NT][TN];      // per term: address of column x of the B blocks (base + 8 * cscat)
-    int64_t a_step[2][NT][KT];  // per term: 8 * cscat_A of the contracted entries of a k-step (two steps in flight)
-    int64_t b_step[2][NT][KT];  // per term: 8 * rscat_B
-    int64_t dump[2][NT][KT];    // where threads that own no table entry store theirs (keeps that store branch-free)
+    static constexpr int KT = CF::KT, NTA = CF::NTA, NTB = CF::NTB;
+    double a[2][CF::TILE];
+    double b[2][CF::TILE];
+    int64_t a_fix[NTA][TM];      // per term: address of row x of the A blocks (base + 8 * rscat), kSentinel where padded
+    int64_t b_fix[NTB][TN];      // per term: address of column x of the B blocks (base + 8 * cscat)
+    int64_t a_step[2][NTA][KT];  // per term: 8 * cscat_A of the contracted entries of a k-step (two table slots)
+    int64_t b_step[2][NTB][KT];  // per term: 8 * rscat_B
+    int64_t dump[2][64];         // where threads that own no table entry store theirs (keeps that store branch-free)
+    int64_t c_rs[MAXC][TM];      // epilogue: row and column scatter entries of every destination
+    int64_t c_cs[MAXC][TN];
 };
 
 // Which elements of a KT x 128 operand tile a thread gathers in a k-step.
@@ -77,11 +103,11 @@ struct Smem {
 //           (one 128-byte line) times 4 x, which also makes the transposing LDS store hit every bank pair twice
 //   VEC   : an element pair per load: (x, x+1) in mode 0, (k, k+1) in mode 1
 // Load e of a thread is element (K0 + CK * e, X0 + CX * e).
-template <int MODE, int NT, bool VEC>
+template <int MODE, int KT, bool VEC>
 struct Map {
-    static constexpr int KT = Cfg<NT>::KT;
+    static constexpr int NE = TM * KT / NTHREADS;
     static constexpr int KB = KT / 16;
-    static constexpr int N = VEC ? Cfg<NT>::NE / 2 : Cfg<NT>::NE;  // loads per thread, term and k-step
+    static constexpr int N = VEC ? NE / 2 : NE;  // loads per thread, term and k-step
     static constexpr int CK = (MODE == 0) ? (VEC ? 8 : 4) : 0;
     static constexpr int CX = (MODE == 1) ? (VEC ? 64 / KB : 32 / KB) : 0;
     __device__ static __forceinline__ int k0(int tid) {
@@ -104,15 +130,14 @@ struct Bases {
 };
 
 // Issue the loads of one k-step for every term; absent terms (index >= nterms) contribute zeros.
-template <int MODE, int NT, bool VEC>
-__device__ __forceinline__ void issue_fast(double (&ld)[NT][Cfg<NT>::NE], const Bases& b, int slot_off, int nterms) {
-    typedef Map<MODE, NT, VEC> M;
-    constexpr int KT = Cfg<NT>::KT;
+template <int MODE, int NT, int KT, bool VEC, bool EXACT>
+__device__ __forceinline__ void issue_fast(double (&ld)[NT][TM * KT / NTHREADS], const Bases& b, int slot_off, int nterms) {
+    typedef Map<MODE, KT, VEC> M;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        if (t > 0 && t >= nterms) {
+        if (!EXACT && t > 0 && t >= nterms) {
 #pragma unroll
-            for (int e = 0; e < Cfg<NT>::NE; ++e) ld[t][e] = 0.0;
+            for (int e = 0; e < M::NE; ++e) ld[t][e] = 0.0;
         } else {
 #pragma unroll
             for (int e = 0; e < M::N; ++e) {
@@ -130,10 +155,10 @@ __device__ __forceinline__ void issue_fast(double (&ld)[NT][Cfg<NT>::NE], const 
 }
 
 // Signed sum of the terms (the operand sum of Sec. 4.1) into the LDS tile.
-template <int MODE, int NT, bool VEC>
-__device__ __forceinline__ void stage_fast(const double (&ld)[NT][Cfg<NT>::NE], double* __restrict__ dst, const double* __restrict__ coef,
+template <int MODE, int NT, int KT, bool VEC>
+__device__ __forceinline__ void stage_fast(const double (&ld)[NT][TM * KT / NTHREADS], double* __restrict__ dst, const double* __restrict__ coef,
                                            bool plain) {
-    typedef Map<MODE, NT, VEC> M;
+    typedef Map<MODE, KT, VEC> M;
 #pragma unroll
     for (int e = 0; e < M::N; ++e) {
         double v[2];
@@ -163,11 +188,11 @@ __device__ __forceinline__ void stage_fast(const double (&ld)[NT][Cfg<NT>::NE], 
 
 // Gather with padding checks (tiles or k-steps that touch the zero padding of a Strassen block or the ragged edge):
 // entries of the padding (negative table sum) read the operand's element 0 and count as zero.  Scalar mapping.
-template <int MODE, int NT>
-__device__ __forceinline__ void issue_checked(double (&ld)[NT][Cfg<NT>::NE], unsigned& padmask, const double* __restrict__ safe,
+template <int MODE, int NT, int KT>
+__device__ __forceinline__ void issue_checked(double (&ld)[NT][TM * KT / NTHREADS], unsigned& padmask, const double* __restrict__ safe,
                                               const int64_t* __restrict__ fixed_tab, const int64_t* __restrict__ step_tab, int nterms, int tid) {
-    typedef Map<MODE, NT, false> M;
-    constexpr int KT = Cfg<NT>::KT, NE = Cfg<NT>::NE;
+    typedef Map<MODE, KT, false> M;
+    constexpr int NE = M::NE;
     const int k0 = M::k0(tid), x0 = M::x0(tid);
     padmask = 0;
 #pragma unroll
@@ -185,11 +210,11 @@ __device__ __forceinline__ void issue_checked(double (&ld)[NT][Cfg<NT>::NE], uns
     }
 }
 
-template <int MODE, int NT>
-__device__ __forceinline__ void stage_checked(const double (&ld)[NT][Cfg<NT>::NE], unsigned padmask, double* __restrict__ tile,
+template <int MODE, int NT, int KT>
+__device__ __forceinline__ void stage_checked(const double (&ld)[NT][TM * KT / NTHREADS], unsigned padmask, double* __restrict__ tile,
                                               const double* __restrict__ coef, int tid) {
-    typedef Map<MODE, NT, false> M;
-    constexpr int NE = Cfg<NT>::NE;
+    typedef Map<MODE, KT, false> M;
+    constexpr int NE = M::NE;
     double* dst = tile + M::k0(tid) * PITCH + M::x0(tid);
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
@@ -205,53 +230,54 @@ __device__ __forceinline__ void stage_checked(const double (&ld)[NT][Cfg<NT>::NE
 
 __device__ __forceinline__ int64_t min64(int64_t a, int64_t b) { return a < b ? a : b; }
 
-template <int AMODE, int BMODE, int NT, bool VA, bool VB>
+template <int AMODE, int BMODE, class CF, bool VA, bool VB>
 struct State {
-    static constexpr int KT = Cfg<NT>::KT, NE = Cfg<NT>::NE, NQ = Cfg<NT>::NQ, TILE = KT * PITCH;
-    Smem<NT>* S;
+    static constexpr int KT = CF::KT, NE = CF::NE, NQ = CF::NQ, TILE = CF::TILE, D = CF::D, NTA = CF::NTA, NTB = CF::NTB;
+    static_assert(NTA * NE <= 32 && NTB * NE <= 32, "padding masks are 32 bits");
+    Smem<CF>* S;
     const Product* P;
     int tid, nA, nB, nk, kfull;
     bool plainA, plainB;       // single term with coefficient +1: staged as loaded
-    bool early;                // this wave issues its gather before the matrix-core work of a k-step, its partner on
-                               // the same SIMD after Cfg::LATE groups: one of the two always has MFMAs to issue
+    bool early;                // first of the two waves of its SIMD
+    double coefA[NTA], coefB[NTB];
     const double *safeA, *safeB;
     // scatter entries of later k-steps
     gvec_t ent_ptr;
     int ent_limit;             // k entries that exist for this thread's term, counted from its own k
     int64_t* ent_dst;
+    int ent_stride;            // distance between the two table slots at ent_dst
     Bases ba, bb;
     // per-lane fragment bases
     const double* fa;
     const double* fb[4];
     double acc[4][2][4];
-    double la[NT][NE], lb[NT][NE];
-    unsigned pa, pb;
-    bool issued_fast;          // the loads in flight were issued without padding checks
+    double la[D][NTA][NE], lb[D][NTB][NE];  // register sets of the gathers in flight
+    unsigned pa[D], pb[D];
+    bool issued_fast[D];       // the loads of a set were issued without padding checks
 
-    // gather of k-step `target` (table slot SLOT = target % 2)
-    template <int SLOT>
+    // gather of k-step `target` into register set SET, with the table slot SLOT (= target % 2).
+    // FAST: the caller knows that the k-step has no padding (target < kfull); otherwise that is decided here.
+    template <int SET, int SLOT, bool FAST>
     __device__ __forceinline__ void issue(int target) {
-        if (target < nk) {
-            issued_fast = target < kfull;  // no padding anywhere in that k-step
-            if (issued_fast) {
-                issue_fast<AMODE, NT, VA>(la, ba, SLOT * NT * KT, nA);
-                issue_fast<BMODE, NT, VB>(lb, bb, SLOT * NT * KT, nB);
-            } else {
-                issue_checked<AMODE, NT>(la, pa, safeA, &S->a_fix[0][0], &S->a_step[SLOT][0][0], nA, tid);
-                issue_checked<BMODE, NT>(lb, pb, safeB, &S->b_fix[0][0], &S->b_step[SLOT][0][0], nB, tid);
-            }
+        if (!FAST) issued_fast[SET] = target < kfull;
+        if (FAST || issued_fast[SET]) {
+            issue_fast<AMODE, NTA, KT, VA, CF::EXACT>(la[SET], ba, SLOT * NTA * KT, nA);
+            issue_fast<BMODE, NTB, KT, VB, CF::EXACT>(lb[SET], bb, SLOT * NTB * KT, nB);
+        } else {
+            issue_checked<AMODE, NTA, KT>(la[SET], pa[SET], safeA, &S->a_fix[0][0], &S->a_step[SLOT][0][0], nA, tid);
+            issue_checked<BMODE, NTB, KT>(lb[SET], pb[SET], safeB, &S->b_fix[0][0], &S->b_step[SLOT][0][0], nB, tid);
         }
     }
 
-    // operand sums of the loads in flight into LDS buffer BUF
-    template <int BUF>
+    // operand sums of register set SET into LDS buffer BUF
+    template <int SET, int BUF, bool FAST>
     __device__ __forceinline__ void stage() {
-        if (issued_fast) {
-            stage_fast<AMODE, NT, VA>(la, ba.stage + BUF * TILE, P->A.coef, plainA);
-            stage_fast<BMODE, NT, VB>(lb, bb.stage + BUF * TILE, P->B.coef, plainB);
+        if (FAST || issued_fast[SET]) {
+            stage_fast<AMODE, NTA, KT, VA>(la[SET], ba.stage + BUF * TILE, coefA, plainA);
+            stage_fast<BMODE, NTB, KT, VB>(lb[SET], bb.stage + BUF * TILE, coefB, plainB);
         } else {
-            stage_checked<AMODE, NT>(la, pa, &S->a[BUF][0], P->A.coef, tid);
-            stage_checked<BMODE, NT>(lb, pb, &S->b[BUF][0], P->B.coef, tid);
+            stage_checked<AMODE, NTA, KT>(la[SET], pa[SET], &S->a[BUF][0], coefA, tid);
+            stage_checked<BMODE, NTB, KT>(lb[SET], pb[SET], &S->b[BUF][0], coefB, tid);
         }
     }
 
@@ -276,49 +302,102 @@ struct State {
                     acc[x][y][s] = __builtin_amdgcn_mfma_f64_4x4x4f64(af[x], bf[y * 4 + s], acc[x][y][s], 0, 0, 0);
     }
 
+    // With one k-step in flight the compiler must not move the waits for gathered data up into the MFMA groups;
+    // with two in flight the data has long arrived and free scheduling measured faster.
+    __device__ static __forceinline__ void pin() {
+        if constexpr (D == 1) __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // What a wave does besides MFMAs once DONE instruction groups of k-step `step` (LDS buffer CUR) are complete.
+    // D = 2: the loads of step + 2 go to register set CUR (its previous contents, k-step `step`, were stored one
+    //        step ago), and set CUR ^ 1 (k-step step + 1, issued one step ago) is stored to LDS buffer CUR ^ 1.
+    // D = 1: the loads of step + 1 are issued and, after the last group, stored.
+    // ROLE: 0 = first wave of the SIMD, 1 = second, 2 = decided at run time (member `early`).
+    template <int CUR, int DONE, int ROLE, bool FAST>
+    __device__ __forceinline__ void between_groups(int step) {
+        constexpr int NXT = CUR ^ 1;
+        constexpr int ISET = (D == 2) ? CUR : 0, SSET = (D == 2) ? NXT : 0, ISLOT = (D == 2) ? CUR : NXT;
+        if constexpr (ROLE != 1 && DONE == CF::STAGE_EARLY) {
+            pin();
+            if (ROLE == 0 || early) stage<SSET, NXT, FAST>();
+            pin();
+        }
+        if constexpr (ROLE != 0 && DONE == CF::STAGE_LATE) {
+            pin();
+            if (ROLE == 1 || !early) stage<SSET, NXT, FAST>();
+            pin();
+        }
+        if constexpr (ROLE != 1 && DONE == 0) {
+            pin();
+            if (ROLE == 0 || early) issue<ISET, ISLOT, FAST>(step + D);
+            pin();
+        }
+        if constexpr (ROLE != 0 && DONE == CF::ISSUE_LATE) {
+            pin();
+            if (ROLE == 1 || !early) issue<ISET, ISLOT, FAST>(step + D);
+            pin();
+        }
+    }
+
     // instruction groups Q .. NQ-1 of the k-step in LDS buffer CUR; the fragments of group Q are in af/bf[Q % 2] and
     // those of group Q + 1 are read while group Q multiplies
-    template <int CUR, int Q, int SLOT>
+    template <int CUR, int Q, int ROLE, bool FAST>
     __device__ __forceinline__ void groups(double (&af)[2][4], double (&bf)[2][8], int step) {
         if constexpr (Q < NQ) {
             if constexpr (Q + 1 < NQ) read_frags<CUR, Q + 1>(af[(Q + 1) & 1], bf[(Q + 1) & 1]);
             multiply(af[Q & 1], bf[Q & 1]);
-            if constexpr (Q + 1 == Cfg<NT>::LATE) {
-                if (!early) issue<SLOT>(step + 1);
-            }
-            groups<CUR, Q + 1, SLOT>(af, bf, step);
+            between_groups<CUR, Q + 1, ROLE, FAST>(step);
+            groups<CUR, Q + 1, ROLE, FAST>(af, bf, step);
         }
     }
 
-    // One k-step: gather k-step step + 1, multiply the tiles of this step (LDS buffer CUR), stage k-step step + 1.
-    template <int CUR>
+    // One k-step.  The scatter entries of k-step step + D + 1 are fetched first (so that waiting for them at the end
+    // of the step does not wait for the gather issued after them) and stored to the free table slot at the end.
+    template <int CUR, int ROLE, bool FAST>
     __device__ __forceinline__ void step_body(int step) {
-        constexpr int NXT = CUR ^ 1;
-        if (early) issue<NXT>(step + 1);
-        // table entry of k-step step + 2; unconditional load: ent_ptr always points at readable memory
-        const int kn = (step + 2) * KT;
+        constexpr int ESLOT = (D == 2) ? (CUR ^ 1) : CUR;
+        const int kn = (step + D + 1) * KT;
         const bool have = kn < ent_limit;
-        const int64_t raw_entry = ent_ptr[have ? kn : 0];
+        const int64_t raw_entry = ent_ptr[have ? kn : 0];  // unconditional load: ent_ptr always points at readable memory
 
+        between_groups<CUR, 0, ROLE, FAST>(step);
         double af[2][4], bf[2][8];
         read_frags<CUR, 0>(af[0], bf[0]);
-        groups<CUR, 0, NXT>(af, bf, step);
+        groups<CUR, 0, ROLE, FAST>(af, bf, step);
 
-        if (step + 1 < nk) stage<NXT>();
-        ent_dst[CUR * NT * KT] = have ? raw_entry * 8 : kSentinel;  // every thread stores: no branch around the wait
+        ent_dst[ESLOT ? ent_stride : 0] = have ? raw_entry * 8 : kSentinel;  // every thread stores: no branch around the wait
         __syncthreads();
+    }
+
+    // k-steps [0, end) (end even) of a tile whose gathers up to k-step end + D - 1 need no padding checks.  The
+    // wave's role is a compile-time property of this loop and there is no control flow inside it, so the compiler's
+    // wait counts for the loads in flight are exact.
+    template <int ROLE>
+    __device__ __forceinline__ void run_fast(int end) {
+        for (int step = 0; step < end; step += 2) {
+            step_body<0, ROLE, true>(step);
+            step_body<1, ROLE, true>(step + 1);
+        }
+    }
+
+    // k-steps [begin, nk) (both even): padding decided per k-step
+    __device__ __forceinline__ void run_checked(int begin) {
+        for (int step = begin; step < nk; step += 2) {
+            step_body<0, 2, false>(step);
+            step_body<1, 2, false>(step + 1);
+        }
     }
 };
 
-template <int AMODE, int BMODE, int NT, bool VA, bool VB>
+template <int AMODE, int BMODE, class CF, bool VA, bool VB>
 __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __restrict__ prods, int first, int tiles_m, int tiles_n,
                                                             const double* __restrict__ Au, const double* __restrict__ Bu,
                                                             double* __restrict__ Cu, double* __restrict__ W, double alpha, double beta, int c_mode) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    Smem<NT>& S = *reinterpret_cast<Smem<NT>*>(smem_raw);
+    Smem<CF>& S = *reinterpret_cast<Smem<CF>*>(smem_raw);
     const int tid = threadIdx.x;
-    typedef State<AMODE, BMODE, NT, VA, VB> St;
-    constexpr int KT = St::KT;
+    typedef State<AMODE, BMODE, CF, VA, VB> St;
+    constexpr int KT = CF::KT, NTA = CF::NTA, NTB = CF::NTB, D = CF::D;
 
     // ---- which tile: spread consecutive logical ids over one XCD (block b runs on XCD b % 8), then walk
     //      GROUP_M tile rows at a time so that co-resident workgroups share A and B panels in that XCD's L2 ----
@@ -336,7 +415,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     const int tm = gm0 + rem % gh, tn = rem / gh;
     const Product& P = prods[first + pidx];
     const int64_t i0 = (int64_t)tm * TM, j0 = (int64_t)tn * TN;
-    const int nA = P.A.nterms, nB = P.B.nterms;
+    const int nA = CF::EXACT ? NTA : P.A.nterms, nB = CF::EXACT ? NTB : P.B.nterms;
 
     St st;
     st.S = &S;
@@ -345,53 +424,68 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     st.nA = nA;
     st.nB = nB;
     st.nk = (int)((P.kb + KT - 1) / KT);
+    st.nk += st.nk & 1;  // the k loop runs two steps per trip; a k-step past the end gathers only zero padding
     st.plainA = nA == 1 && P.A.coef[0] == 1.0;
     st.plainB = nB == 1 && P.B.coef[0] == 1.0;
+#pragma unroll
+    for (int t = 0; t < NTA; ++t) st.coefA[t] = P.A.coef[t];
+#pragma unroll
+    for (int t = 0; t < NTB; ++t) st.coefB[t] = P.B.coef[t];
     const double* Abase = (P.A.space == 0 ? Au : W) + P.A.base_off;
     const double* Bbase = (P.B.space == 0 ? Bu : W) + P.B.base_off;
     st.safeA = Abase;
     st.safeB = Bbase;
-    st.pa = st.pb = 0;
-    st.issued_fast = false;
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        st.pa[d] = st.pb[d] = 0;
+        st.issued_fast[d] = false;
+    }
 
     // ---- tile-fixed gather tables; how much of the tile and of the k range is free of zero padding ----
     int64_t klimit = P.kb;       // k entries that are real in every term of both operands
     bool tile_full = true;       // every row and column of the tile is real in every term
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
+    for (int t = 0; t < NTA; ++t)
         if (t < nA) {
             klimit = min64(klimit, P.A.cs_len - P.A.coff[t]);
             tile_full = tile_full && (i0 + TM <= min64(P.mb, P.A.rs_len - P.A.roff[t]));
         }
+#pragma unroll
+    for (int t = 0; t < NTB; ++t)
         if (t < nB) {
             klimit = min64(klimit, P.B.rs_len - P.B.roff[t]);
             tile_full = tile_full && (j0 + TN <= min64(P.nb, P.B.cs_len - P.B.coff[t]));
         }
-    }
     st.kfull = tile_full ? (int)(klimit / KT) : 0;  // k-steps [0, kfull) need no checks
-    for (int e = tid; e < NT * TM; e += NTHREADS) {
+    for (int e = tid; e < NTA * TM; e += NTHREADS) {
         const int t = e / TM, x = e % TM;
         const int64_t gi = i0 + x;
         int64_t val = kSentinel;
         if (t < nA && gi < P.mb && P.A.roff[t] + gi < P.A.rs_len) val = (int64_t)Abase + 8 * as_global(P.A.rs)[P.A.roff[t] + gi];
         S.a_fix[t][x] = val;
+    }
+    for (int e = tid; e < NTB * TN; e += NTHREADS) {
+        const int t = e / TN, x = e % TN;
         const int64_t gj = j0 + x;
-        val = kSentinel;
+        int64_t val = kSentinel;
         if (t < nB && gj < P.nb && P.B.coff[t] + gj < P.B.cs_len) val = (int64_t)Bbase + 8 * as_global(P.B.cs)[P.B.coff[t] + gj];
         S.b_fix[t][x] = val;
     }
-    // Threads 0..KT*NT-1 fetch the column scatter entries of A for a k-step (one per term and k), threads
-    // 256..256+KT*NT-1 the row scatter entries of B, two k-steps ahead of the tile that uses them.
+    // Threads 0..KT*NTA-1 fetch the column scatter entries of A for a k-step (one per term and k), threads
+    // 256..256+KT*NTB-1 the row scatter entries of B, D + 1 k-steps ahead of the tile that uses them.
+    static_assert(KT * NTA <= 256 && KT * NTB <= 256, "one owner thread per table entry");
     st.ent_ptr = as_global(reinterpret_cast<const int64_t*>(&P));  // dummy target for threads without an entry
     st.ent_limit = 0;
-    st.ent_dst = &S.dump[0][0][0];
+    st.ent_dst = &S.dump[0][0];
+    st.ent_stride = 64;
     {
         const bool isB = tid >= 256;
         const int q = tid & 255, t = q / KT, kl = q % KT;
-        if (t < NT) {
+        if (t < (isB ? NTB : NTA)) {
             const Operand& op = isB ? P.B : P.A;
             st.ent_dst = isB ? &S.b_step[0][t][kl] : &S.a_step[0][t][kl];
-            if (t < op.nterms) {
+            st.ent_stride = (isB ? NTB : NTA) * KT;
+            if (t < (isB ? nB : nA)) {
                 const int64_t off0 = isB ? op.roff[t] : op.coff[t];
                 st.ent_ptr = as_global(isB ? op.rs : op.cs) + off0 + kl;
                 st.ent_limit = (int)(min64(P.kb, (isB ? op.rs_len : op.cs_len) - off0) - kl);
@@ -399,20 +493,19 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         }
     }
     st.ent_dst[0] = (0 < st.ent_limit) ? 8 * st.ent_ptr[0] : kSentinel;
-    st.ent_dst[NT * KT] = (KT < st.ent_limit) ? 8 * st.ent_ptr[KT] : kSentinel;
+    st.ent_dst[st.ent_stride] = (KT < st.ent_limit) ? 8 * st.ent_ptr[KT] : kSentinel;
     __syncthreads();
 
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
     const int l16 = lane & 15, lk = lane >> 4;
-    st.early = wm == 0;
     // per-lane bases; everything else in an LDS address is a compile-time offset
     st.fa = &S.a[0][0] + 4 * lk * PITCH + wm * 64 + l16;
 #pragma unroll
     for (int s = 0; s < 4; ++s) st.fb[s] = &S.b[0][0] + 4 * lk * PITCH + wn * 32 + ((l16 + 4 * s) & 15);
     {
-        typedef Map<AMODE, NT, VA> MA;
-        typedef Map<BMODE, NT, VB> MB;
+        typedef Map<AMODE, KT, VA> MA;
+        typedef Map<BMODE, KT, VB> MB;
         st.ba.fix = &S.a_fix[0][0] + MA::x0(tid);
         st.ba.step = &S.a_step[0][0][0] + MA::k0(tid);
         st.ba.stage = &S.a[0][0] + MA::k0(tid) * PITCH + MA::x0(tid);
@@ -421,9 +514,15 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         st.bb.stage = &S.b[0][0] + MB::k0(tid) * PITCH + MB::x0(tid);
     }
 
-    // ---- prologue: k-step 0 into LDS buffer 0 ----
-    st.template issue<0>(0);
-    st.template stage<0>();
+    // ---- prologue: k-step 0 into LDS buffer 0; with two steps in flight also the gather of k-step 1 and the
+    //      scatter entries of k-step 2 ----
+    st.template issue<0, 0, false>(0);
+    if constexpr (D == 2) {
+        st.template issue<1, 1, false>(1);
+        __syncthreads();  // table slot 0 has been read by every thread
+        st.ent_dst[0] = (2 * KT < st.ent_limit) ? 8 * st.ent_ptr[2 * KT] : kSentinel;
+    }
+    st.template stage<0, 0, false>();
 #pragma unroll
     for (int x = 0; x < 4; ++x)
 #pragma unroll
@@ -432,23 +531,31 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
             for (int s = 0; s < 4; ++s) st.acc[x][y][s] = 0.0;
     __syncthreads();
 
-    for (int step = 0; step < st.nk; step += 2) {
-        st.template step_body<0>(step);
-        if (step + 1 < st.nk) st.template step_body<1>(step + 1);
+    // k-steps whose gathers need no padding checks run in a loop specialised for the wave's role on its SIMD
+    // (wm = 0: first, wm = 1: second); the remaining ones (ragged edge, zero padding, the last D steps) decide per step.
+    st.early = wm == 0;
+    int nfast = st.kfull - D;
+    nfast = nfast < 2 ? 0 : (nfast & ~1);
+    if (nfast > 0) {
+        if (__builtin_amdgcn_readfirstlane(wm) == 0)
+            st.template run_fast<0>(nfast);
+        else
+            st.template run_fast<1>(nfast);
+        if constexpr (D == 2) st.issued_fast[1] = true;  // the gather of k-step nfast + 1 is in flight
     }
+    st.run_checked(nfast);
 
     // ---- epilogue: add alpha * tile to every destination block of C (Sec. 4.2) ----
     // The accumulators hold 4x4 blocks scattered over the tile; they are transposed through LDS (the operand buffers
     // are dead) so that each wave-wide access to C covers 64 consecutive entries of C's contiguous direction.
-    // The gather tables' LDS is reused for the destinations' scatter tables.
     constexpr int NPASS = (sizeof(S.a) + sizeof(S.b) >= (size_t)TN * OPITCH * sizeof(double)) ? 1 : 2;
     constexpr int CP = TN / NPASS;  // tile columns staged per pass
     static_assert(sizeof(S.a) + sizeof(S.b) >= (size_t)CP * OPITCH * sizeof(double), "output staging does not fit");
-    int64_t(*c_rs)[TM] = reinterpret_cast<int64_t(*)[TM]>(&S.a_fix[0][0]);
-    int64_t(*c_cs)[TN] = reinterpret_cast<int64_t(*)[TN]>(&S.b_fix[0][0]);
+    int64_t(*c_rs)[TM] = S.c_rs;
+    int64_t(*c_cs)[TN] = S.c_cs;
     double* otile = &S.a[0][0];  // [CP columns][OPITCH], rows fastest
     const int nC = P.C.nterms;
-    for (int e = tid; e < NT * TM; e += NTHREADS) {
+    for (int e = tid; e < MAXC * TM; e += NTHREADS) {
         const int d = e / TM, x = e % TM;
         const int64_t gi = i0 + x, gj = j0 + x;
         int64_t val = kSentinel;
@@ -521,13 +628,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     }
 }
 
-template <int AMODE, int BMODE, int NT, bool VA, bool VB>
+template <int AMODE, int BMODE, class CF, bool VA, bool VB>
 int launch_one(const Product* prods, int first, int count, int tiles_m, int tiles_n, const double* A, const double* B, double* C,
                double* W, double alpha, double beta, int c_mode, hipStream_t stream) {
     static bool configured = false;
-    static_assert(sizeof(Smem<NT>) <= 160 * 1024, "LDS budget of one CU");
-    const size_t smem = sizeof(Smem<NT>);
-    auto kern = fused_kernel<AMODE, BMODE, NT, VA, VB>;
+    static_assert(sizeof(Smem<CF>) <= 160 * 1024, "LDS budget of one CU");
+    const size_t smem = sizeof(Smem<CF>);
+    auto kern = fused_kernel<AMODE, BMODE, CF, VA, VB>;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return (int)e;
@@ -539,20 +646,22 @@ int launch_one(const Product* prods, int first, int count, int tiles_m, int tile
     return (int)hipGetLastError();
 }
 
-// vec: bit 0 = pair-wise gather of A, bit 1 = of B
-template <int NT>
-int launch_nt(int a_mode, int b_mode, int vec, int c_mode, const Product* prods, int first, int count, int tiles_m, int tiles_n, const double* A,
-              const double* B, double* C, double* W, double alpha, double beta, hipStream_t stream);
+// One launcher per kernel family, each defined in a translation unit of its own.  vec: bit 0 = pair-wise gather of A,
+// bit 1 = of B.
+template <int NTA, int NTB, bool EXACT>
+int launch_family(int a_mode, int b_mode, int vec, int c_mode, const Product* prods, int first, int count, int tiles_m, int tiles_n,
+                  const double* A, const double* B, double* C, double* W, double alpha, double beta, hipStream_t stream);
 
 #define TC_FUSED_CASE(AM, BM, VA, VB) \
     case ((AM) * 8 + (BM) * 4 + (VA) * 2 + (VB)): \
-        return launch_one<AM, BM, NT, (VA) != 0, (VB) != 0>(prods, first, count, tiles_m, tiles_n, A, B, C, W, alpha, beta, c_mode, stream);
+        return launch_one<AM, BM, CF, (VA) != 0, (VB) != 0>(prods, first, count, tiles_m, tiles_n, A, B, C, W, alpha, beta, c_mode, stream);
 
-#define TC_FUSED_DEFINE_LAUNCH(NTV)                                                                                                  \
+#define TC_FUSED_DEFINE_LAUNCH(NTAV, NTBV, EXACTV)                                                                                   \
     template <>                                                                                                                      \
-    int launch_nt<NTV>(int a_mode, int b_mode, int vec, int c_mode, const Product* prods, int first, int count, int tiles_m, int tiles_n,        \
-                       const double* A, const double* B, double* C, double* W, double alpha, double beta, hipStream_t stream) {      \
-        constexpr int NT = NTV;                                                                                                      \
+    int launch_family<NTAV, NTBV, EXACTV>(int a_mode, int b_mode, int vec, int c_mode, const Product* prods, int first, int count,   \
+                                          int tiles_m, int tiles_n, const double* A, const double* B, double* C, double* W,          \
+                                          double alpha, double beta, hipStream_t stream) {                                           \
+        typedef Cfg<NTAV, NTBV, EXACTV> CF;                                                                                          \
         switch (a_mode * 8 + b_mode * 4 + (vec & 1) * 2 + ((vec >> 1) & 1)) {                                                        \
             TC_FUSED_CASE(0, 0, 0, 0) TC_FUSED_CASE(0, 0, 0, 1) TC_FUSED_CASE(0, 0, 1, 0) TC_FUSED_CASE(0, 0, 1, 1)                  \
             TC_FUSED_CASE(0, 1, 0, 0) TC_FUSED_CASE(0, 1, 0, 1) TC_FUSED_CASE(0, 1, 1, 0) TC_FUSED_CASE(0, 1, 1, 1)                  \

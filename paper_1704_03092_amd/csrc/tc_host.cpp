@@ -222,7 +222,9 @@ void add_term(Operand& op, int64_t roff, int64_t coff, double coef) {
     ++op.nterms;
 }
 
-int terms_class(int n) { return n <= 1 ? 1 : n <= 2 ? 2 : 4; }
+// Kernel family of a product: sums of one or two terms on both sides have kernels specialised for exactly those
+// counts (key 8 * n_a + n_b); everything else runs in the family that counts terms at run time (key 0).
+int terms_class(int n_a, int n_b) { return (n_a <= 2 && n_b <= 2) ? 8 * n_a + n_b : 0; }
 
 int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const tc_tensor_desc_t* C, int level, int variant,
                const tc_options_t* opts, void* stream) {
@@ -408,7 +410,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
             std::vector<int> pclass;
             for (size_t e = 0; e < list.size(); ++e) {
                 const tc_product_t& v = list[e].view;
-                int cls = terms_class(std::max(v.n_a, std::max(v.n_b, v.n_c)));
+                int cls = terms_class(v.n_a, v.n_b);
                 int chosen = -1;
                 if (merge) {
                     for (int ph = 0; ph < nphase && chosen < 0; ++ph) {
@@ -428,9 +430,9 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         }
         // emit in phase order; the first product (in that order) to write a block of C applies beta to it
         const bool fusedC = (variant == TC_VARIANT_ABC || level == 0);
-        const tc::FusedConfig user_cfg_base{p->a_mode, p->b_mode, 1, p->a_vec, p->b_vec, 0, 0, p->c_mode};
+        const tc::FusedConfig user_cfg_base{p->a_mode, p->b_mode, 1, 1, p->a_vec, p->b_vec, 0, 0, p->c_mode};
         for (int ph = 0; ph < nphase; ++ph) {
-            int first_dev = (int)p->prods.size(), count = 0, cls = 1;
+            int first_dev = (int)p->prods.size(), count = 0, cls = 0;
             for (size_t e = 0; e < list.size(); ++e) {
                 if (phase[e] != ph) continue;
                 Pending& q = list[e];
@@ -441,7 +443,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
                     t = 1;
                 }
                 q.view.launch = (int)p->steps.size();
-                cls = std::max(cls, terms_class(std::max(q.view.n_a, std::max(q.view.n_b, q.view.n_c))));
+                cls = terms_class(q.view.n_a, q.view.n_b);  // merged launches hold one class
                 if (fusedC) {
                     q.pr.first_mask = first_mask;
                     p->prods.push_back(q.pr);
@@ -484,9 +486,10 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
                         add_term(mul.A, 0, 0, 1.0);
                         set_operand(mul.B, vec(V_RSTB), vec(V_CSTB), p->kb, p->nb, 1, p->wsTB);
                         add_term(mul.B, 0, 0, 1.0);
-                        cfg = tc::FusedConfig{0, 1, 1, 1, 1, 1, 1, 0};  // dense temporaries: block extents are multiples of 16
+                        cfg = tc::FusedConfig{0, 1, 1, 1, 1, 1, 1, 1, 0};  // dense temporaries: block extents are multiples of 16
                     } else {
-                        cfg.max_terms = terms_class(std::max(q.view.n_a, q.view.n_b));
+                        cfg.nta = terms_class(q.view.n_a, q.view.n_b) / 8;
+                        cfg.ntb = terms_class(q.view.n_a, q.view.n_b) % 8;
                     }
                     int i1 = (int)p->prods.size();
                     p->prods.push_back(mul);
@@ -499,7 +502,8 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
             }
             if (fusedC && count > 0) {
                 tc::FusedConfig cfg = user_cfg_base;
-                cfg.max_terms = cls;
+                cfg.nta = cls / 8;
+                cfg.ntb = cls % 8;
                 p->steps.push_back(Step{STEP_FUSED, first_dev, count, cfg, p->mb, p->nb, 0, 0});
             }
         }

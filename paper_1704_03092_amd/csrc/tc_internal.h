@@ -46,7 +46,8 @@ struct BundleDesc {
 
 struct FusedConfig {
     int a_mode, b_mode;   // 0: lanes run along the free bundle when gathering, 1: along the contracted bundle
-    int max_terms;        // 1, 2 or 4: which instantiation to launch
+    int nta, ntb;         // terms of the A and B sums if every product of the launch has exactly that many (1 or 2 each);
+                          // 0, 0: up to four terms, counted at run time
     int a_vec, b_vec;     // consecutive entry pairs along the lane direction are contiguous and evenly placed
     int a_space, b_space; // 0: caller's tensor, 1: workspace (for the pointer alignment check)
     int c_mode;           // 0: the destination is contiguous along its rows (free bundle I), 1: along its columns
