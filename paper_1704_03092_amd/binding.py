@@ -31,7 +31,7 @@ def build(verbose: bool = False) -> str:
     """Compile the HIP library for gfx950 with hipcc (cross-compiles without a GPU); translation units in parallel."""
     from concurrent.futures import ThreadPoolExecutor
 
-    names = ["tc_host.cpp", "tc_device.hip", "tc_fused_11.hip", "tc_fused_12.hip", "tc_fused_21.hip", "tc_fused_22.hip", "tc_fused_44.hip"]
+    names = ["tc_host.cpp", "tc_device.hip", "tc_fused_11.hip", "tc_fused_12.hip", "tc_fused_21.hip", "tc_fused_22.hip", "tc_fused_14.hip", "tc_fused_41.hip", "tc_fused_24.hip", "tc_fused_42.hip", "tc_fused_44.hip", "tc_fused_any.hip"]
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objdir = os.path.join(_HERE, "csrc", "_build")
     os.makedirs(objdir, exist_ok=True)

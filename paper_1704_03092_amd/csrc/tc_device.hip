@@ -155,6 +155,11 @@ int launch_fused(const FusedConfig& cfg, const Product* prods_dev, int first, in
         case 1 * 8 + 2: TC_FAMILY(1, 2, true);
         case 2 * 8 + 1: TC_FAMILY(2, 1, true);
         case 2 * 8 + 2: TC_FAMILY(2, 2, true);
+        case 1 * 8 + 4: TC_FAMILY(1, 4, true);
+        case 4 * 8 + 1: TC_FAMILY(4, 1, true);
+        case 2 * 8 + 4: TC_FAMILY(2, 4, true);
+        case 4 * 8 + 2: TC_FAMILY(4, 2, true);
+        case 4 * 8 + 4: TC_FAMILY(4, 4, true);
         default: return (int)hipErrorInvalidValue;
     }
 #undef TC_FAMILY

@@ -52,7 +52,7 @@ struct Cfg {
     static constexpr bool EXACT = EXACT_;
 #ifndef TC_D2
 #define TC_D2 (EXACT && NTA == 1 && NTB == 1)
-#define TC_KT32 EXACT
+#define TC_KT32 (EXACT && NTA <= 2 && NTB <= 2)
 #define TC_IL1 4
 #endif
     static constexpr int D = TC_D2 ? 2 : 1;
@@ -65,7 +65,7 @@ struct Cfg {
     // gather before group 0, its partner after ISSUE_LATE groups, when the first burst of loads has drained from
     // the CU's address pipeline.
 #ifndef TC_SCHED8
-#define TC_SCHED8 4, 6, 3
+#define TC_SCHED8 5, 6, 4
 #define TC_SCHED4 2, 3, 1
 #endif
     static constexpr int kSched8[3] = {TC_SCHED8}, kSched4[3] = {TC_SCHED4};  // ISSUE_LATE, STAGE_EARLY, STAGE_LATE
@@ -155,9 +155,8 @@ __device__ __forceinline__ void issue_fast(double (&ld)[NT][TM * KT / NTHREADS],
 }
 
 // Signed sum of the terms (the operand sum of Sec. 4.1) into the LDS tile.
-template <int MODE, int NT, int KT, bool VEC>
-__device__ __forceinline__ void stage_fast(const double (&ld)[NT][TM * KT / NTHREADS], double* __restrict__ dst, const double* __restrict__ coef,
-                                           bool plain) {
+template <int MODE, int NT, int KT, bool VEC, bool PLAIN>
+__device__ __forceinline__ void stage_fast(const double (&ld)[NT][TM * KT / NTHREADS], double* __restrict__ dst, const double* __restrict__ coef) {
     typedef Map<MODE, KT, VEC> M;
 #pragma unroll
     for (int e = 0; e < M::N; ++e) {
@@ -166,7 +165,7 @@ __device__ __forceinline__ void stage_fast(const double (&ld)[NT][TM * KT / NTHR
         for (int h = 0; h < (VEC ? 2 : 1); ++h) {
             const int i = VEC ? 2 * e + h : e;
             if (NT == 1) {
-                v[h] = plain ? ld[0][i] : coef[0] * ld[0][i];
+                v[h] = (PLAIN && NT == 1) ? ld[0][i] : coef[0] * ld[0][i];
             } else {
                 v[h] = coef[0] * ld[0][i];
 #pragma unroll
@@ -270,11 +269,12 @@ struct State {
     }
 
     // operand sums of register set SET into LDS buffer BUF
-    template <int SET, int BUF, bool FAST>
+    // PLAIN: both operands are single terms with coefficient +1 and are stored as loaded
+    template <int SET, int BUF, bool FAST, bool PLAIN>
     __device__ __forceinline__ void stage() {
         if (FAST || issued_fast[SET]) {
-            stage_fast<AMODE, NTA, KT, VA>(la[SET], ba.stage + BUF * TILE, coefA, plainA);
-            stage_fast<BMODE, NTB, KT, VB>(lb[SET], bb.stage + BUF * TILE, coefB, plainB);
+            stage_fast<AMODE, NTA, KT, VA, PLAIN>(la[SET], ba.stage + BUF * TILE, coefA);
+            stage_fast<BMODE, NTB, KT, VB, PLAIN>(lb[SET], bb.stage + BUF * TILE, coefB);
         } else {
             stage_checked<AMODE, NTA, KT>(la[SET], pa[SET], &S->a[BUF][0], coefA, tid);
             stage_checked<BMODE, NTB, KT>(lb[SET], pb[SET], &S->b[BUF][0], coefB, tid);
@@ -285,11 +285,17 @@ struct State {
     __device__ __forceinline__ void read_frags(double (&af)[4], double (&bf)[8]) {
         constexpr int ROW = 16 * (Q / 4) + (Q % 4);
 #pragma unroll
-        for (int x = 0; x < 4; ++x) af[x] = fa[CUR * TILE + ROW * PITCH + x * 16];
+        for (int xp = 0; xp < 2; ++xp) {
+            const double2_t v = *reinterpret_cast<const double2_t*>(fa + CUR * TILE + ROW * PITCH + xp * 32);
+            af[2 * xp] = v.x;
+            af[2 * xp + 1] = v.y;
+        }
 #pragma unroll
-        for (int y = 0; y < 2; ++y)
-#pragma unroll
-            for (int s = 0; s < 4; ++s) bf[y * 4 + s] = fb[s][CUR * TILE + ROW * PITCH + y * 16];
+        for (int s = 0; s < 4; ++s) {
+            const double2_t v = *reinterpret_cast<const double2_t*>(fb[s] + CUR * TILE + ROW * PITCH);
+            bf[s] = v.x;
+            bf[4 + s] = v.y;
+        }
     }
 
     __device__ __forceinline__ void multiply(const double (&af)[4], const double (&bf)[8]) {
@@ -313,18 +319,18 @@ struct State {
     //        step ago), and set CUR ^ 1 (k-step step + 1, issued one step ago) is stored to LDS buffer CUR ^ 1.
     // D = 1: the loads of step + 1 are issued and, after the last group, stored.
     // ROLE: 0 = first wave of the SIMD, 1 = second, 2 = decided at run time (member `early`).
-    template <int CUR, int DONE, int ROLE, bool FAST>
+    template <int CUR, int DONE, int ROLE, bool FAST, bool PLAIN>
     __device__ __forceinline__ void between_groups(int step) {
         constexpr int NXT = CUR ^ 1;
         constexpr int ISET = (D == 2) ? CUR : 0, SSET = (D == 2) ? NXT : 0, ISLOT = (D == 2) ? CUR : NXT;
         if constexpr (ROLE != 1 && DONE == CF::STAGE_EARLY) {
             pin();
-            if (ROLE == 0 || early) stage<SSET, NXT, FAST>();
+            if (ROLE == 0 || early) stage<SSET, NXT, FAST, PLAIN>();
             pin();
         }
         if constexpr (ROLE != 0 && DONE == CF::STAGE_LATE) {
             pin();
-            if (ROLE == 1 || !early) stage<SSET, NXT, FAST>();
+            if (ROLE == 1 || !early) stage<SSET, NXT, FAST, PLAIN>();
             pin();
         }
         if constexpr (ROLE != 1 && DONE == 0) {
@@ -341,29 +347,29 @@ struct State {
 
     // instruction groups Q .. NQ-1 of the k-step in LDS buffer CUR; the fragments of group Q are in af/bf[Q % 2] and
     // those of group Q + 1 are read while group Q multiplies
-    template <int CUR, int Q, int ROLE, bool FAST>
+    template <int CUR, int Q, int ROLE, bool FAST, bool PLAIN>
     __device__ __forceinline__ void groups(double (&af)[2][4], double (&bf)[2][8], int step) {
         if constexpr (Q < NQ) {
             if constexpr (Q + 1 < NQ) read_frags<CUR, Q + 1>(af[(Q + 1) & 1], bf[(Q + 1) & 1]);
             multiply(af[Q & 1], bf[Q & 1]);
-            between_groups<CUR, Q + 1, ROLE, FAST>(step);
-            groups<CUR, Q + 1, ROLE, FAST>(af, bf, step);
+            between_groups<CUR, Q + 1, ROLE, FAST, PLAIN>(step);
+            groups<CUR, Q + 1, ROLE, FAST, PLAIN>(af, bf, step);
         }
     }
 
     // One k-step.  The scatter entries of k-step step + D + 1 are fetched first (so that waiting for them at the end
     // of the step does not wait for the gather issued after them) and stored to the free table slot at the end.
-    template <int CUR, int ROLE, bool FAST>
+    template <int CUR, int ROLE, bool FAST, bool PLAIN>
     __device__ __forceinline__ void step_body(int step) {
         constexpr int ESLOT = (D == 2) ? (CUR ^ 1) : CUR;
         const int kn = (step + D + 1) * KT;
         const bool have = kn < ent_limit;
         const int64_t raw_entry = ent_ptr[have ? kn : 0];  // unconditional load: ent_ptr always points at readable memory
 
-        between_groups<CUR, 0, ROLE, FAST>(step);
+        between_groups<CUR, 0, ROLE, FAST, PLAIN>(step);
         double af[2][4], bf[2][8];
         read_frags<CUR, 0>(af[0], bf[0]);
-        groups<CUR, 0, ROLE, FAST>(af, bf, step);
+        groups<CUR, 0, ROLE, FAST, PLAIN>(af, bf, step);
 
         ent_dst[ESLOT ? ent_stride : 0] = have ? raw_entry * 8 : kSentinel;  // every thread stores: no branch around the wait
         __syncthreads();
@@ -372,19 +378,19 @@ struct State {
     // k-steps [0, end) (end even) of a tile whose gathers up to k-step end + D - 1 need no padding checks.  The
     // wave's role is a compile-time property of this loop and there is no control flow inside it, so the compiler's
     // wait counts for the loads in flight are exact.
-    template <int ROLE>
+    template <int ROLE, bool PLAIN>
     __device__ __forceinline__ void run_fast(int end) {
         for (int step = 0; step < end; step += 2) {
-            step_body<0, ROLE, true>(step);
-            step_body<1, ROLE, true>(step + 1);
+            step_body<0, ROLE, true, PLAIN>(step);
+            step_body<1, ROLE, true, PLAIN>(step + 1);
         }
     }
 
     // k-steps [begin, nk) (both even): padding decided per k-step
     __device__ __forceinline__ void run_checked(int begin) {
         for (int step = begin; step < nk; step += 2) {
-            step_body<0, 2, false>(step);
-            step_body<1, 2, false>(step + 1);
+            step_body<0, 2, false, false>(step);
+            step_body<1, 2, false, false>(step + 1);
         }
     }
 };
@@ -500,9 +506,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     const int wm = wave >> 2, wn = wave & 3;
     const int l16 = lane & 15, lk = lane >> 4;
     // per-lane bases; everything else in an LDS address is a compile-time offset
-    st.fa = &S.a[0][0] + 4 * lk * PITCH + wm * 64 + l16;
+    // Fragment x of a lane is tile row 32 * (x / 2) + 2 * l16 + x % 2 of the wave's 64 rows, fragment (y, s) column
+    // 2 * ((l16 + 4 s) % 16) + y of its 32 columns: two fragments per 16-byte LDS read, conflict-free, and every
+    // read address is a per-lane base plus a constant that fits the instruction's offset field.
+    st.fa = &S.a[0][0] + 4 * lk * PITCH + wm * 64 + 2 * l16;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) st.fb[s] = &S.b[0][0] + 4 * lk * PITCH + wn * 32 + ((l16 + 4 * s) & 15);
+    for (int s = 0; s < 4; ++s) st.fb[s] = &S.b[0][0] + 4 * lk * PITCH + wn * 32 + 2 * ((l16 + 4 * s) & 15);
     {
         typedef Map<AMODE, KT, VA> MA;
         typedef Map<BMODE, KT, VB> MB;
@@ -522,7 +531,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         __syncthreads();  // table slot 0 has been read by every thread
         st.ent_dst[0] = (2 * KT < st.ent_limit) ? 8 * st.ent_ptr[2 * KT] : kSentinel;
     }
-    st.template stage<0, 0, false>();
+    st.template stage<0, 0, false, false>();
 #pragma unroll
     for (int x = 0; x < 4; ++x)
 #pragma unroll
@@ -537,10 +546,19 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     int nfast = st.kfull - D;
     nfast = nfast < 2 ? 0 : (nfast & ~1);
     if (nfast > 0) {
-        if (__builtin_amdgcn_readfirstlane(wm) == 0)
-            st.template run_fast<0>(nfast);
-        else
-            st.template run_fast<1>(nfast);
+        constexpr bool kPlainLoop = NTA == 1 && NTB == 1;  // a loop of its own for operands stored exactly as loaded
+        const bool role0 = __builtin_amdgcn_readfirstlane(wm) == 0;
+        if (kPlainLoop && st.plainA && st.plainB) {
+            if (role0)
+                st.template run_fast<0, kPlainLoop>(nfast);
+            else
+                st.template run_fast<1, kPlainLoop>(nfast);
+        } else {
+            if (role0)
+                st.template run_fast<0, false>(nfast);
+            else
+                st.template run_fast<1, false>(nfast);
+        }
         if constexpr (D == 2) st.issued_fast[1] = true;  // the gather of k-step nfast + 1 is in flight
     }
     st.run_checked(nfast);
@@ -578,7 +596,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
                 for (int s = 0; s < 4; ++s)
 #pragma unroll
                     for (int x = 0; x < 4; ++x)
-                        otile[(cw + y * 16 + ((dblk + s) & 3) * 4 + dj) * OPITCH + wm * 64 + x * 16 + dblk * 4 + di] = alpha * st.acc[x][y][s];
+                        otile[(cw + 2 * (((dblk + s) & 3) * 4 + dj) + y) * OPITCH + wm * 64 + 32 * (x >> 1) + 2 * (dblk * 4 + di) + (x & 1)] =
+                            alpha * st.acc[x][y][s];
         }
         __syncthreads();
         for (int d = 0; d < nC; ++d) {

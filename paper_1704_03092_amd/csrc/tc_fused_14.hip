@@ -1,0 +1,8 @@
+// Fused kernel family: 1 term(s) of A, 4 of B, exact.
+#include "tc_fused.h"
+
+namespace tc {
+namespace fused {
+TC_FUSED_DEFINE_LAUNCH(1, 4, true)
+}  // namespace fused
+}  // namespace tc

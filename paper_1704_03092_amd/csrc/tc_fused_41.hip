@@ -1,0 +1,8 @@
+// Fused kernel family: 4 term(s) of A, 1 of B, exact.
+#include "tc_fused.h"
+
+namespace tc {
+namespace fused {
+TC_FUSED_DEFINE_LAUNCH(4, 1, true)
+}  // namespace fused
+}  // namespace tc

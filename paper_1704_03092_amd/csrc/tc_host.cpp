@@ -222,9 +222,10 @@ void add_term(Operand& op, int64_t roff, int64_t coff, double coef) {
     ++op.nterms;
 }
 
-// Kernel family of a product: sums of one or two terms on both sides have kernels specialised for exactly those
-// counts (key 8 * n_a + n_b); everything else runs in the family that counts terms at run time (key 0).
-int terms_class(int n_a, int n_b) { return (n_a <= 2 && n_b <= 2) ? 8 * n_a + n_b : 0; }
+// Kernel family of a product: sums of one, two or four terms on both sides have kernels specialised for exactly
+// those counts (key 8 * n_a + n_b); a three-term sum (a four-term sum that lost a block to the zero padding) runs
+// in the family that counts terms at run time (key 0).
+int terms_class(int n_a, int n_b) { return (n_a != 3 && n_b != 3) ? 8 * n_a + n_b : 0; }
 
 int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const tc_tensor_desc_t* C, int level, int variant,
                const tc_options_t* opts, void* stream) {
