@@ -24,6 +24,20 @@ if ROOT not in sys.path:
 FP64_MFMA_PEAK_TFLOPS = 78.6  # MI355X published dense FP64 matrix peak
 
 
+def profiled_traffic(N, level, variant):
+    """HBM bytes per fused-kernel launch (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy kernel) from the committed
+    counter summary of this exact workload; None if there is none.  The counters need the profiler, so they are
+    collected in separate runs of this script under rocprofv3 --pmc and written down in profiles/."""
+    import re
+
+    path = os.path.join(ROOT, "profiles", f"fused_kernel_cfg2_{N}_level{level}_{variant}.md")
+    try:
+        m = re.search(r"^hbm_traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(path).read(), re.M)
+    except OSError:
+        return None
+    return float(m.group(1)) if m else None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -34,6 +48,8 @@ def main():
     ap.add_argument("--variant", default="abc")
     ap.add_argument("--modes", default="0abc,1abc,1ab,1naive,2abc,2ab,2naive", help="other modes to time (level+variant)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also launch one plain element-wise copy of 512 MiB (for scaling the profiler's HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -99,6 +115,13 @@ def main():
         ev_ms = sum(e0.elapsed_time(e1) for e0, e1 in evs) / steps
         return wall_ms, ev_ms, info
 
+    if args.calib_copy:  # reads 2^26 doubles and writes 2^26 doubles, nothing else
+        cx = torch.rand(1 << 26, dtype=torch.float64, device="cuda")
+        cy = torch.empty_like(cx)
+        torch.mul(cx, 1.0, out=cy)
+        torch.cuda.synchronize()
+        del cx, cy
+
     # ---- headline mode ----
     wall_ms, ev_ms, info = time_mode(args.level, args.variant, args.steps, args.warmup)
     value = flops / (wall_ms * 1e-3) * 1e-9
@@ -125,7 +148,7 @@ def main():
     executed = flops * (7.0 / 8.0) ** info["level"]
     achieved = executed / (ev_ms * 1e-3) * 1e-12
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / FP64_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                "frac": round(achieved / FP64_MFMA_PEAK_TFLOPS, 4), "traffic": profiled_traffic(N, info["level"], args.variant),
                 "kernel": "fused_kernel", "launches_per_contract": nlaunch_fused,
                 "flops_per_launch": executed / nlaunch_fused, "avg_launch_ms": round(ev_ms / nlaunch_fused, 4)}
 

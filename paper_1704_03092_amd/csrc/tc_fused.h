@@ -32,9 +32,9 @@ constexpr int GROUP_M = 8;     // tile rows per rasterisation group
 constexpr int MAXC = 4;        // destinations of a product
 
 // LDS tile layout: element (k, x) of a KT x 128 tile lives at k * PITCH + x.  Instruction group q of a k-step
-// takes k = 16 * (q / 4) + 4 * (lane / 16) + q % 4, so one fragment load touches rows k and k + 4 in each half-wave;
-// with PITCH = 132 those rows start 16 bank-pairs apart and the load is conflict-free, and every fragment address
-// is one per-lane base plus a compile-time offset.
+// takes k = 16 * (q / 4) + krow(lane / 16) + q % 4 with krow = 0, 8, 4, 12, so every fragment address is one
+// per-lane base plus a compile-time offset; PITCH = 132 keeps both the fragment reads and the transposing stores
+// of the staging step (nearly) free of bank conflicts.
 constexpr int PITCH = 132;
 constexpr int OPITCH = 130;  // row pitch of the output tile staged in LDS by the epilogue
 
@@ -509,9 +509,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     // Fragment x of a lane is tile row 32 * (x / 2) + 2 * l16 + x % 2 of the wave's 64 rows, fragment (y, s) column
     // 2 * ((l16 + 4 s) % 16) + y of its 32 columns: two fragments per 16-byte LDS read, conflict-free, and every
     // read address is a per-lane base plus a constant that fits the instruction's offset field.
-    st.fa = &S.a[0][0] + 4 * lk * PITCH + wm * 64 + 2 * l16;
+    // Lane group lk = lane / 16 takes the contracted entries krow + q (+ 16 per further four groups).  Measured: a
+    // 16-byte LDS read is conflict-free only if lanes l and l + 16 of each half-wave are a multiple of 256 bytes
+    // apart, i.e. 8 tile rows with PITCH = 132; the two half-waves may differ.
+    const int krow = 8 * (lk & 1) + 4 * (lk >> 1);
+    st.fa = &S.a[0][0] + krow * PITCH + wm * 64 + 2 * l16;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) st.fb[s] = &S.b[0][0] + 4 * lk * PITCH + wn * 32 + 2 * ((l16 + 4 * s) & 15);
+    for (int s = 0; s < 4; ++s) st.fb[s] = &S.b[0][0] + krow * PITCH + wn * 32 + 2 * ((l16 + 4 * s) & 15);
     {
         typedef Map<AMODE, KT, VA> MA;
         typedef Map<BMODE, KT, VB> MB;
