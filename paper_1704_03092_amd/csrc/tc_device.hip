@@ -141,11 +141,7 @@ int launch_fused(const FusedConfig& cfg, const Product* prods_dev, int first, in
     const int64_t tiles_m = (mb + fused::kTile - 1) / fused::kTile, tiles_n = (nb + fused::kTile - 1) / fused::kTile;
     if (tiles_m <= 0 || tiles_n <= 0 || tiles_m > (1 << 20) || tiles_n > (1 << 20)) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
-    // pair-wise gathers need 16-byte aligned pairs: the plan vouches for the strides, the pointers are checked here
-    auto aligned = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
-    int vec = 0;
-    if (cfg.a_vec && aligned(cfg.a_space == 0 ? (const void*)A : (const void*)W)) vec |= 1;
-    if (cfg.b_vec && aligned(cfg.b_space == 0 ? (const void*)B : (const void*)W)) vec |= 2;
+    const int vec = (cfg.a_vec ? 1 : 0) | (cfg.b_vec ? 2 : 0);  // pair-wise gathers (pairs are 8-byte aligned)
     const int tm = (int)tiles_m, tn = (int)tiles_n;
 #define TC_FAMILY(NA, NB, EX) \
     return fused::launch_family<NA, NB, EX>(cfg.a_mode, cfg.b_mode, vec, cfg.c_mode, prods_dev, first, count, tm, tn, A, B, C, W, alpha, beta, st)

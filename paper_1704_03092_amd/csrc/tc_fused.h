@@ -16,7 +16,7 @@
 // gather tables hold ready-made byte addresses (one 64-bit add per load), the k-step loop is unrolled over the two
 // LDS buffers so that every LDS address is a per-lane base plus a constant, and an operand with a single +1 term is
 // stored as loaded.  A wave-wide global load costs the CU's address pipeline the same whatever its width, so
-// operands whose consecutive entries are contiguous and 16-byte aligned are gathered two elements per load.
+// operands whose consecutive entry pairs are contiguous are gathered two elements per load.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -81,7 +81,8 @@ typedef const __attribute__((address_space(1))) int64_t* gvec_t;
 __device__ __forceinline__ gvec_t as_global(const int64_t* p) { return (gvec_t)p; }
 typedef const __attribute__((address_space(1))) double* gdbl_t;
 typedef double double2_t __attribute__((ext_vector_type(2)));
-typedef const __attribute__((address_space(1))) double2_t* gdbl2_t;
+typedef double2_t double2_u __attribute__((aligned(8)));  // an element pair in global memory: 8-byte aligned only
+typedef const __attribute__((address_space(1))) double2_u* gdbl2_t;
 
 template <class CF>
 struct Smem {
@@ -155,7 +156,7 @@ __device__ __forceinline__ void issue_fast(double (&ld)[NT][TM * KT / NTHREADS],
 }
 
 // Signed sum of the terms (the operand sum of Sec. 4.1) into the LDS tile.
-template <int MODE, int NT, int KT, bool VEC, bool PLAIN>
+template <int MODE, int NT, int KT, bool VEC, bool UNIT>
 __device__ __forceinline__ void stage_fast(const double (&ld)[NT][TM * KT / NTHREADS], double* __restrict__ dst, const double* __restrict__ coef) {
     typedef Map<MODE, KT, VEC> M;
 #pragma unroll
@@ -165,9 +166,9 @@ __device__ __forceinline__ void stage_fast(const double (&ld)[NT][TM * KT / NTHR
         for (int h = 0; h < (VEC ? 2 : 1); ++h) {
             const int i = VEC ? 2 * e + h : e;
             if (NT == 1) {
-                v[h] = (PLAIN && NT == 1) ? ld[0][i] : coef[0] * ld[0][i];
+                v[h] = UNIT ? ld[0][i] : coef[0] * ld[0][i];
             } else {
-                v[h] = coef[0] * ld[0][i];
+                v[h] = UNIT ? ld[0][i] : coef[0] * ld[0][i];
 #pragma unroll
                 for (int t = 1; t < NT; ++t) v[h] = __builtin_fma(coef[t], ld[t][i], v[h]);
             }
@@ -236,7 +237,7 @@ struct State {
     Smem<CF>* S;
     const Product* P;
     int tid, nA, nB, nk, kfull;
-    bool plainA, plainB;       // single term with coefficient +1: staged as loaded
+    bool unitA, unitB;         // the first coefficient is +1
     bool early;                // first of the two waves of its SIMD
     double coefA[NTA], coefB[NTB];
     const double *safeA, *safeB;
@@ -269,12 +270,12 @@ struct State {
     }
 
     // operand sums of register set SET into LDS buffer BUF
-    // PLAIN: both operands are single terms with coefficient +1 and are stored as loaded
-    template <int SET, int BUF, bool FAST, bool PLAIN>
+    // UNIT: the first coefficient of both operand sums is +1 (a single term is then stored as loaded)
+    template <int SET, int BUF, bool FAST, bool UNIT>
     __device__ __forceinline__ void stage() {
         if (FAST || issued_fast[SET]) {
-            stage_fast<AMODE, NTA, KT, VA, PLAIN>(la[SET], ba.stage + BUF * TILE, coefA);
-            stage_fast<BMODE, NTB, KT, VB, PLAIN>(lb[SET], bb.stage + BUF * TILE, coefB);
+            stage_fast<AMODE, NTA, KT, VA, UNIT>(la[SET], ba.stage + BUF * TILE, coefA);
+            stage_fast<BMODE, NTB, KT, VB, UNIT>(lb[SET], bb.stage + BUF * TILE, coefB);
         } else {
             stage_checked<AMODE, NTA, KT>(la[SET], pa[SET], &S->a[BUF][0], coefA, tid);
             stage_checked<BMODE, NTB, KT>(lb[SET], pb[SET], &S->b[BUF][0], coefB, tid);
@@ -319,18 +320,18 @@ struct State {
     //        step ago), and set CUR ^ 1 (k-step step + 1, issued one step ago) is stored to LDS buffer CUR ^ 1.
     // D = 1: the loads of step + 1 are issued and, after the last group, stored.
     // ROLE: 0 = first wave of the SIMD, 1 = second, 2 = decided at run time (member `early`).
-    template <int CUR, int DONE, int ROLE, bool FAST, bool PLAIN>
+    template <int CUR, int DONE, int ROLE, bool FAST, bool UNIT>
     __device__ __forceinline__ void between_groups(int step) {
         constexpr int NXT = CUR ^ 1;
         constexpr int ISET = (D == 2) ? CUR : 0, SSET = (D == 2) ? NXT : 0, ISLOT = (D == 2) ? CUR : NXT;
         if constexpr (ROLE != 1 && DONE == CF::STAGE_EARLY) {
             pin();
-            if (ROLE == 0 || early) stage<SSET, NXT, FAST, PLAIN>();
+            if (ROLE == 0 || early) stage<SSET, NXT, FAST, UNIT>();
             pin();
         }
         if constexpr (ROLE != 0 && DONE == CF::STAGE_LATE) {
             pin();
-            if (ROLE == 1 || !early) stage<SSET, NXT, FAST, PLAIN>();
+            if (ROLE == 1 || !early) stage<SSET, NXT, FAST, UNIT>();
             pin();
         }
         if constexpr (ROLE != 1 && DONE == 0) {
@@ -347,29 +348,29 @@ struct State {
 
     // instruction groups Q .. NQ-1 of the k-step in LDS buffer CUR; the fragments of group Q are in af/bf[Q % 2] and
     // those of group Q + 1 are read while group Q multiplies
-    template <int CUR, int Q, int ROLE, bool FAST, bool PLAIN>
+    template <int CUR, int Q, int ROLE, bool FAST, bool UNIT>
     __device__ __forceinline__ void groups(double (&af)[2][4], double (&bf)[2][8], int step) {
         if constexpr (Q < NQ) {
             if constexpr (Q + 1 < NQ) read_frags<CUR, Q + 1>(af[(Q + 1) & 1], bf[(Q + 1) & 1]);
             multiply(af[Q & 1], bf[Q & 1]);
-            between_groups<CUR, Q + 1, ROLE, FAST, PLAIN>(step);
-            groups<CUR, Q + 1, ROLE, FAST, PLAIN>(af, bf, step);
+            between_groups<CUR, Q + 1, ROLE, FAST, UNIT>(step);
+            groups<CUR, Q + 1, ROLE, FAST, UNIT>(af, bf, step);
         }
     }
 
     // One k-step.  The scatter entries of k-step step + D + 1 are fetched first (so that waiting for them at the end
     // of the step does not wait for the gather issued after them) and stored to the free table slot at the end.
-    template <int CUR, int ROLE, bool FAST, bool PLAIN>
+    template <int CUR, int ROLE, bool FAST, bool UNIT>
     __device__ __forceinline__ void step_body(int step) {
         constexpr int ESLOT = (D == 2) ? (CUR ^ 1) : CUR;
         const int kn = (step + D + 1) * KT;
         const bool have = kn < ent_limit;
         const int64_t raw_entry = ent_ptr[have ? kn : 0];  // unconditional load: ent_ptr always points at readable memory
 
-        between_groups<CUR, 0, ROLE, FAST, PLAIN>(step);
+        between_groups<CUR, 0, ROLE, FAST, UNIT>(step);
         double af[2][4], bf[2][8];
         read_frags<CUR, 0>(af[0], bf[0]);
-        groups<CUR, 0, ROLE, FAST, PLAIN>(af, bf, step);
+        groups<CUR, 0, ROLE, FAST, UNIT>(af, bf, step);
 
         ent_dst[ESLOT ? ent_stride : 0] = have ? raw_entry * 8 : kSentinel;  // every thread stores: no branch around the wait
         __syncthreads();
@@ -378,11 +379,11 @@ struct State {
     // k-steps [0, end) (end even) of a tile whose gathers up to k-step end + D - 1 need no padding checks.  The
     // wave's role is a compile-time property of this loop and there is no control flow inside it, so the compiler's
     // wait counts for the loads in flight are exact.
-    template <int ROLE, bool PLAIN>
+    template <int ROLE, bool UNIT>
     __device__ __forceinline__ void run_fast(int end) {
         for (int step = 0; step < end; step += 2) {
-            step_body<0, ROLE, true, PLAIN>(step);
-            step_body<1, ROLE, true, PLAIN>(step + 1);
+            step_body<0, ROLE, true, UNIT>(step);
+            step_body<1, ROLE, true, UNIT>(step + 1);
         }
     }
 
@@ -431,8 +432,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     st.nB = nB;
     st.nk = (int)((P.kb + KT - 1) / KT);
     st.nk += st.nk & 1;  // the k loop runs two steps per trip; a k-step past the end gathers only zero padding
-    st.plainA = nA == 1 && P.A.coef[0] == 1.0;
-    st.plainB = nB == 1 && P.B.coef[0] == 1.0;
+    st.unitA = P.A.coef[0] == 1.0;
+    st.unitB = P.B.coef[0] == 1.0;
 #pragma unroll
     for (int t = 0; t < NTA; ++t) st.coefA[t] = P.A.coef[t];
 #pragma unroll
@@ -550,13 +551,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     int nfast = st.kfull - D;
     nfast = nfast < 2 ? 0 : (nfast & ~1);
     if (nfast > 0) {
-        constexpr bool kPlainLoop = NTA == 1 && NTB == 1;  // a loop of its own for operands stored exactly as loaded
         const bool role0 = __builtin_amdgcn_readfirstlane(wm) == 0;
-        if (kPlainLoop && st.plainA && st.plainB) {
+        if (CF::EXACT && st.unitA && st.unitB) {  // a loop of its own: no multiply (or no arithmetic at all) per element
             if (role0)
-                st.template run_fast<0, kPlainLoop>(nfast);
+                st.template run_fast<0, CF::EXACT>(nfast);
             else
-                st.template run_fast<1, kPlainLoop>(nfast);
+                st.template run_fast<1, CF::EXACT>(nfast);
         } else {
             if (role0)
                 st.template run_fast<0, false>(nfast);

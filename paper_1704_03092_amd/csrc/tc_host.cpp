@@ -116,24 +116,18 @@ int64_t min_stride(const std::vector<Dim>& bundle, int which) {
 }
 
 // Pairs (2q, 2q+1) of consecutive entries of `lane` (the bundle the gather lanes run along) are contiguous in
-// memory, and every pair starts at an even element offset, iff the bundle's fastest dimension has stride 1 and
-// even length and every other stride of the tensor (rest of that bundle and the whole other bundle) is even.
-bool pairs_contiguous(const std::vector<Dim>& lane, const std::vector<Dim>& other, int which) {
+// memory iff the bundle's fastest dimension has stride 1 and no pair straddles its end: its length is even, or it
+// is the bundle's only dimension (the odd last entry then sits in a ragged tile, which is gathered entry by entry).
+// Pairs are only 8-byte aligned in general; the kernel's 16-byte loads do not need more.
+bool pairs_contiguous(const std::vector<Dim>& lane, int which) {
     auto stride = [which](const Dim& d) { return which == 0 ? d.sA : which == 1 ? d.sB : d.sC; };
-    bool first = true;
+    int nontrivial = 0;
+    for (const Dim& d : lane) nontrivial += d.len > 1;
     for (const Dim& d : lane) {
         if (d.len <= 1) continue;
-        if (first) {
-            if (stride(d) != 1 || d.len % 2 != 0) return false;
-            first = false;
-        } else if (stride(d) % 2 != 0) {
-            return false;
-        }
+        return stride(d) == 1 && (d.len % 2 == 0 || nontrivial == 1);
     }
-    if (first) return false;  // the bundle has a single entry: nothing to pair
-    for (const Dim& d : other)
-        if (d.len > 1 && stride(d) % 2 != 0) return false;
-    return true;
+    return false;  // the bundle has a single entry: nothing to pair
 }
 
 void order_bundle(std::vector<Dim>& bundle, int which) {
@@ -222,6 +216,18 @@ void add_term(Operand& op, int64_t roff, int64_t coff, double coef) {
     ++op.nterms;
 }
 
+// Put a term with coefficient +1 first (every Strassen operand sum has one): the kernel then starts the sum from
+// the gathered element itself instead of a product.
+void lead_with_plus(Operand& op) {
+    for (int t = 0; t < op.nterms; ++t)
+        if (op.coef[t] == 1.0) {
+            std::swap(op.roff[0], op.roff[t]);
+            std::swap(op.coff[0], op.coff[t]);
+            std::swap(op.coef[0], op.coef[t]);
+            return;
+        }
+}
+
 // Kernel family of a product: sums of one, two or four terms on both sides have kernels specialised for exactly
 // those counts (key 8 * n_a + n_b); a three-term sum (a four-term sum that lost a block to the zero padding) runs
 // in the family that counts terms at run time (key 0).
@@ -279,8 +285,8 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     order_bundle(p->J, p->b_mode == 0 ? 1 : 2);
     order_bundle(p->P, p->a_mode == 1 ? 0 : (p->b_mode == 1 ? 1 : 0));
 
-    p->a_vec = p->a_mode == 0 ? pairs_contiguous(p->I, p->P, 0) : pairs_contiguous(p->P, p->I, 0);
-    p->b_vec = p->b_mode == 0 ? pairs_contiguous(p->J, p->P, 1) : pairs_contiguous(p->P, p->J, 1);
+    p->a_vec = pairs_contiguous(p->a_mode == 0 ? p->I : p->P, 0);
+    p->b_vec = pairs_contiguous(p->b_mode == 0 ? p->J : p->P, 1);
 
     // ---- Strassen partition of the matrix view (Sec. 3) ----
     p->level_requested = level;
@@ -398,6 +404,8 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
                         add_term(e.pr.C, bi * p->mb, bj * p->nb, W[r][bi * g + bj]);
                         e.view.c_row[e.view.n_c] = bi, e.view.c_col[e.view.n_c] = bj, e.view.c_sign[e.view.n_c] = W[r][bi * g + bj], ++e.view.n_c;
                     }
+            lead_with_plus(e.pr.A);
+            lead_with_plus(e.pr.B);
             // a product whose operand sum or destination set lies wholly in the zero padding contributes nothing
             if (e.view.n_a == 0 || e.view.n_b == 0 || e.view.n_c == 0) continue;
             list.push_back(e);

@@ -49,7 +49,7 @@ struct FusedConfig {
     int nta, ntb;         // terms of the A and B sums if every product of the launch has exactly that many (1 or 2 each);
                           // 0, 0: up to four terms, counted at run time
     int a_vec, b_vec;     // consecutive entry pairs along the lane direction are contiguous and evenly placed
-    int a_space, b_space; // 0: caller's tensor, 1: workspace (for the pointer alignment check)
+    int a_space, b_space; // 0: caller's tensor, 1: workspace
     int c_mode;           // 0: the destination is contiguous along its rows (free bundle I), 1: along its columns
 };
 
