@@ -548,7 +548,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     // k-steps whose gathers need no padding checks run in a loop specialised for the wave's role on its SIMD
     // (wm = 0: first, wm = 1: second); the remaining ones (ragged edge, zero padding, the last D steps) decide per step.
     st.early = wm == 0;
-    int nfast = st.kfull - D;
+    // (sums whose terms are counted at run time only occur for blocks a few tiles wide: they take the general loop)
+    int nfast = CF::EXACT ? st.kfull - D : 0;
     nfast = nfast < 2 ? 0 : (nfast & ~1);
     if (nfast > 0) {
         const bool role0 = __builtin_amdgcn_readfirstlane(wm) == 0;

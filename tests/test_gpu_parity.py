@@ -100,6 +100,24 @@ def test_random_contractions_random_layouts(gpu):
         _check(gpu, A, B, C, rng.choice([1.0, -2.0]), rng.choice([0.0, 1.0, 3.0]), level, variant, exact=bool(trial % 2))
 
 
+@pytest.mark.parametrize("idxA,idxB", [("ik", "kj"), ("ki", "kj"), ("ik", "jk"), ("ki", "jk")])
+def test_midsize_every_kernel_family(gpu, idxA, idxB):
+    """Sizes at which the padding-free loops of the fused kernel run (several full 128 x 128 tiles and k-steps per
+    Strassen block at level 2) next to ragged tiles, for the four combinations of gather direction; at levels 1 and 2
+    the products cover every exact (terms of A, terms of B) kernel family.  Once with even extents (pair-wise
+    gathers, 16-byte aligned), once with an odd leading dimension (pairs only 8-byte aligned), once with odd extents."""
+    for (m, n, k), pad, kind in (((672, 608, 704), 0, "uniform"), ((672, 608, 704), 1, "smallint"), ((645, 583, 657), 0, "uniform")):
+        lengths = {"i": m, "j": n, "k": k}
+        tens = []
+        for tid, idx in enumerate((idxA, idxB, "ij")):
+            lens = [lengths[c] for c in idx]
+            st = strides_for_order(lens, list(range(len(idx))), pad=pad)
+            tens.append(workloads.make_tensor(idx, lengths, 77 + tid, tid, kind, st))
+        A, B, C = tens
+        for level, variant in ((0, "abc"), (1, "abc"), (2, "abc"), (1, "naive"), (2, "ab")):
+            _check(gpu, A, B, C, 1.0, 1.0, level, variant, exact=(kind == "smallint"))
+
+
 def test_benchmark_index_strings_reduced_sizes(gpu):
     cfgs = workloads.configs()
     small = {
