@@ -52,7 +52,7 @@ typedef enum {
     TC_ERR_LABEL = -3,     /* label repeated inside a tensor, or not in exactly two tensors */
     TC_ERR_LENGTH = -4,    /* negative length, or one label with two different lengths */
     TC_ERR_STRIDE = -5,    /* negative stride, zero stride on a dimension longer than 1, or C's elements may overlap */
-    TC_ERR_LEVEL = -6,     /* level not in {0, 1, 2} */
+    TC_ERR_LEVEL = -6,     /* level not in {0, 1, 2} and not TC_LEVEL_AUTO */
     TC_ERR_VARIANT = -7,   /* unknown variant */
     TC_ERR_WORKSPACE = -8, /* workspace is NULL although tc_plan_workspace_bytes() > 0 */
     TC_ERR_HIP = -9,       /* a HIP runtime call failed (no device, out of memory, launch failure) */
@@ -61,6 +61,11 @@ typedef enum {
 } tc_status_t;
 
 #define TC_MAX_NDIM 16
+
+/* Sec. 5 ("Performance Model") lets the library choose: pass TC_LEVEL_AUTO and/or TC_VARIANT_AUTO to tc_plan() and
+ * the plan takes the level in {0, 1, 2} and/or the variant with the smallest modelled time (tc_plan_predict). */
+#define TC_LEVEL_AUTO (-1)
+#define TC_VARIANT_AUTO (-1)
 
 /* One tensor of the contraction (Sec. 2.3 "Tensor" and "General stride layouts").
  * idx holds ndim single-character labels, e.g. "aebf" (not necessarily NUL-terminated). */
@@ -103,6 +108,30 @@ typedef struct {
     int launch;     /* index of the kernel launch that runs this product */
 } tc_product_t;
 
+/* Parameters of the performance model (Sec. 5, notation table): tau_a = 1 / (rho_a * peak_flops),
+ * tau_b = 8 / (rho_b * bandwidth).  The arithmetic penalty rho_a depends on how many blocks the larger operand sum
+ * of a product has (1, 2, 4: index 0, 1, 2), which is what makes this kernel slower; t_launch is added per kernel
+ * launch; the arithmetic term counts whole waves of `units` 128 x 128 tiles, each wave with a fixed cost t_tile
+ * (filling and draining a tile's pipeline). */
+typedef struct {
+    double peak_flops;  /* flop/s of the device */
+    double rho_a[3];
+    double bandwidth;   /* bytes/s */
+    double rho_b;
+    double t_launch;    /* seconds */
+    double t_tile;      /* seconds per wave of tiles */
+    int units;          /* tiles that run at the same time (compute units) */
+    int reserved[3];
+} tc_model_params_t;
+
+/* Modelled time of one tc_contract() with beta != 0, in seconds, split as in Sec. 5 eq. (2)-(4):
+ * arith = W_a^x T_a^x (whole waves of tiles), c_update = W_m^{C x} T_m^{C x} (destination updates of the products),
+ * temporaries = the T_m^{+} terms (element-wise passes of the AB and Naive variants), launch = launches * t_launch.
+ * Reading A and B is taken as hidden behind the matrix cores. */
+typedef struct {
+    double total, arith, c_update, temporaries, launch;
+} tc_model_time_t;
+
 /* Build a plan: classify labels into bundles (Sec. 2.3), choose the order inside each bundle, compute the
  * scatter and block scatter vectors on the device (planner kernel, enqueued on `stream`, a hipStream_t or NULL),
  * and schedule the 1 / 7 / 49 products of level 0 / 1 / 2 (Sec. 2.2 eq. (allops), Sec. 3 eq. (straprim1)).
@@ -126,6 +155,11 @@ int tc_contract(const tc_plan_t *plan, double alpha, const double *A_dev, const 
 int tc_destroy(tc_plan_t *plan);
 
 const char *tc_strerror(int status);
+
+/* Performance model (Sec. 5).  tc_model_defaults() fills the parameters measured on MI355X; tc_plan_predict()
+ * evaluates the model for the plan's schedule (params == NULL: the defaults).  Host-only, no HIP call. */
+int tc_model_defaults(tc_model_params_t *out);
+int tc_plan_predict(const tc_plan_t *plan, const tc_model_params_t *params, tc_model_time_t *out);
 
 /* Inspection (tests, tools). */
 int tc_plan_info(const tc_plan_t *plan, tc_plan_info_t *out);

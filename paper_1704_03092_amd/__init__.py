@@ -4,6 +4,8 @@ from .binding import (  # noqa: F401
     TcError,
     Plan,
     VARIANTS,
+    TC_LEVEL_AUTO,
+    TC_VARIANT_AUTO,
     build,
     lib_path,
     load_library,
@@ -11,6 +13,8 @@ from .binding import (  # noqa: F401
     tc_destroy,
     tc_plan,
     tc_plan_info,
+    tc_plan_predict,
+    tc_model_defaults,
     tc_plan_schedule,
     tc_plan_vector,
     tc_plan_workspace_bytes,

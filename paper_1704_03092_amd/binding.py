@@ -16,7 +16,9 @@ _ROOT = os.path.dirname(_HERE)
 _LIB = os.path.join(_HERE, "libstrassen_tc.so")
 _lib = None
 
-VARIANTS = {"naive": 0, "ab": 1, "abc": 2}
+VARIANTS = {"naive": 0, "ab": 1, "abc": 2, "auto": -1}
+TC_LEVEL_AUTO = -1
+TC_VARIANT_AUTO = -1
 TC_MAX_NDIM = 16
 
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-std=c++17", "-shared",
@@ -84,6 +86,16 @@ class tc_product_t(ctypes.Structure):
                [("c_first", ctypes.c_int * 4), ("launch", ctypes.c_int)]
 
 
+class tc_model_params_t(ctypes.Structure):
+    _fields_ = [("peak_flops", ctypes.c_double), ("rho_a", ctypes.c_double * 3), ("bandwidth", ctypes.c_double), ("rho_b", ctypes.c_double),
+                ("t_launch", ctypes.c_double), ("t_tile", ctypes.c_double), ("units", ctypes.c_int), ("reserved", ctypes.c_int * 3)]
+
+
+class tc_model_time_t(ctypes.Structure):
+    _fields_ = [("total", ctypes.c_double), ("arith", ctypes.c_double), ("c_update", ctypes.c_double), ("temporaries", ctypes.c_double),
+                ("launch", ctypes.c_double)]
+
+
 class TcError(RuntimeError):
     def __init__(self, status: int, what: str):
         super().__init__(f"{what}: {tc_strerror(status)} ({status})")
@@ -115,6 +127,10 @@ def load_library():
         lib.tc_plan_info.argtypes = [vp, ctypes.POINTER(tc_plan_info_t)]
         lib.tc_plan_schedule.restype = ci
         lib.tc_plan_schedule.argtypes = [vp, ci, ctypes.POINTER(tc_product_t)]
+        lib.tc_model_defaults.restype = ci
+        lib.tc_model_defaults.argtypes = [ctypes.POINTER(tc_model_params_t)]
+        lib.tc_plan_predict.restype = ci
+        lib.tc_plan_predict.argtypes = [vp, ctypes.POINTER(tc_model_params_t), ctypes.POINTER(tc_model_time_t)]
         lib.tc_plan_vector.restype = ctypes.c_int64
         lib.tc_plan_vector.argtypes = [vp, ci, vp, ctypes.c_int64]
         _lib = lib
@@ -210,6 +226,28 @@ def tc_plan_info(plan: Plan) -> dict:
     for k in "IJP":
         d[k] = d[k].decode()
     return d
+
+
+def tc_model_defaults() -> dict:
+    mp = tc_model_params_t()
+    rc = load_library().tc_model_defaults(ctypes.byref(mp))
+    if rc != 0:
+        raise TcError(rc, "tc_model_defaults")
+    return {"peak_flops": mp.peak_flops, "rho_a": list(mp.rho_a), "bandwidth": mp.bandwidth, "rho_b": mp.rho_b, "t_launch": mp.t_launch,
+            "t_tile": mp.t_tile, "units": mp.units}
+
+
+def tc_plan_predict(plan: Plan, params: Optional[dict] = None) -> dict:
+    """Modelled seconds of one tc_contract (beta != 0); params as returned by tc_model_defaults (None: the defaults)."""
+    mp = None
+    if params is not None:
+        mp = tc_model_params_t(params["peak_flops"], (ctypes.c_double * 3)(*params["rho_a"]), params["bandwidth"], params["rho_b"],
+                               params["t_launch"], params["t_tile"], int(params["units"]))
+    out = tc_model_time_t()
+    rc = load_library().tc_plan_predict(plan.handle, ctypes.byref(mp) if mp is not None else None, ctypes.byref(out))
+    if rc != 0:
+        raise TcError(rc, "tc_plan_predict")
+    return {k: getattr(out, k) for k, _ in tc_model_time_t._fields_}
 
 
 def tc_plan_schedule(plan: Plan) -> list:

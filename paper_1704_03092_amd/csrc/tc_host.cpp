@@ -540,9 +540,97 @@ void copy_labels(char* out, const std::vector<Dim>& b) {
     out[i] = 0;
 }
 
+// ---- performance model (Sec. 5) on the plan's schedule ----
+// Defaults fitted to the measured grid of paper_1704_03092_amd/sweep.py on one MI355X (RMS error of log time 8 %).
+const tc_model_params_t kDefaultModel = {
+    78.6e12,               // published FP64 matrix peak
+    {0.84, 0.79, 0.66},    // fused kernel with 1 / 2 / 4-term operand sums
+    8.0e12,                // HBM3E
+    0.6,                   // element-wise passes and destination updates
+    20.0e-6,               // per launch (with its ramp-up and tail)
+    10.0e-6,               // per wave of tiles: gather tables, pipeline fill, destination update
+    256, {0, 0, 0}};
+
+void predict(const tc_plan_t* p, const tc_model_params_t& mp, tc_model_time_t* out) {
+    const double tau_b = 8.0 / (mp.rho_b * mp.bandwidth);
+    tc_model_time_t t = {0, 0, 0, 0, 0};
+    for (const Step& s : p->steps) {
+        t.launch += mp.t_launch;
+        if (s.kind == STEP_FUSED) {
+            const int64_t tiles_m = (s.rows + 127) / 128, tiles_n = (s.cols + 127) / 128;
+            const int64_t tiles = (int64_t)s.count * tiles_m * tiles_n;
+            int terms = 1;
+            double c_elems = 0;
+            int64_t kb = 0;
+            for (int i = s.first; i < s.first + s.count; ++i) {
+                const Product& q = p->prods[i];
+                terms = std::max(terms, std::max(q.A.nterms, q.B.nterms));
+                kb = q.kb;
+                c_elems += (q.overwrite ? 1.0 : 2.0) * q.C.nterms * (double)q.mb * (double)q.nb;
+            }
+            if (tiles == 0) continue;
+            const double rho = terms <= 1 ? mp.rho_a[0] : terms <= 2 ? mp.rho_a[1] : mp.rho_a[2];
+            const int64_t waves = (tiles + mp.units - 1) / mp.units;
+            t.arith += (double)waves * (mp.units * 2.0 * 128.0 * 128.0 * (double)kb / (rho * mp.peak_flops) + mp.t_tile);
+            t.c_update += c_elems * tau_b;
+        } else {
+            const Product& q = p->prods[s.first];
+            const double elems = (q.A.nterms + (q.overwrite ? 1.0 : 2.0) * q.C.nterms) * (double)s.rows * (double)s.cols;
+            t.temporaries += elems * tau_b;
+        }
+    }
+    t.total = t.arith + t.c_update + t.temporaries + t.launch;
+    *out = t;
+}
+
+// TC_LEVEL_AUTO / TC_VARIANT_AUTO: schedule every candidate on the host, keep the one the model likes best.
+int choose_by_model(const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const tc_tensor_desc_t* C, int* level, int* variant,
+                    const tc_options_t* opts) {
+    tc_options_t o;
+    std::memset(&o, 0, sizeof o);
+    if (opts) o = *opts;
+    o.host_only = 1;
+    double best = 0;
+    int best_level = -1, best_variant = -1;
+    for (int L = 0; L <= 2; ++L) {
+        if (*level != TC_LEVEL_AUTO && L != *level) continue;
+        for (int v = TC_VARIANT_ABC; v >= TC_VARIANT_NAIVE; --v) {
+            if (*variant != TC_VARIANT_AUTO && v != *variant) continue;
+            if (L == 0 && v != TC_VARIANT_ABC && *variant == TC_VARIANT_AUTO) continue;  // the variants coincide at level 0
+            tc_plan_t cand;
+            int rc = build_plan(&cand, A, B, C, L, v, &o, nullptr);
+            if (rc != TC_OK) return rc;
+            if (cand.level != L) continue;  // lowered: the same schedule as a smaller L
+            tc_model_time_t t;
+            predict(&cand, kDefaultModel, &t);
+            if (best_level < 0 || t.total < best) best = t.total, best_level = L, best_variant = v;
+        }
+    }
+    if (best_level < 0) best_level = 0, best_variant = (*variant == TC_VARIANT_AUTO) ? TC_VARIANT_ABC : *variant;
+    *level = best_level;
+    *variant = best_variant;
+    return TC_OK;
+}
+
 }  // namespace
 
 extern "C" {
+
+int tc_model_defaults(tc_model_params_t* out) {
+    if (!out) return TC_ERR_NULL;
+    *out = kDefaultModel;
+    return TC_OK;
+}
+
+int tc_plan_predict(const tc_plan_t* plan, const tc_model_params_t* params, tc_model_time_t* out) {
+    if (!plan || !out) return TC_ERR_NULL;
+    const tc_model_params_t& mp = params ? *params : kDefaultModel;
+    if (!(mp.peak_flops > 0) || !(mp.bandwidth > 0) || !(mp.rho_b > 0) || mp.units <= 0) return TC_ERR_STATE;
+    for (int i = 0; i < 3; ++i)
+        if (!(mp.rho_a[i] > 0)) return TC_ERR_STATE;
+    predict(plan, mp, out);
+    return TC_OK;
+}
 
 int tc_plan_ex(tc_plan_t** plan_out, const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const tc_tensor_desc_t* C, int level,
                int variant, const tc_options_t* opts, void* stream) {
@@ -550,6 +638,12 @@ int tc_plan_ex(tc_plan_t** plan_out, const tc_tensor_desc_t* A, const tc_tensor_
     *plan_out = nullptr;
     tc_plan_t* p = nullptr;
     try {
+        if (level == TC_LEVEL_AUTO || variant == TC_VARIANT_AUTO) {
+            if (level != TC_LEVEL_AUTO && (level < 0 || level > 2)) return TC_ERR_LEVEL;
+            if (variant != TC_VARIANT_AUTO && (variant < TC_VARIANT_NAIVE || variant > TC_VARIANT_ABC)) return TC_ERR_VARIANT;
+            int rc = choose_by_model(A, B, C, &level, &variant, opts);
+            if (rc != TC_OK) return rc;
+        }
         p = new tc_plan_t();
         int rc = build_plan(p, A, B, C, level, variant, opts, stream);
         if (rc != TC_OK) {

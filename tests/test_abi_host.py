@@ -149,3 +149,84 @@ def test_empty_bundles():
     p = _plan(("", (), ()), ("", (), ()), ("", (), ()))  # scalar times scalar
     info = tc.tc_plan_info(p)
     assert (info["m"], info["n"], info["k"]) == (1, 1, 1)
+
+
+def _gemm_desc(m, n, k):
+    return ("ik", (m, k), (1, m)), ("kj", (k, n), (1, k)), ("ij", (m, n), (1, m))
+
+
+def _oracle_prediction(plan, params):
+    """The library's modelled time recomputed by the oracle (oracle.model.granular_time) from the schedule: which
+    products share a launch comes from tc_plan_schedule, everything else from the plan's extents."""
+    import math
+
+    from oracle import model as M
+
+    info = tc.tc_plan_info(plan)
+    sched = tc.tc_plan_schedule(plan)
+    mb, nb, kb = info["mb"], info["nb"], info["kb"]
+    tiles = math.ceil(mb / 128) * math.ceil(nb / 128)
+    fused_c = info["variant"] == 2 or info["level"] == 0
+    launches = []
+    if fused_c:
+        by_launch = {}
+        for e in sched:
+            by_launch.setdefault(e["launch"], []).append(e)
+        for key in sorted(by_launch):
+            launches.append({"kind": "mul", "products": [
+                {"tiles": tiles, "kb": kb, "terms": max(len(e["a"]), len(e["b"])), "c_elems": 2 * len(e["c"]) * mb * nb} for e in by_launch[key]]})
+    else:
+        for e in sched:
+            na, nbt = len(e["a"]), len(e["b"])
+            if info["variant"] == 0:  # Naive: operand sums to TA, TB, then a single-term product
+                launches.append({"kind": "add", "elems": (na + 1) * mb * kb})
+                launches.append({"kind": "add", "elems": (nbt + 1) * kb * nb})
+                na = nbt = 1
+            launches.append({"kind": "mul", "products": [{"tiles": tiles, "kb": kb, "terms": max(na, nbt), "c_elems": mb * nb}]})
+            launches.append({"kind": "add", "elems": (1 + 2 * len(e["c"])) * mb * nb})
+    mp = M.MachineParams(peak_flops=params["peak_flops"], rho_a=params["rho_a"], bandwidth=params["bandwidth"], rho_b=params["rho_b"],
+                         t_launch=params["t_launch"], t_tile=params["t_tile"], units=params["units"])
+    return M.granular_time(launches, mp)
+
+
+@pytest.mark.parametrize("shape", [(4096, 4096, 4096), (1000, 3000, 520), (16384, 16384, 256), (9216, 96, 4096), (300, 200, 100)])
+def test_model_prediction_matches_the_oracle_model(shape):
+    defaults = tc.tc_model_defaults()
+    other = dict(defaults, peak_flops=50e12, rho_a=[0.9, 0.7, 0.5], bandwidth=3e12, rho_b=0.8, t_launch=1e-5, t_tile=3e-5, units=100)
+    for level in (0, 1, 2):
+        for variant in ("abc", "ab", "naive"):
+            plan = _plan(*_gemm_desc(*shape), level=level, variant=variant)
+            for params in (None, other):
+                got = tc.tc_plan_predict(plan, params)
+                want = _oracle_prediction(plan, params or defaults)
+                for key in ("arith", "c_update", "temporaries", "launch", "total"):
+                    assert got[key] == pytest.approx(want[key], rel=1e-12, abs=1e-18), (shape, level, variant, key)
+            tc.tc_destroy(plan)
+
+
+def test_automatic_choice_is_the_argmin_of_the_model():
+    for shape in [(16384, 16384, 16384), (4096, 4096, 4096), (512, 512, 512), (16384, 16384, 256), (9216, 96, 4096), (36864, 2304, 36864)]:
+        desc = _gemm_desc(*shape)
+        times = {}
+        for level in (0, 1, 2):
+            for variant in ("abc", "ab", "naive"):
+                plan = _plan(*desc, level=level, variant=variant)
+                if tc.tc_plan_info(plan)["level"] == level:
+                    times[(level, tc.VARIANTS[variant])] = tc.tc_plan_predict(plan)["total"]
+                tc.tc_destroy(plan)
+        auto = _plan(*desc, level=tc.TC_LEVEL_AUTO, variant="auto")
+        info = tc.tc_plan_info(auto)
+        assert times[(info["level"], info["variant"])] == min(times.values()), (shape, info["level"], info["variant"], times)
+        tc.tc_destroy(auto)
+        # one of the two fixed by the caller
+        auto = _plan(*desc, level=tc.TC_LEVEL_AUTO, variant="ab")
+        info = tc.tc_plan_info(auto)
+        assert info["variant"] == 1 and times[(info["level"], 1)] == min(t for (L, v), t in times.items() if v == 1)
+        tc.tc_destroy(auto)
+        auto = _plan(*desc, level=1, variant="auto")
+        info = tc.tc_plan_info(auto)
+        assert info["level"] == 1 and times[(1, info["variant"])] == min(t for (L, v), t in times.items() if L == 1)
+        tc.tc_destroy(auto)
+    with pytest.raises(tc.TcError) as e:
+        _plan(*_gemm_desc(8, 8, 8), level=5, variant="auto")
+    assert e.value.status == -6

@@ -44,7 +44,7 @@ def _check(gpu, A, B, C, alpha, beta, level, variant, exact=False, **kw):
         assert np.array_equal(got, ref.view()), (level, variant)
     else:
         err = oracle.error_metric(got, ref.view(), oracle.tensor_norm(A), oracle.tensor_norm(B))
-        assert err <= TOL[level], (level, variant, err)
+        assert err <= TOL[info["level"]], (level, variant, err)
     return info
 
 
@@ -116,6 +116,17 @@ def test_midsize_every_kernel_family(gpu, idxA, idxB):
         A, B, C = tens
         for level, variant in ((0, "abc"), (1, "abc"), (2, "abc"), (1, "naive"), (2, "ab")):
             _check(gpu, A, B, C, 1.0, 1.0, level, variant, exact=(kind == "smallint"))
+
+
+def test_automatic_level_and_variant(gpu):
+    """TC_LEVEL_AUTO / TC_VARIANT_AUTO: whatever the model picks, the result is the contraction."""
+    import paper_1704_03092_amd as tc
+
+    for lengths in ({"i": 300, "j": 260, "k": 90}, {"i": 1500, "j": 1400, "k": 1300}):
+        c = workloads.Contraction("g", "ij", "ik", "kj", lengths, seed=9)
+        A, B, C = c.tensors()
+        info = _check(gpu, A, B, C, 1.0, 1.0, tc.TC_LEVEL_AUTO, "auto")
+        assert info["level"] in (0, 1, 2) and info["variant"] in (0, 1, 2) and info["level_requested"] == info["level"]
 
 
 def test_benchmark_index_strings_reduced_sizes(gpu):
