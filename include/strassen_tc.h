@@ -81,7 +81,11 @@ typedef struct {
     int bs_block;   /* entries per block of the block scatter vectors (Sec. 2.3); 0 = default 16 */
     int host_only;  /* 1: analyse and schedule on the host only (no HIP call); the plan cannot run */
     int no_merge;   /* 1: one kernel launch per Strassen product even where destinations are disjoint */
-    int reserved[5];
+    int split_k;    /* level 0 only: 0 or 1 = off; 2..4 = cut the contracted bundle into that many chunks whose products
+                     * run side by side into dense temporaries and are summed into C by one element-wise pass (for
+                     * shapes with too few 128 x 128 tiles to fill the device; needs workspace; not from the paper);
+                     * -1 = as many chunks as the performance model likes best */
+    int reserved[4];
 } tc_options_t;
 
 /* Facts about a plan (tc_plan_info). */
@@ -90,7 +94,7 @@ typedef struct {
     int level_requested;
     int level;            /* level actually executed: lowered while a bundle is shorter than 2^level */
     int variant;
-    int n_products;       /* 1, 7 or 49 */
+    int n_products;       /* 1, 7 or 49 (fewer if blocks lie wholly in the zero padding); the chunks with split_k */
     int n_launches;       /* kernel launches per tc_contract() */
     int bs_block;
     int a_mode, b_mode;   /* 0: stride-1 direction of the operand is its free bundle, 1: the contracted bundle */
@@ -141,7 +145,7 @@ int tc_plan(tc_plan_t **plan_out, const tc_tensor_desc_t *A, const tc_tensor_des
 int tc_plan_ex(tc_plan_t **plan_out, const tc_tensor_desc_t *A, const tc_tensor_desc_t *B, const tc_tensor_desc_t *C,
                int level, int variant, const tc_options_t *opts, void *stream);
 
-/* Bytes of device workspace tc_contract() needs (0 for level 0 and for the ABC variant). */
+/* Bytes of device workspace tc_contract() needs (0 for the ABC variant and for level 0 without split_k). */
 size_t tc_plan_workspace_bytes(const tc_plan_t *plan);
 
 /* C := alpha * A * B + beta * C.  A_dev, B_dev, C_dev, workspace_dev are device pointers owned by the caller;

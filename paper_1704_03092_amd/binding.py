@@ -69,7 +69,8 @@ class tc_tensor_desc_t(ctypes.Structure):
 
 
 class tc_options_t(ctypes.Structure):
-    _fields_ = [("bs_block", ctypes.c_int), ("host_only", ctypes.c_int), ("no_merge", ctypes.c_int), ("reserved", ctypes.c_int * 5)]
+    _fields_ = [("bs_block", ctypes.c_int), ("host_only", ctypes.c_int), ("no_merge", ctypes.c_int), ("split_k", ctypes.c_int),
+                ("reserved", ctypes.c_int * 4)]
 
 
 class tc_plan_info_t(ctypes.Structure):
@@ -182,7 +183,7 @@ class Plan:
 
 
 def tc_plan(A, B, C, level: int = 0, variant="abc", stream=None, bs_block: int = 0, host_only: bool = False,
-            no_merge: bool = False) -> Plan:
+            no_merge: bool = False, split_k: int = 0) -> Plan:
     """A, B, C: (labels, lengths, strides) triples or objects with .idx/.lens/.strides."""
     lib = load_library()
     ds = []
@@ -193,7 +194,7 @@ def tc_plan(A, B, C, level: int = 0, variant="abc", stream=None, bs_block: int =
             ds.append(_desc(*T))
     v = VARIANTS[variant] if isinstance(variant, str) else int(variant)
     out = ctypes.c_void_p()
-    opts = tc_options_t(int(bs_block), int(bool(host_only)), int(bool(no_merge)))
+    opts = tc_options_t(int(bs_block), int(bool(host_only)), int(bool(no_merge)), int(split_k))
     rc = lib.tc_plan_ex(ctypes.byref(out), ctypes.byref(ds[0]), ctypes.byref(ds[1]), ctypes.byref(ds[2]), int(level), v,
                         ctypes.byref(opts), _stream(stream))
     if rc != 0:

@@ -241,11 +241,14 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     if (variant != TC_VARIANT_NAIVE && variant != TC_VARIANT_AB && variant != TC_VARIANT_ABC) return TC_ERR_VARIANT;
     p->bs_block = 16;
     bool no_merge = false;
+    int split = 1;
     if (opts) {
         if (opts->bs_block < 0 || opts->bs_block > (1 << 20)) return TC_ERR_STATE;
         if (opts->bs_block > 0) p->bs_block = opts->bs_block;
         p->host_only = opts->host_only != 0;
         no_merge = opts->no_merge != 0;
+        if (opts->split_k > 4 || opts->split_k < -1) return TC_ERR_STATE;
+        split = std::max(opts->split_k, 1);  // -1 has been resolved by the caller (tc_plan_ex)
     }
     // ---- bundles (Sec. 2.3): every label in exactly two tensors ----
     const tc_tensor_desc_t* T[3] = {A, B, C};
@@ -310,10 +313,19 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     p->bundles[V_RSC] = make_bundle(p->I, 2);
     p->bundles[V_CSC] = make_bundle(p->J, 2);
     const bool empty = p->m == 0 || p->n == 0;
+    // split_k (level 0): chunks of the contracted bundle, each at least 64 entries and a multiple of 16 long
+    int64_t kc = p->k;
+    if (level > 0 || empty) split = 1;
+    while (split > 1 && round_up((p->k + split - 1) / split, 16) < 64) --split;
+    if (split > 1) {
+        kc = round_up((p->k + split - 1) / split, 16);
+        split = (int)((p->k + kc - 1) / kc);
+    }
+    const bool use_S = split > 1;
     const bool use_M = !empty && p->k > 0 && level > 0 && variant != TC_VARIANT_ABC;
     const bool use_T = use_M && variant == TC_VARIANT_NAIVE;
-    p->bundles[V_RSM] = make_dense(use_M ? p->mb : 0, 1);
-    p->bundles[V_CSM] = make_dense(use_M ? p->nb : 0, p->mb);
+    p->bundles[V_RSM] = make_dense(use_M || use_S ? p->mb : 0, 1);
+    p->bundles[V_CSM] = make_dense(use_M ? p->nb : use_S ? split * p->nb : 0, p->mb);  // the chunks' temporaries side by side
     p->bundles[V_RSTA] = make_dense(use_T ? p->mb : 0, 1);
     p->bundles[V_CSTA] = make_dense(use_T ? p->kb : 0, p->mb);
     p->bundles[V_RSTB] = make_dense(use_T ? p->kb : 0, 1);
@@ -328,6 +340,10 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         off += (b.total + p->bs_block - 1) / p->bs_block;
     }
     p->store_entries = off;
+    if (use_S) {
+        p->wsM = 0;
+        p->workspace_bytes = (size_t)(split * p->mb * p->nb) * sizeof(double);
+    }
     if (use_M) {
         int64_t w = 0;
         p->wsM = w;
@@ -366,6 +382,42 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         pr.first_mask = 1;
         p->prods.push_back(pr);
         p->steps.push_back(Step{STEP_LINCOMB, 0, 1, {}, p->m, p->n, p->c_mode == 0 ? 1 : 0, 0});
+    } else if (use_S) {
+        // chunk s: A[:, s kc : (s+1) kc) * B[s kc : (s+1) kc), :] -> temporary s (one launch for all chunks), then
+        // C := beta C + alpha-scaled sum of the temporaries (one element-wise pass)
+        const int first = (int)p->prods.size();
+        for (int s = 0; s < split; ++s) {
+            Product mul;
+            std::memset(&mul, 0, sizeof mul);
+            set_operand(mul.A, vec(V_RSA), vec(V_CSA), p->m, p->k, 0, 0);
+            add_term(mul.A, 0, s * kc, 1.0);
+            set_operand(mul.B, vec(V_RSB), vec(V_CSB), p->k, p->n, 0, 0);
+            add_term(mul.B, s * kc, 0, 1.0);
+            set_operand(mul.C, vec(V_RSM), vec(V_CSM), p->mb, split * p->nb, 1, p->wsM);
+            add_term(mul.C, 0, s * p->nb, 1.0);
+            mul.mb = p->mb, mul.nb = p->nb, mul.kb = kc;
+            mul.first_mask = 1, mul.overwrite = 1;
+            p->prods.push_back(mul);
+            tc_product_t view;
+            std::memset(&view, 0, sizeof view);
+            view.n_a = view.n_b = view.n_c = 1;
+            view.a_sign[0] = view.b_sign[0] = view.c_sign[0] = 1;
+            view.c_first[0] = s == 0;
+            view.launch = 0;
+            p->sched.push_back(view);
+        }
+        tc::FusedConfig cfg{p->a_mode, p->b_mode, 1, 1, p->a_vec, p->b_vec, 0, 0, 0};  // temporaries: contiguous rows
+        p->steps.push_back(Step{STEP_FUSED, first, split, cfg, p->mb, p->nb, 0, 0});
+        Product acc;
+        std::memset(&acc, 0, sizeof acc);
+        set_operand(acc.A, vec(V_RSM), vec(V_CSM), p->mb, split * p->nb, 1, p->wsM);
+        for (int s = 0; s < split; ++s) add_term(acc.A, 0, s * p->nb, 1.0);
+        set_operand(acc.C, vec(V_RSC), vec(V_CSC), p->m, p->n, 0, 0);
+        add_term(acc.C, 0, 0, 1.0);
+        acc.mb = p->mb, acc.nb = p->nb;
+        acc.first_mask = 1;
+        p->prods.push_back(acc);
+        p->steps.push_back(Step{STEP_LINCOMB, first + split, 1, {}, p->mb, p->nb, p->c_mode == 0 ? 1 : 0, 0});
     } else {
         std::vector<std::vector<int>> U, V, W;
         block_tables(level, U, V, W);
@@ -583,6 +635,25 @@ void predict(const tc_plan_t* p, const tc_model_params_t& mp, tc_model_time_t* o
     *out = t;
 }
 
+// split_k = -1: the number of chunks (1..4) with the smallest modelled time
+int choose_split(const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const tc_tensor_desc_t* C, int variant, tc_options_t* o) {
+    tc_options_t t = *o;
+    t.host_only = 1;
+    double best = 0;
+    int best_s = 1;
+    for (int s = 1; s <= 4; ++s) {
+        t.split_k = s;
+        tc_plan_t cand;
+        int rc = build_plan(&cand, A, B, C, 0, variant, &t, nullptr);
+        if (rc != TC_OK) return rc;
+        tc_model_time_t mt;
+        predict(&cand, kDefaultModel, &mt);
+        if (s == 1 || mt.total < best) best = mt.total, best_s = s;
+    }
+    o->split_k = best_s;
+    return TC_OK;
+}
+
 // TC_LEVEL_AUTO / TC_VARIANT_AUTO: schedule every candidate on the host, keep the one the model likes best.
 int choose_by_model(const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const tc_tensor_desc_t* C, int* level, int* variant,
                     const tc_options_t* opts) {
@@ -590,6 +661,13 @@ int choose_by_model(const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const 
     std::memset(&o, 0, sizeof o);
     if (opts) o = *opts;
     o.host_only = 1;
+    tc_options_t o0 = o;  // level 0 competes with the split it would run with
+    if (o.split_k == -1) {
+        o0.split_k = 1;
+        int rc = choose_split(A, B, C, TC_VARIANT_ABC, &o0);
+        if (rc != TC_OK) return rc;
+        o.split_k = 1;
+    }
     double best = 0;
     int best_level = -1, best_variant = -1;
     for (int L = 0; L <= 2; ++L) {
@@ -598,7 +676,7 @@ int choose_by_model(const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const 
             if (*variant != TC_VARIANT_AUTO && v != *variant) continue;
             if (L == 0 && v != TC_VARIANT_ABC && *variant == TC_VARIANT_AUTO) continue;  // the variants coincide at level 0
             tc_plan_t cand;
-            int rc = build_plan(&cand, A, B, C, L, v, &o, nullptr);
+            int rc = build_plan(&cand, A, B, C, L, v, L == 0 ? &o0 : &o, nullptr);
             if (rc != TC_OK) return rc;
             if (cand.level != L) continue;  // lowered: the same schedule as a smaller L
             tc_model_time_t t;
@@ -644,8 +722,18 @@ int tc_plan_ex(tc_plan_t** plan_out, const tc_tensor_desc_t* A, const tc_tensor_
             int rc = choose_by_model(A, B, C, &level, &variant, opts);
             if (rc != TC_OK) return rc;
         }
+        tc_options_t o;
+        std::memset(&o, 0, sizeof o);
+        if (opts) o = *opts;
+        if (o.split_k == -1) {
+            o.split_k = 1;
+            if (level == 0) {
+                int rc = choose_split(A, B, C, variant, &o);
+                if (rc != TC_OK) return rc;
+            }
+        }
         p = new tc_plan_t();
-        int rc = build_plan(p, A, B, C, level, variant, opts, stream);
+        int rc = build_plan(p, A, B, C, level, variant, &o, stream);
         if (rc != TC_OK) {
             release(p);
             return rc;

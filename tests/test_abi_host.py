@@ -230,3 +230,37 @@ def test_automatic_choice_is_the_argmin_of_the_model():
     with pytest.raises(tc.TcError) as e:
         _plan(*_gemm_desc(8, 8, 8), level=5, variant="auto")
     assert e.value.status == -6
+
+
+def test_split_k_schedule():
+    desc = _gemm_desc(9216, 96, 4096)
+    plain = _plan(*desc)
+    assert tc.tc_plan_workspace_bytes(plain) == 0 and tc.tc_plan_info(plain)["n_launches"] == 1
+    t1 = tc.tc_plan_predict(plain)["total"]
+    tc.tc_destroy(plain)
+    times = {1: t1}
+    for s in (2, 3, 4):
+        plan = _plan(*desc, split_k=s)
+        info = tc.tc_plan_info(plan)
+        assert info["n_products"] == s and info["n_launches"] == 2 and info["level"] == 0
+        assert tc.tc_plan_workspace_bytes(plan) == s * 9216 * 96 * 8
+        times[s] = tc.tc_plan_predict(plan)["total"]
+        tc.tc_destroy(plan)
+    auto = _plan(*desc, split_k=-1)
+    info = tc.tc_plan_info(auto)
+    assert times[info["n_products"]] == min(times.values()) and info["n_products"] > 1  # 72 tiles on 256 units: splitting pays
+    tc.tc_destroy(auto)
+    # chunks shorter than 64 entries are not made; Strassen levels ignore the option; out-of-range values are refused
+    short = _plan(*_gemm_desc(256, 256, 90), split_k=4)
+    assert tc.tc_plan_info(short)["n_products"] == 1 and tc.tc_plan_workspace_bytes(short) == 0
+    tc.tc_destroy(short)
+    lvl1 = _plan(*desc, level=1, variant="abc", split_k=4)
+    assert tc.tc_plan_info(lvl1)["n_products"] == 7 and tc.tc_plan_workspace_bytes(lvl1) == 0
+    tc.tc_destroy(lvl1)
+    with pytest.raises(tc.TcError) as e:
+        _plan(*desc, split_k=5)
+    assert e.value.status == -10
+    # a large square problem has tiles enough: the model keeps it whole
+    big = _plan(*_gemm_desc(8192, 8192, 8192), split_k=-1)
+    assert tc.tc_plan_info(big)["n_products"] == 1
+    tc.tc_destroy(big)

@@ -30,11 +30,11 @@ def gpu():
     return tc
 
 
-def _modes(cfg):
-    return [(l, v) for (l, v) in cfg.modes]
+def _modes(cfg, extra=()):
+    return [(l, v, {}) for (l, v) in cfg.modes] + list(extra)
 
 
-def _run_modes(tc, cfg, sampled):
+def _run_modes(tc, cfg, sampled, extra=()):
     import torch
 
     t0 = time.time()
@@ -47,8 +47,8 @@ def _run_modes(tc, cfg, sampled):
     view = None
     ref_rows = {}
     full_ref = None
-    for level, variant in _modes(cfg):
-        plan = tc.tc_plan(A, B, C, level, variant, st)
+    for level, variant, kw in _modes(cfg, extra):
+        plan = tc.tc_plan(A, B, C, level, variant, st, **kw)
         info = tc.tc_plan_info(plan)
         orders = (list(info["I"]), list(info["J"]), list(info["P"]))
         if view is None:
@@ -56,6 +56,8 @@ def _run_modes(tc, cfg, sampled):
         nbytes = tc.tc_plan_workspace_bytes(plan)
         ws = torch.full((max(nbytes // 8, 1),), float("nan"), dtype=torch.float64, device="cuda") if nbytes else None
         dC = dC0.clone()
+        level = info["level"]
+        variant = f"{variant}{kw if kw else ''}"
         print(f"[{cfg.name}] level {level} {variant}: launching ({info['n_launches']} launches)", flush=True)
         tc.tc_contract(plan, cfg.alpha, dA, dB, cfg.beta, dC, ws, st)  # warm-up + result
         torch.cuda.synchronize()
@@ -125,7 +127,9 @@ def test_cfg3(gpu):
 
 
 def test_cfg4a(gpu):
-    _run_modes(gpu, workloads.configs()["cfg4a"], sampled=False)
+    # 72 tiles of 128 x 128 on 256 compute units: also with the contracted bundle cut into chunks, and with everything automatic
+    _run_modes(gpu, workloads.configs()["cfg4a"], sampled=False,
+               extra=[(0, "abc", {"split_k": 2}), (0, "abc", {"split_k": -1}), (-1, "auto", {"split_k": -1})])
 
 
 def test_cfg4b(gpu):

@@ -129,6 +129,25 @@ def test_automatic_level_and_variant(gpu):
         assert info["level"] in (0, 1, 2) and info["variant"] in (0, 1, 2) and info["level_requested"] == info["level"]
 
 
+def test_split_k(gpu):
+    """Level 0 with the contracted bundle cut into chunks (temporaries + one summing pass), also through general strides."""
+    cfg = workloads.scaled(workloads.configs()["cfg4a"], {"a": 13, "b": 21, "c": 12, "d": 37, "e": 19})  # k = 703
+    for kind in ("uniform", "smallint"):
+        A, B, C = cfg.tensors(kind=kind)
+        for split in (2, 3, 4, -1):
+            info = _check(gpu, A, B, C, 1.5, -0.5, 0, "abc", exact=(kind == "smallint"), split_k=split)
+            assert split == -1 or info["n_products"] == split
+    c = workloads.Contraction("g", "ij", "ik", "kj", {"i": 300, "j": 96, "k": 1000}, seed=3)
+    A, B, C = c.tensors()
+    C.data[:] = np.nan  # beta = 0 must not read C
+    run_gpu, logical = gpu
+    got_flat, info = run_gpu(A, B, C, 2.0, 0.0, 0, "abc", split_k=4)
+    ref = from_dense("ij", np.zeros((300, 96)))
+    oracle.contract_matrix(A, B, ref, 2.0, 0.0)
+    assert info["n_products"] == 4
+    assert oracle.error_metric(logical(C, got_flat), ref.view(), oracle.tensor_norm(A), oracle.tensor_norm(B)) <= TOL[0]
+
+
 def test_benchmark_index_strings_reduced_sizes(gpu):
     cfgs = workloads.configs()
     small = {
