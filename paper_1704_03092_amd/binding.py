@@ -16,7 +16,7 @@ _ROOT = os.path.dirname(_HERE)
 _LIB = os.path.join(_HERE, "libstrassen_tc.so")
 _lib = None
 
-VARIANTS = {"naive": 0, "ab": 1, "abc": 2, "auto": -1}
+VARIANTS = {"naive": 0, "ab": 1, "abc": 2, "hybrid": 3, "auto": -1}
 TC_LEVEL_AUTO = -1
 TC_VARIANT_AUTO = -1
 TC_MAX_NDIM = 16

@@ -238,7 +238,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     int rc;
     if ((rc = check_desc(A)) || (rc = check_desc(B)) || (rc = check_desc(C))) return rc;
     if (level < 0 || level > 2) return TC_ERR_LEVEL;
-    if (variant != TC_VARIANT_NAIVE && variant != TC_VARIANT_AB && variant != TC_VARIANT_ABC) return TC_ERR_VARIANT;
+    if (variant < TC_VARIANT_NAIVE || variant > TC_VARIANT_HYBRID) return TC_ERR_VARIANT;
     p->bs_block = 16;
     bool no_merge = false;
     int split = 1;
@@ -296,6 +296,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     p->variant = variant;
     while (level > 0 && std::min(p->m, std::min(p->n, p->k)) < (1 << level)) --level;
     p->level = level;
+    if (variant == TC_VARIANT_HYBRID && level < 2) variant = TC_VARIANT_ABC;  // nothing to store below two levels
     const int g = 1 << level;
     // Block extents: the matrix view is cut at multiples of the extent; the last block of each direction may be
     // short (or empty) and is completed with zeros (Sec. 3, last paragraph: zero padding of the whole bundle).
@@ -322,14 +323,16 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         split = (int)((p->k + kc - 1) / kc);
     }
     const bool use_S = split > 1;
-    const bool use_M = !empty && p->k > 0 && level > 0 && variant != TC_VARIANT_ABC;
+    const bool use_H = !empty && p->k > 0 && variant == TC_VARIANT_HYBRID;  // first-level operand sums: two blocks square
+    const bool use_M = !empty && p->k > 0 && level > 0 && (variant == TC_VARIANT_AB || variant == TC_VARIANT_NAIVE);
     const bool use_T = use_M && variant == TC_VARIANT_NAIVE;
     p->bundles[V_RSM] = make_dense(use_M || use_S ? p->mb : 0, 1);
     p->bundles[V_CSM] = make_dense(use_M ? p->nb : use_S ? split * p->nb : 0, p->mb);  // the chunks' temporaries side by side
-    p->bundles[V_RSTA] = make_dense(use_T ? p->mb : 0, 1);
-    p->bundles[V_CSTA] = make_dense(use_T ? p->kb : 0, p->mb);
-    p->bundles[V_RSTB] = make_dense(use_T ? p->kb : 0, 1);
-    p->bundles[V_CSTB] = make_dense(use_T ? p->nb : 0, p->kb);
+    const int64_t tm = use_H ? 2 * p->mb : p->mb, tn = use_H ? 2 * p->nb : p->nb, tk = use_H ? 2 * p->kb : p->kb;  // temporaries' extents
+    p->bundles[V_RSTA] = make_dense(use_T || use_H ? tm : 0, 1);
+    p->bundles[V_CSTA] = make_dense(use_T || use_H ? tk : 0, tm);
+    p->bundles[V_RSTB] = make_dense(use_T || use_H ? tk : 0, 1);
+    p->bundles[V_CSTB] = make_dense(use_T || use_H ? tn : 0, tk);
     int64_t off = 0;
     for (auto& b : p->bundles) {
         b.out_off = off;
@@ -343,6 +346,11 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     if (use_S) {
         p->wsM = 0;
         p->workspace_bytes = (size_t)(split * p->mb * p->nb) * sizeof(double);
+    }
+    if (use_H) {
+        p->wsTA = 0;
+        p->wsTB = tm * tk;
+        p->workspace_bytes = (size_t)(tm * tk + tk * tn) * sizeof(double);
     }
     if (use_M) {
         int64_t w = 0;
@@ -366,6 +374,120 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         if (max_total > 0 && tc::launch_planner(p->bundles_dev, V_COUNT, max_total, p->bs_block, p->store_dev, stream)) return TC_ERR_HIP;
     }
     auto vec = [p](int id) -> const int64_t* { return p->store_dev ? p->store_dev + p->bundles[id].out_off : nullptr; };
+
+    struct Pending {
+        Product pr;
+        tc_product_t view;
+    };
+    std::vector<char> touched(g * g, 0);  // blocks of C written so far: the first product to write one applies beta
+    // Turn a list of products into launches (and, for AB / Naive, their temporaries and element-wise passes).
+    auto emit = [&](std::vector<Pending>& list, const tc::FusedConfig& user_cfg_base, bool fusedC_) {
+        // Products whose destination sets are disjoint may share one launch (ABC); otherwise one launch each.
+        std::vector<int> phase(list.size(), 0);
+        int nphase = 0;
+        const bool merge = fusedC_ && !no_merge;
+        {
+            std::vector<std::vector<char>> used;  // per phase: blocks written, and operand class
+            std::vector<int> pclass;
+            for (size_t e = 0; e < list.size(); ++e) {
+                const tc_product_t& v = list[e].view;
+                int cls = terms_class(list[e].pr.A.nterms, list[e].pr.B.nterms);
+                int chosen = -1;
+                if (merge) {
+                    for (int ph = 0; ph < nphase && chosen < 0; ++ph) {
+                        bool ok = pclass[ph] == cls;
+                        for (int d = 0; d < v.n_c && ok; ++d) ok = !used[ph][v.c_row[d] * g + v.c_col[d]];
+                        if (ok) chosen = ph;
+                    }
+                }
+                if (chosen < 0) {
+                    chosen = nphase++;
+                    used.push_back(std::vector<char>(g * g, 0));
+                    pclass.push_back(cls);
+                }
+                for (int d = 0; d < v.n_c; ++d) used[chosen][v.c_row[d] * g + v.c_col[d]] = 1;
+                phase[e] = chosen;
+            }
+        }
+        // emit in phase order; the first product (in that order) to write a block of C applies beta to it
+        const bool fusedC = fusedC_;
+                for (int ph = 0; ph < nphase; ++ph) {
+            int first_dev = (int)p->prods.size(), count = 0, cls = 0;
+            for (size_t e = 0; e < list.size(); ++e) {
+                if (phase[e] != ph) continue;
+                Pending& q = list[e];
+                uint32_t first_mask = 0;
+                for (int d = 0; d < q.view.n_c; ++d) {
+                    char& t = touched[q.view.c_row[d] * g + q.view.c_col[d]];
+                    if (!t) first_mask |= 1u << d, q.view.c_first[d] = 1;
+                    t = 1;
+                }
+                q.view.launch = (int)p->steps.size();
+                cls = terms_class(q.pr.A.nterms, q.pr.B.nterms);  // merged launches hold one class
+                if (fusedC) {
+                    q.pr.first_mask = first_mask;
+                    p->prods.push_back(q.pr);
+                    ++count;
+                } else {
+                    // temporaries: dense, column-major, one block extent each
+                    Product acc;  // M -> destinations of C
+                    std::memset(&acc, 0, sizeof acc);
+                    set_operand(acc.A, vec(V_RSM), vec(V_CSM), p->mb, p->nb, 1, p->wsM);
+                    add_term(acc.A, 0, 0, 1.0);
+                    acc.C = q.pr.C;
+                    acc.mb = p->mb;
+                    acc.nb = p->nb;
+                    acc.first_mask = first_mask;
+                    Product mul = q.pr;  // (sum A)(sum B) -> M
+                    set_operand(mul.C, vec(V_RSM), vec(V_CSM), p->mb, p->nb, 1, p->wsM);
+                    add_term(mul.C, 0, 0, 1.0);
+                    mul.first_mask = 1;
+                    mul.overwrite = 1;
+                    tc::FusedConfig cfg = user_cfg_base;
+                    cfg.c_mode = 0;  // M is dense with contiguous rows
+                    if (variant == TC_VARIANT_NAIVE) {
+                        Product sa, sb;  // operand sums -> TA, TB
+                        std::memset(&sa, 0, sizeof sa);
+                        std::memset(&sb, 0, sizeof sb);
+                        sa.A = q.pr.A;
+                        set_operand(sa.C, vec(V_RSTA), vec(V_CSTA), p->mb, p->kb, 1, p->wsTA);
+                        add_term(sa.C, 0, 0, 1.0);
+                        sa.mb = p->mb, sa.nb = p->kb, sa.first_mask = 1, sa.overwrite = 1;
+                        sb.A = q.pr.B;
+                        set_operand(sb.C, vec(V_RSTB), vec(V_CSTB), p->kb, p->nb, 1, p->wsTB);
+                        add_term(sb.C, 0, 0, 1.0);
+                        sb.mb = p->kb, sb.nb = p->nb, sb.first_mask = 1, sb.overwrite = 1;
+                        int i0 = (int)p->prods.size();
+                        p->prods.push_back(sa);
+                        p->prods.push_back(sb);
+                        p->steps.push_back(Step{STEP_LINCOMB, i0, 1, {}, p->mb, p->kb, p->a_mode == 0 ? 1 : 0, 0});
+                        p->steps.push_back(Step{STEP_LINCOMB, i0 + 1, 1, {}, p->kb, p->nb, p->b_mode == 1 ? 1 : 0, 1});
+                        set_operand(mul.A, vec(V_RSTA), vec(V_CSTA), p->mb, p->kb, 1, p->wsTA);
+                        add_term(mul.A, 0, 0, 1.0);
+                        set_operand(mul.B, vec(V_RSTB), vec(V_CSTB), p->kb, p->nb, 1, p->wsTB);
+                        add_term(mul.B, 0, 0, 1.0);
+                        cfg = tc::FusedConfig{0, 1, 1, 1, 1, 1, 1, 1, 0};  // dense temporaries: block extents are multiples of 16
+                    } else {
+                        cfg.nta = terms_class(q.pr.A.nterms, q.pr.B.nterms) / 8;
+                        cfg.ntb = terms_class(q.pr.A.nterms, q.pr.B.nterms) % 8;
+                    }
+                    int i1 = (int)p->prods.size();
+                    p->prods.push_back(mul);
+                    p->prods.push_back(acc);
+                    q.view.launch = (int)p->steps.size();
+                    p->steps.push_back(Step{STEP_FUSED, i1, 1, cfg, p->mb, p->nb, 0, 0});
+                    p->steps.push_back(Step{STEP_LINCOMB, i1 + 1, 1, {}, p->mb, p->nb, p->c_mode == 0 ? 1 : 0, 0});
+                }
+                p->sched.push_back(q.view);
+            }
+            if (fusedC && count > 0) {
+                tc::FusedConfig cfg = user_cfg_base;
+                cfg.nta = cls / 8;
+                cfg.ntb = cls % 8;
+                p->steps.push_back(Step{STEP_FUSED, first_dev, count, cfg, p->mb, p->nb, 0, 0});
+            }
+        }
+        };
 
     // ---- schedule ----
     if (empty) return TC_OK;  // nothing to do at run time
@@ -418,15 +540,126 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         acc.first_mask = 1;
         p->prods.push_back(acc);
         p->steps.push_back(Step{STEP_LINCOMB, first + split, 1, {}, p->mb, p->nb, p->c_mode == 0 ? 1 : 0, 0});
+    } else if (use_H) {
+        // Two levels, the first stored, the second fused.  For each first-level product r: operand sums of two
+        // first-level blocks go to the dense temporaries TA, TB (a single +1 block is used in place); the seven
+        // second-level products of TA * TB are scheduled like one-level ABC, each adding to the second-level blocks
+        // of every first-level destination of r (up to 2 x 2 blocks of the 4 x 4 grid of C).
+        std::vector<std::vector<int>> U1, V1, W1;
+        block_tables(1, U1, V1, W1);
+        const int64_t MB = 2 * p->mb, NB = 2 * p->nb, KB = 2 * p->kb;
+        struct Blk {
+            int r, c, sign;
+        };
+        for (int r = 0; r < 7; ++r) {
+            std::vector<Blk> oa, ob, oc;
+            for (int i = 0; i < 2; ++i)
+                for (int j = 0; j < 2; ++j) {
+                    if (U1[r][i * 2 + j] && i * MB < p->m && j * KB < p->k) oa.push_back({i, j, U1[r][i * 2 + j]});
+                    if (V1[r][i * 2 + j] && i * KB < p->k && j * NB < p->n) ob.push_back({i, j, V1[r][i * 2 + j]});
+                    if (W1[r][i * 2 + j] && i * MB < p->m && j * NB < p->n) oc.push_back({i, j, W1[r][i * 2 + j]});
+                }
+            if (oa.empty() || ob.empty() || oc.empty()) continue;
+            // where the second level reads its operands: (vectors, lengths, space, offset of the first-level block, real extents)
+            struct Src {
+                const int64_t *rs, *cs;
+                int64_t rs_len, cs_len, r0, c0, rows, cols;
+                int space;
+                int64_t base;
+                bool direct;
+            };
+            auto real = [](int64_t total, int64_t start, int64_t ext) { return std::min(ext, total - start); };
+            Src sa, sb;
+            sa.direct = oa.size() == 1 && oa[0].sign == 1;
+            sb.direct = ob.size() == 1 && ob[0].sign == 1;
+            if (sa.direct) {
+                sa = Src{vec(V_RSA), vec(V_CSA), p->m, p->k, oa[0].r * MB, oa[0].c * KB, real(p->m, oa[0].r * MB, MB), real(p->k, oa[0].c * KB, KB), 0, 0, true};
+            } else {
+                Product sum;
+                std::memset(&sum, 0, sizeof sum);
+                set_operand(sum.A, vec(V_RSA), vec(V_CSA), p->m, p->k, 0, 0);
+                int64_t rows = 0, cols = 0;
+                for (const Blk& b : oa) {
+                    add_term(sum.A, b.r * MB, b.c * KB, b.sign);
+                    rows = std::max(rows, real(p->m, b.r * MB, MB));
+                    cols = std::max(cols, real(p->k, b.c * KB, KB));
+                }
+                set_operand(sum.C, vec(V_RSTA), vec(V_CSTA), MB, KB, 1, p->wsTA);
+                add_term(sum.C, 0, 0, 1.0);
+                sum.mb = MB, sum.nb = KB, sum.first_mask = 1, sum.overwrite = 1;
+                p->steps.push_back(Step{STEP_LINCOMB, (int)p->prods.size(), 1, {}, MB, KB, p->a_mode == 0 ? 1 : 0, 0});
+                p->prods.push_back(sum);
+                sa = Src{vec(V_RSTA), vec(V_CSTA), MB, KB, 0, 0, rows, cols, 1, p->wsTA, false};
+            }
+            if (sb.direct) {
+                sb = Src{vec(V_RSB), vec(V_CSB), p->k, p->n, ob[0].r * KB, ob[0].c * NB, real(p->k, ob[0].r * KB, KB), real(p->n, ob[0].c * NB, NB), 0, 0, true};
+            } else {
+                Product sum;
+                std::memset(&sum, 0, sizeof sum);
+                set_operand(sum.A, vec(V_RSB), vec(V_CSB), p->k, p->n, 0, 0);
+                int64_t rows = 0, cols = 0;
+                for (const Blk& b : ob) {
+                    add_term(sum.A, b.r * KB, b.c * NB, b.sign);
+                    rows = std::max(rows, real(p->k, b.r * KB, KB));
+                    cols = std::max(cols, real(p->n, b.c * NB, NB));
+                }
+                set_operand(sum.C, vec(V_RSTB), vec(V_CSTB), KB, NB, 1, p->wsTB);
+                add_term(sum.C, 0, 0, 1.0);
+                sum.mb = KB, sum.nb = NB, sum.first_mask = 1, sum.overwrite = 1;
+                p->steps.push_back(Step{STEP_LINCOMB, (int)p->prods.size(), 1, {}, KB, NB, p->b_mode == 1 ? 1 : 0, 1});
+                p->prods.push_back(sum);
+                sb = Src{vec(V_RSTB), vec(V_CSTB), KB, NB, 0, 0, rows, cols, 1, p->wsTB, false};
+            }
+            std::vector<Pending> list;
+            for (int q = 0; q < 7; ++q) {
+                Pending e;
+                std::memset(&e.pr, 0, sizeof e.pr);
+                std::memset(&e.view, 0, sizeof e.view);
+                set_operand(e.pr.A, sa.rs, sa.cs, sa.rs_len, sa.cs_len, sa.space, sa.base);
+                set_operand(e.pr.B, sb.rs, sb.cs, sb.rs_len, sb.cs_len, sb.space, sb.base);
+                set_operand(e.pr.C, vec(V_RSC), vec(V_CSC), p->m, p->n, 0, 0);
+                e.pr.mb = p->mb, e.pr.nb = p->nb, e.pr.kb = p->kb;
+                for (int i = 0; i < 2; ++i)
+                    for (int j = 0; j < 2; ++j) {
+                        if (U1[q][i * 2 + j] && i * p->mb < sa.rows && j * p->kb < sa.cols) {
+                            add_term(e.pr.A, sa.r0 + i * p->mb, sa.c0 + j * p->kb, U1[q][i * 2 + j]);
+                            for (const Blk& b : oa)  // what the product means on the 4 x 4 grid
+                                if (e.view.n_a < 4) {
+                                    const int t = e.view.n_a++;
+                                    e.view.a_row[t] = 2 * b.r + i, e.view.a_col[t] = 2 * b.c + j, e.view.a_sign[t] = b.sign * U1[q][i * 2 + j];
+                                }
+                        }
+                        if (V1[q][i * 2 + j] && i * p->kb < sb.rows && j * p->nb < sb.cols) {
+                            add_term(e.pr.B, sb.r0 + i * p->kb, sb.c0 + j * p->nb, V1[q][i * 2 + j]);
+                            for (const Blk& b : ob)
+                                if (e.view.n_b < 4) {
+                                    const int t = e.view.n_b++;
+                                    e.view.b_row[t] = 2 * b.r + i, e.view.b_col[t] = 2 * b.c + j, e.view.b_sign[t] = b.sign * V1[q][i * 2 + j];
+                                }
+                        }
+                        if (W1[q][i * 2 + j])
+                            for (const Blk& b : oc) {
+                                const int bi = 2 * b.r + i, bj = 2 * b.c + j;
+                                if (bi * p->mb < p->m && bj * p->nb < p->n) {
+                                    add_term(e.pr.C, bi * p->mb, bj * p->nb, b.sign * W1[q][i * 2 + j]);
+                                    const int t = e.view.n_c++;
+                                    e.view.c_row[t] = bi, e.view.c_col[t] = bj, e.view.c_sign[t] = b.sign * W1[q][i * 2 + j];
+                                }
+                            }
+                    }
+                lead_with_plus(e.pr.A);
+                lead_with_plus(e.pr.B);
+                if (e.pr.A.nterms == 0 || e.pr.B.nterms == 0 || e.pr.C.nterms == 0) continue;
+                list.push_back(e);
+            }
+            tc::FusedConfig cfg{sa.direct ? p->a_mode : 0, sb.direct ? p->b_mode : 1, 1, 1, sa.direct ? p->a_vec : 1, sb.direct ? p->b_vec : 1,
+                                sa.space, sb.space, p->c_mode};
+            emit(list, cfg, true);
+        }
     } else {
         std::vector<std::vector<int>> U, V, W;
         block_tables(level, U, V, W);
         const int R = (int)U.size();
-        std::vector<char> touched(g * g, 0);
-        struct Pending {
-            Product pr;
-            tc_product_t view;
-        };
         std::vector<Pending> list;
         for (int r = 0; r < R; ++r) {
             Pending e;
@@ -462,112 +695,8 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
             if (e.view.n_a == 0 || e.view.n_b == 0 || e.view.n_c == 0) continue;
             list.push_back(e);
         }
-        // Products whose destination sets are disjoint may share one launch (ABC); otherwise one launch each.
-        std::vector<int> phase(list.size(), 0);
-        int nphase = 0;
-        const bool merge = (variant == TC_VARIANT_ABC || level == 0) && !no_merge;
-        {
-            std::vector<std::vector<char>> used;  // per phase: blocks written, and operand class
-            std::vector<int> pclass;
-            for (size_t e = 0; e < list.size(); ++e) {
-                const tc_product_t& v = list[e].view;
-                int cls = terms_class(v.n_a, v.n_b);
-                int chosen = -1;
-                if (merge) {
-                    for (int ph = 0; ph < nphase && chosen < 0; ++ph) {
-                        bool ok = pclass[ph] == cls;
-                        for (int d = 0; d < v.n_c && ok; ++d) ok = !used[ph][v.c_row[d] * g + v.c_col[d]];
-                        if (ok) chosen = ph;
-                    }
-                }
-                if (chosen < 0) {
-                    chosen = nphase++;
-                    used.push_back(std::vector<char>(g * g, 0));
-                    pclass.push_back(cls);
-                }
-                for (int d = 0; d < v.n_c; ++d) used[chosen][v.c_row[d] * g + v.c_col[d]] = 1;
-                phase[e] = chosen;
-            }
-        }
-        // emit in phase order; the first product (in that order) to write a block of C applies beta to it
-        const bool fusedC = (variant == TC_VARIANT_ABC || level == 0);
-        const tc::FusedConfig user_cfg_base{p->a_mode, p->b_mode, 1, 1, p->a_vec, p->b_vec, 0, 0, p->c_mode};
-        for (int ph = 0; ph < nphase; ++ph) {
-            int first_dev = (int)p->prods.size(), count = 0, cls = 0;
-            for (size_t e = 0; e < list.size(); ++e) {
-                if (phase[e] != ph) continue;
-                Pending& q = list[e];
-                uint32_t first_mask = 0;
-                for (int d = 0; d < q.view.n_c; ++d) {
-                    char& t = touched[q.view.c_row[d] * g + q.view.c_col[d]];
-                    if (!t) first_mask |= 1u << d, q.view.c_first[d] = 1;
-                    t = 1;
-                }
-                q.view.launch = (int)p->steps.size();
-                cls = terms_class(q.view.n_a, q.view.n_b);  // merged launches hold one class
-                if (fusedC) {
-                    q.pr.first_mask = first_mask;
-                    p->prods.push_back(q.pr);
-                    ++count;
-                } else {
-                    // temporaries: dense, column-major, one block extent each
-                    Product acc;  // M -> destinations of C
-                    std::memset(&acc, 0, sizeof acc);
-                    set_operand(acc.A, vec(V_RSM), vec(V_CSM), p->mb, p->nb, 1, p->wsM);
-                    add_term(acc.A, 0, 0, 1.0);
-                    acc.C = q.pr.C;
-                    acc.mb = p->mb;
-                    acc.nb = p->nb;
-                    acc.first_mask = first_mask;
-                    Product mul = q.pr;  // (sum A)(sum B) -> M
-                    set_operand(mul.C, vec(V_RSM), vec(V_CSM), p->mb, p->nb, 1, p->wsM);
-                    add_term(mul.C, 0, 0, 1.0);
-                    mul.first_mask = 1;
-                    mul.overwrite = 1;
-                    tc::FusedConfig cfg = user_cfg_base;
-                    cfg.c_mode = 0;  // M is dense with contiguous rows
-                    if (variant == TC_VARIANT_NAIVE) {
-                        Product sa, sb;  // operand sums -> TA, TB
-                        std::memset(&sa, 0, sizeof sa);
-                        std::memset(&sb, 0, sizeof sb);
-                        sa.A = q.pr.A;
-                        set_operand(sa.C, vec(V_RSTA), vec(V_CSTA), p->mb, p->kb, 1, p->wsTA);
-                        add_term(sa.C, 0, 0, 1.0);
-                        sa.mb = p->mb, sa.nb = p->kb, sa.first_mask = 1, sa.overwrite = 1;
-                        sb.A = q.pr.B;
-                        set_operand(sb.C, vec(V_RSTB), vec(V_CSTB), p->kb, p->nb, 1, p->wsTB);
-                        add_term(sb.C, 0, 0, 1.0);
-                        sb.mb = p->kb, sb.nb = p->nb, sb.first_mask = 1, sb.overwrite = 1;
-                        int i0 = (int)p->prods.size();
-                        p->prods.push_back(sa);
-                        p->prods.push_back(sb);
-                        p->steps.push_back(Step{STEP_LINCOMB, i0, 1, {}, p->mb, p->kb, p->a_mode == 0 ? 1 : 0, 0});
-                        p->steps.push_back(Step{STEP_LINCOMB, i0 + 1, 1, {}, p->kb, p->nb, p->b_mode == 1 ? 1 : 0, 1});
-                        set_operand(mul.A, vec(V_RSTA), vec(V_CSTA), p->mb, p->kb, 1, p->wsTA);
-                        add_term(mul.A, 0, 0, 1.0);
-                        set_operand(mul.B, vec(V_RSTB), vec(V_CSTB), p->kb, p->nb, 1, p->wsTB);
-                        add_term(mul.B, 0, 0, 1.0);
-                        cfg = tc::FusedConfig{0, 1, 1, 1, 1, 1, 1, 1, 0};  // dense temporaries: block extents are multiples of 16
-                    } else {
-                        cfg.nta = terms_class(q.view.n_a, q.view.n_b) / 8;
-                        cfg.ntb = terms_class(q.view.n_a, q.view.n_b) % 8;
-                    }
-                    int i1 = (int)p->prods.size();
-                    p->prods.push_back(mul);
-                    p->prods.push_back(acc);
-                    q.view.launch = (int)p->steps.size();
-                    p->steps.push_back(Step{STEP_FUSED, i1, 1, cfg, p->mb, p->nb, 0, 0});
-                    p->steps.push_back(Step{STEP_LINCOMB, i1 + 1, 1, {}, p->mb, p->nb, p->c_mode == 0 ? 1 : 0, 0});
-                }
-                p->sched.push_back(q.view);
-            }
-            if (fusedC && count > 0) {
-                tc::FusedConfig cfg = user_cfg_base;
-                cfg.nta = cls / 8;
-                cfg.ntb = cls % 8;
-                p->steps.push_back(Step{STEP_FUSED, first_dev, count, cfg, p->mb, p->nb, 0, 0});
-            }
-        }
+        tc::FusedConfig base_cfg{p->a_mode, p->b_mode, 1, 1, p->a_vec, p->b_vec, 0, 0, p->c_mode};
+        emit(list, base_cfg, variant == TC_VARIANT_ABC || level == 0);
     }
     p->n_launches = (int)p->steps.size();
     if (!p->host_only && !p->prods.empty()) {
@@ -672,7 +801,8 @@ int choose_by_model(const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const 
     int best_level = -1, best_variant = -1;
     for (int L = 0; L <= 2; ++L) {
         if (*level != TC_LEVEL_AUTO && L != *level) continue;
-        for (int v = TC_VARIANT_ABC; v >= TC_VARIANT_NAIVE; --v) {
+        for (int v = TC_VARIANT_HYBRID; v >= TC_VARIANT_NAIVE; --v) {
+            if (v == TC_VARIANT_HYBRID && L != 2 && *variant == TC_VARIANT_AUTO) continue;  // the same as ABC below two levels
             if (*variant != TC_VARIANT_AUTO && v != *variant) continue;
             if (L == 0 && v != TC_VARIANT_ABC && *variant == TC_VARIANT_AUTO) continue;  // the variants coincide at level 0
             tc_plan_t cand;
@@ -718,7 +848,7 @@ int tc_plan_ex(tc_plan_t** plan_out, const tc_tensor_desc_t* A, const tc_tensor_
     try {
         if (level == TC_LEVEL_AUTO || variant == TC_VARIANT_AUTO) {
             if (level != TC_LEVEL_AUTO && (level < 0 || level > 2)) return TC_ERR_LEVEL;
-            if (variant != TC_VARIANT_AUTO && (variant < TC_VARIANT_NAIVE || variant > TC_VARIANT_ABC)) return TC_ERR_VARIANT;
+            if (variant != TC_VARIANT_AUTO && (variant < TC_VARIANT_NAIVE || variant > TC_VARIANT_HYBRID)) return TC_ERR_VARIANT;
             int rc = choose_by_model(A, B, C, &level, &variant, opts);
             if (rc != TC_OK) return rc;
         }

@@ -86,7 +86,7 @@ def test_plan_info_bundles_and_modes():
 
 
 @pytest.mark.parametrize("level", [1, 2])
-@pytest.mark.parametrize("variant", ["abc", "ab", "naive"])
+@pytest.mark.parametrize("variant", ["abc", "ab", "naive", "hybrid"])
 def test_schedule_satisfies_brent_equations(level, variant):
     """The library's own product schedule, read back through the ABI, multiplies block matrices correctly."""
     N = 64
@@ -125,8 +125,12 @@ def test_schedule_satisfies_brent_equations(level, variant):
             blocks.add((ci, cj))
     ws = tc.tc_plan_workspace_bytes(p)
     blk = info["mb"] * info["nb"], info["mb"] * info["kb"], info["kb"] * info["nb"]
-    assert ws == {"abc": 0, "ab": 8 * blk[0], "naive": 8 * sum(blk)}[variant]
-    if variant == "abc":
+    hybrid_ws = 8 * 4 * (blk[1] + blk[2]) if level == 2 else 0  # a quarter of A and of B; below two levels the same as ABC
+    assert ws == {"abc": 0, "ab": 8 * blk[0], "naive": 8 * sum(blk), "hybrid": hybrid_ws}[variant]
+    if variant == "hybrid" and level == 2:
+        # 5 + 5 stored operand sums, and for each first-level product the four launches of one-level ABC
+        assert info["n_launches"] == 10 + 7 * 4
+    if variant == "abc" or (variant == "hybrid" and level == 1):
         assert info["n_launches"] == (4 if level == 1 else len(by_launch))
         assert info["n_launches"] < 7 ** level
 
@@ -166,9 +170,30 @@ def _oracle_prediction(plan, params):
     sched = tc.tc_plan_schedule(plan)
     mb, nb, kb = info["mb"], info["nb"], info["kb"]
     tiles = math.ceil(mb / 128) * math.ceil(nb / 128)
-    fused_c = info["variant"] == 2 or info["level"] == 0
+    fused_c = info["variant"] == 2 or info["level"] == 0 or (info["variant"] == 3 and info["level"] < 2)
     launches = []
-    if fused_c:
+    if info["variant"] == 3 and info["level"] == 2:
+        # first-level operand sums of more than one block are stored (element-wise launches over two-block-square
+        # extents); every multiplying launch holds second-level products with two-term sums at most
+        import oracle
+
+        U1, V1, _ = oracle.strassen_tables(1)
+        by_launch = {}
+        for e in sched:
+            by_launch.setdefault(e["launch"], []).append(e)
+        keys = sorted(by_launch)
+        per_outer = len(keys) // 7  # launches of one first-level product (shapes here have no pruned blocks)
+        for r in range(7):
+            na, nbt = int(np.count_nonzero(U1[r])), int(np.count_nonzero(V1[r]))
+            if na > 1:
+                launches.append({"kind": "add", "elems": (na + 1) * 4 * mb * kb})
+            if nbt > 1:
+                launches.append({"kind": "add", "elems": (nbt + 1) * 4 * kb * nb})
+            for key in keys[r * per_outer:(r + 1) * per_outer]:
+                launches.append({"kind": "mul", "products": [
+                    {"tiles": tiles, "kb": kb, "terms": 2 if max(len(e["a"]) // na, len(e["b"]) // nbt) > 1 else 1,
+                     "c_elems": 2 * len(e["c"]) * mb * nb} for e in by_launch[key]]})
+    elif fused_c:
         by_launch = {}
         for e in sched:
             by_launch.setdefault(e["launch"], []).append(e)
@@ -194,8 +219,12 @@ def test_model_prediction_matches_the_oracle_model(shape):
     defaults = tc.tc_model_defaults()
     other = dict(defaults, peak_flops=50e12, rho_a=[0.9, 0.7, 0.5], bandwidth=3e12, rho_b=0.8, t_launch=1e-5, t_tile=3e-5, units=100)
     for level in (0, 1, 2):
-        for variant in ("abc", "ab", "naive"):
+        for variant in ("abc", "ab", "naive", "hybrid"):
             plan = _plan(*_gemm_desc(*shape), level=level, variant=variant)
+            info = tc.tc_plan_info(plan)
+            if variant == "hybrid" and level == 2 and not (3 * info["mb"] < shape[0] and 3 * info["nb"] < shape[1] and 3 * info["kb"] < shape[2]):
+                tc.tc_destroy(plan)  # the helper below rebuilds the first level without pruned blocks only
+                continue
             for params in (None, other):
                 got = tc.tc_plan_predict(plan, params)
                 want = _oracle_prediction(plan, params or defaults)
@@ -209,7 +238,7 @@ def test_automatic_choice_is_the_argmin_of_the_model():
         desc = _gemm_desc(*shape)
         times = {}
         for level in (0, 1, 2):
-            for variant in ("abc", "ab", "naive"):
+            for variant in ("abc", "ab", "naive") + (("hybrid",) if level == 2 else ()):
                 plan = _plan(*desc, level=level, variant=variant)
                 if tc.tc_plan_info(plan)["level"] == level:
                     times[(level, tc.VARIANTS[variant])] = tc.tc_plan_predict(plan)["total"]
