@@ -11,11 +11,11 @@
 // A 16x16 output patch is covered by 4 instructions whose B operand has its four column blocks rotated by
 // s = 0..3 positions: block slot b of instruction s multiplies row block b by column block (b + s) % 4.
 //
-// Other VALU instructions do not overlap with these MFMAs on this chip (measured: every integer or fp64 VALU
-// instruction adds its full issue time), so the main loop is written to need as few of them as possible: the
-// gather tables hold ready-made byte addresses (one 64-bit add per load), the k-step loop is unrolled over the two
-// LDS buffers so that every LDS address is a per-lane base plus a constant, and an operand with a single +1 term is
-// stored as loaded.  A wave-wide global load costs the CU's address pipeline the same whatever its width, so
+// Other VALU instructions delay these MFMAs on this chip (measured: integer or fp64 VALU work added to an MFMA loop
+// adds its issue time), so the main loop needs few of them: the gather tables hold ready-made byte addresses (one
+// 64-bit add per load), the k-step loop is unrolled over the two LDS buffers so that every LDS address is a
+// per-lane base plus a constant, and an operand whose leading coefficient is +1 starts its sum from the gathered
+// element itself.  A wave-wide global load costs the CU's address pipeline the same whatever its width, so
 // operands whose consecutive entry pairs are contiguous are gathered two elements per load.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -39,39 +39,31 @@ constexpr int PITCH = 132;
 constexpr int OPITCH = 130;  // row pitch of the output tile staged in LDS by the epilogue
 
 // One kernel family per (NTA, NTB) = terms of the operand sums of A and B.
-//   EXACT : every product of the launch has exactly NTA and NTB terms.  The term loops are compile-time and the
-//           gather of TWO k-steps is in flight (D = 2): measured under load, a gathered element takes about 7000
-//           cycles to arrive, more than the matrix-core work of one k-step, so the loads of k-step s + 2 are issued
-//           during k-step s and their sum is stored to LDS during k-step s + 1, long after they have landed.
-//   !EXACT: up to NTA / NTB terms, counted at run time (the 3- and 4-term sums of two-level schedules); one k-step
-//           of gather in flight, stored at the end of the step it was issued in.
-// The register sets of the loads in flight bound the k-step depth KT: 32 for single terms, 16 otherwise.
+//   EXACT : every product of the launch has exactly NTA and NTB terms; the term loops are compile-time.
+//   !EXACT: up to NTA / NTB terms, counted at run time (a four-term sum that lost a block to the zero padding).
+// D = k-steps of gather in flight.  Measured under load, a gathered element takes 7000-9000 cycles to arrive, about
+// the matrix-core work of one 32-deep k-step, so with D = 2 the loads of k-step s + 2 are issued during k-step s and
+// their sum is stored to LDS during k-step s + 1, long after they have landed.  Two register sets fit only for
+// single-term operands (two sets of the (1,2) family already spill); the others keep D = 1 and, while both sums have
+// at most two terms, a k-step deep enough (KT = 32) to cover most of the latency.  Four-term sums: KT = 16.
 template <int NTA_, int NTB_, bool EXACT_>
 struct Cfg {
     static constexpr int NTA = NTA_, NTB = NTB_;
     static constexpr bool EXACT = EXACT_;
-#ifndef TC_D2
-#define TC_D2 (EXACT && NTA == 1 && NTB == 1)
-#define TC_KT32 (EXACT && NTA <= 2 && NTB <= 2)
-#define TC_IL1 4
-#endif
-    static constexpr int D = TC_D2 ? 2 : 1;
-    static constexpr int KT = TC_KT32 ? 32 : 16;
+    static constexpr int D = (EXACT && NTA == 1 && NTB == 1) ? 2 : 1;
+    static constexpr int KT = (EXACT && NTA <= 2 && NTB <= 2) ? 32 : 16;
     static constexpr int NE = TM * KT / NTHREADS;  // elements of each operand tile (and term) a thread gathers per k-step
     static constexpr int NQ = KT / 4;              // matrix-core instruction groups per k-step
     static constexpr int TILE = KT * PITCH;
-    // Schedule inside a k-step, in instruction groups completed.  The two waves of a SIMD do their loads and LDS
-    // stores at different times so that one of them always has MFMAs to issue: the first ("early") wave issues its
-    // gather before group 0, its partner after ISSUE_LATE groups, when the first burst of loads has drained from
-    // the CU's address pipeline.
-#ifndef TC_SCHED8
-#define TC_SCHED8 5, 6, 4
-#define TC_SCHED4 2, 3, 1
-#endif
-    static constexpr int kSched8[3] = {TC_SCHED8}, kSched4[3] = {TC_SCHED4};  // ISSUE_LATE, STAGE_EARLY, STAGE_LATE
-    static constexpr int ISSUE_LATE = (D == 2) ? (NQ == 8 ? kSched8[0] : kSched4[0]) : (NQ == 8 ? TC_IL1 : 3);
-    static constexpr int STAGE_EARLY = (D == 2) ? (NQ == 8 ? kSched8[1] : kSched4[1]) : NQ;
-    static constexpr int STAGE_LATE = (D == 2) ? (NQ == 8 ? kSched8[2] : kSched4[2]) : NQ;
+    // Schedule inside a k-step, in instruction groups completed (measured optima).  The two waves of a SIMD do their
+    // loads and LDS stores at different times so that one of them always has MFMAs to issue: the first wave issues
+    // its gather before group 0, its partner after ISSUE_LATE groups, when the first burst of loads has drained from
+    // the CU's address pipeline.  With D = 2 the second wave stores right before it issues and the first wave
+    // three quarters into the step; with D = 1 both store after the last group.
+    static constexpr int ISSUE_LATE = (D == 2) ? 5 : (NQ == 8 ? 4 : 3);
+    static constexpr int STAGE_EARLY = (D == 2) ? 6 : NQ;
+    static constexpr int STAGE_LATE = (D == 2) ? 4 : NQ;
+    static_assert(D == 1 || NQ == 8, "the D = 2 schedule is written for 8 groups");
 };
 
 // Scatter vectors are reached through pointers stored in the product descriptors; telling the compiler that they

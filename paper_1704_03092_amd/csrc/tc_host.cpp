@@ -411,7 +411,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         }
         // emit in phase order; the first product (in that order) to write a block of C applies beta to it
         const bool fusedC = fusedC_;
-                for (int ph = 0; ph < nphase; ++ph) {
+        for (int ph = 0; ph < nphase; ++ph) {
             int first_dev = (int)p->prods.size(), count = 0, cls = 0;
             for (size_t e = 0; e < list.size(); ++e) {
                 if (phase[e] != ph) continue;
