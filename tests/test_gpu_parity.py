@@ -92,6 +92,42 @@ def _random_case(rng, kind="uniform"):
     return tens
 
 
+def _random_midsize_case(rng, kind):
+    """Up to three dimensions per bundle whose lengths multiply to a few hundred .. a couple of thousand; random
+    storage order and padding for every tensor."""
+    labels = list("abcdefghijkl")
+    rng.shuffle(labels)
+    nI, nJ, nP = rng.randint(1, 3), rng.randint(1, 3), rng.randint(1, 3)
+    I, J, P = labels[:nI], labels[nI:nI + nJ], labels[nI + nJ:nI + nJ + nP]
+    lengths = {}
+    for group, target in ((I, rng.choice([130, 300, 700, 1100])), (J, rng.choice([130, 300, 700, 1100])), (P, rng.choice([200, 900, 1700]))):
+        rem = target
+        for n, c in enumerate(group):
+            f = rem if n == len(group) - 1 else min(rng.choice([2, 3, 4, 5, 7, 8, 12, 16, 17, 24]), rem)
+            lengths[c] = max(1, f)
+            rem = max(1, rem // max(1, f))
+    idxA, idxB, idxC = I + P, P + J, I + J
+    for s in (idxA, idxB, idxC):
+        rng.shuffle(s)
+    tens = []
+    for tid, idx in enumerate((idxA, idxB, idxC)):
+        lens = [lengths[c] for c in idx]
+        order = list(range(len(idx)))
+        rng.shuffle(order)
+        tens.append(workloads.make_tensor("".join(idx), lengths, rng.randint(0, 10 ** 6), tid, kind, strides_for_order(lens, order, pad=rng.randint(0, 2))))
+    return tens
+
+
+def test_random_midsize_contractions_every_mode(gpu):
+    rng = random.Random(1704)
+    modes = [(l, v, {}) for (l, v) in MODES] + [(0, "abc", {"split_k": 3}), (-1, "auto", {"split_k": -1}), (1, "hybrid", {})]
+    for trial in range(66):
+        kind = "smallint" if trial % 2 else "uniform"
+        A, B, C = _random_midsize_case(rng, kind)
+        level, variant, kw = modes[trial % len(modes)]
+        _check(gpu, A, B, C, rng.choice([1.0, -2.0]), rng.choice([0.0, 1.0, 3.0]), level, variant, exact=bool(trial % 2), **kw)
+
+
 def test_random_contractions_random_layouts(gpu):
     rng = random.Random(2024)
     for trial in range(40):
