@@ -46,7 +46,7 @@ def main():
     ap.add_argument("--size", type=int, default=16384, help="m = n = k of the square contraction")
     ap.add_argument("--level", type=int, default=1)
     ap.add_argument("--variant", default="abc")
-    ap.add_argument("--modes", default="0abc,1abc,1ab,1naive,2abc,2ab,2naive,2hybrid", help="other modes to time (level+variant)")
+    ap.add_argument("--modes", default="0abc,1abc,1ab,1naive,2abc,2ab,2naive,1hybrid,2hybrid", help="other modes to time (level+variant)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain element-wise copy of 512 MiB (for scaling the profiler's HBM byte counters)")

@@ -43,10 +43,12 @@ typedef enum {
     TC_VARIANT_NAIVE = 0, /* operand sums and product stored in dense temporaries (Sec. 4.1) */
     TC_VARIANT_AB = 1,    /* operand sums fused into tile staging; product M stored densely, then accumulated into C */
     TC_VARIANT_ABC = 2,   /* fully fused: no temporaries, each product added to up to 2^L blocks of C from registers */
-    TC_VARIANT_HYBRID = 3 /* two levels only (otherwise the same as ABC): the operand sums of the first level are stored in
-                           * dense temporaries as in Naive, the second level is fully fused as in ABC and adds each of
-                           * its products to up to four blocks of C.  Not one of the paper's variants: its two-level
-                           * ABC needs four-block operand sums, which this GPU gathers at a lower rate than two-block ones. */
+    TC_VARIANT_HYBRID = 3 /* the operand sums of the first level are stored in dense temporaries as in Naive (a single block
+                           * is used in place), everything after that is fused as in ABC: at one level each product of
+                           * two temporaries is added to its blocks of C; at two levels the second level runs inside
+                           * the kernel and each of its products is added to up to four blocks of C.  Not one of the
+                           * paper's variants: this GPU gathers dense temporaries and two-block sums at a higher rate
+                           * than the two- and four-block sums of one- and two-level ABC. */
 } tc_variant_t;
 
 typedef enum {
@@ -150,7 +152,7 @@ int tc_plan_ex(tc_plan_t **plan_out, const tc_tensor_desc_t *A, const tc_tensor_
                int level, int variant, const tc_options_t *opts, void *stream);
 
 /* Bytes of device workspace tc_contract() needs (0 for the ABC variant and for level 0 without split_k;
- * AB: one block of C; Naive: plus one block of A and of B; HYBRID at two levels: a quarter of A and of B). */
+ * AB: one block of C; Naive: plus one block of A and of B; HYBRID: one first-level block of A and of B). */
 size_t tc_plan_workspace_bytes(const tc_plan_t *plan);
 
 /* C := alpha * A * B + beta * C.  A_dev, B_dev, C_dev, workspace_dev are device pointers owned by the caller;

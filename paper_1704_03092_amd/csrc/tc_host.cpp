@@ -296,7 +296,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     p->variant = variant;
     while (level > 0 && std::min(p->m, std::min(p->n, p->k)) < (1 << level)) --level;
     p->level = level;
-    if (variant == TC_VARIANT_HYBRID && level < 2) variant = TC_VARIANT_ABC;  // nothing to store below two levels
+    if (variant == TC_VARIANT_HYBRID && level < 1) variant = TC_VARIANT_ABC;  // nothing to store without a Strassen level
     const int g = 1 << level;
     // Block extents: the matrix view is cut at multiples of the extent; the last block of each direction may be
     // short (or empty) and is completed with zeros (Sec. 3, last paragraph: zero padding of the whole bundle).
@@ -323,12 +323,13 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         split = (int)((p->k + kc - 1) / kc);
     }
     const bool use_S = split > 1;
-    const bool use_H = !empty && p->k > 0 && variant == TC_VARIANT_HYBRID;  // first-level operand sums: two blocks square
+    const bool use_H = !empty && p->k > 0 && variant == TC_VARIANT_HYBRID;  // first-level operand sums: one first-level block
+    const int64_t hsub = level == 2 ? 2 : 1;  // second-level blocks per first-level block and direction
     const bool use_M = !empty && p->k > 0 && level > 0 && (variant == TC_VARIANT_AB || variant == TC_VARIANT_NAIVE);
     const bool use_T = use_M && variant == TC_VARIANT_NAIVE;
     p->bundles[V_RSM] = make_dense(use_M || use_S ? p->mb : 0, 1);
     p->bundles[V_CSM] = make_dense(use_M ? p->nb : use_S ? split * p->nb : 0, p->mb);  // the chunks' temporaries side by side
-    const int64_t tm = use_H ? 2 * p->mb : p->mb, tn = use_H ? 2 * p->nb : p->nb, tk = use_H ? 2 * p->kb : p->kb;  // temporaries' extents
+    const int64_t tm = use_H ? hsub * p->mb : p->mb, tn = use_H ? hsub * p->nb : p->nb, tk = use_H ? hsub * p->kb : p->kb;  // temporaries' extents
     p->bundles[V_RSTA] = make_dense(use_T || use_H ? tm : 0, 1);
     p->bundles[V_CSTA] = make_dense(use_T || use_H ? tk : 0, tm);
     p->bundles[V_RSTB] = make_dense(use_T || use_H ? tk : 0, 1);
@@ -541,13 +542,16 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         p->prods.push_back(acc);
         p->steps.push_back(Step{STEP_LINCOMB, first + split, 1, {}, p->mb, p->nb, p->c_mode == 0 ? 1 : 0, 0});
     } else if (use_H) {
-        // Two levels, the first stored, the second fused.  For each first-level product r: operand sums of two
-        // first-level blocks go to the dense temporaries TA, TB (a single +1 block is used in place); the seven
-        // second-level products of TA * TB are scheduled like one-level ABC, each adding to the second-level blocks
-        // of every first-level destination of r (up to 2 x 2 blocks of the 4 x 4 grid of C).
-        std::vector<std::vector<int>> U1, V1, W1;
+        // The first level stored, the rest fused.  For each first-level product r: operand sums of two first-level
+        // blocks go to the dense temporaries TA, TB (a single +1 block is used in place).  One level: TA * TB is
+        // one product added to the first-level destinations of r.  Two levels: the seven second-level products of
+        // TA * TB are scheduled like one-level ABC, each adding to the second-level blocks of every first-level
+        // destination of r (up to 2 x 2 blocks of the 4 x 4 grid of C).
+        std::vector<std::vector<int>> U1, V1, W1, U2, V2, W2;
         block_tables(1, U1, V1, W1);
-        const int64_t MB = 2 * p->mb, NB = 2 * p->nb, KB = 2 * p->kb;
+        block_tables(level - 1, U2, V2, W2);
+        const int h = (int)hsub, R2 = (int)U2.size();
+        const int64_t MB = hsub * p->mb, NB = hsub * p->nb, KB = hsub * p->kb;
         struct Blk {
             int r, c, sign;
         };
@@ -611,7 +615,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
                 sb = Src{vec(V_RSTB), vec(V_CSTB), KB, NB, 0, 0, rows, cols, 1, p->wsTB, false};
             }
             std::vector<Pending> list;
-            for (int q = 0; q < 7; ++q) {
+            for (int q = 0; q < R2; ++q) {
                 Pending e;
                 std::memset(&e.pr, 0, sizeof e.pr);
                 std::memset(&e.view, 0, sizeof e.view);
@@ -619,31 +623,31 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
                 set_operand(e.pr.B, sb.rs, sb.cs, sb.rs_len, sb.cs_len, sb.space, sb.base);
                 set_operand(e.pr.C, vec(V_RSC), vec(V_CSC), p->m, p->n, 0, 0);
                 e.pr.mb = p->mb, e.pr.nb = p->nb, e.pr.kb = p->kb;
-                for (int i = 0; i < 2; ++i)
-                    for (int j = 0; j < 2; ++j) {
-                        if (U1[q][i * 2 + j] && i * p->mb < sa.rows && j * p->kb < sa.cols) {
-                            add_term(e.pr.A, sa.r0 + i * p->mb, sa.c0 + j * p->kb, U1[q][i * 2 + j]);
+                for (int i = 0; i < h; ++i)
+                    for (int j = 0; j < h; ++j) {
+                        if (U2[q][i * h + j] && i * p->mb < sa.rows && j * p->kb < sa.cols) {
+                            add_term(e.pr.A, sa.r0 + i * p->mb, sa.c0 + j * p->kb, U2[q][i * h + j]);
                             for (const Blk& b : oa)  // what the product means on the 4 x 4 grid
                                 if (e.view.n_a < 4) {
                                     const int t = e.view.n_a++;
-                                    e.view.a_row[t] = 2 * b.r + i, e.view.a_col[t] = 2 * b.c + j, e.view.a_sign[t] = b.sign * U1[q][i * 2 + j];
+                                    e.view.a_row[t] = h * b.r + i, e.view.a_col[t] = h * b.c + j, e.view.a_sign[t] = b.sign * U2[q][i * h + j];
                                 }
                         }
-                        if (V1[q][i * 2 + j] && i * p->kb < sb.rows && j * p->nb < sb.cols) {
-                            add_term(e.pr.B, sb.r0 + i * p->kb, sb.c0 + j * p->nb, V1[q][i * 2 + j]);
+                        if (V2[q][i * h + j] && i * p->kb < sb.rows && j * p->nb < sb.cols) {
+                            add_term(e.pr.B, sb.r0 + i * p->kb, sb.c0 + j * p->nb, V2[q][i * h + j]);
                             for (const Blk& b : ob)
                                 if (e.view.n_b < 4) {
                                     const int t = e.view.n_b++;
-                                    e.view.b_row[t] = 2 * b.r + i, e.view.b_col[t] = 2 * b.c + j, e.view.b_sign[t] = b.sign * V1[q][i * 2 + j];
+                                    e.view.b_row[t] = h * b.r + i, e.view.b_col[t] = h * b.c + j, e.view.b_sign[t] = b.sign * V2[q][i * h + j];
                                 }
                         }
-                        if (W1[q][i * 2 + j])
+                        if (W2[q][i * h + j])
                             for (const Blk& b : oc) {
-                                const int bi = 2 * b.r + i, bj = 2 * b.c + j;
+                                const int bi = h * b.r + i, bj = h * b.c + j;
                                 if (bi * p->mb < p->m && bj * p->nb < p->n) {
-                                    add_term(e.pr.C, bi * p->mb, bj * p->nb, b.sign * W1[q][i * 2 + j]);
+                                    add_term(e.pr.C, bi * p->mb, bj * p->nb, b.sign * W2[q][i * h + j]);
                                     const int t = e.view.n_c++;
-                                    e.view.c_row[t] = bi, e.view.c_col[t] = bj, e.view.c_sign[t] = b.sign * W1[q][i * 2 + j];
+                                    e.view.c_row[t] = bi, e.view.c_col[t] = bj, e.view.c_sign[t] = b.sign * W2[q][i * h + j];
                                 }
                             }
                     }
@@ -802,7 +806,7 @@ int choose_by_model(const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const 
     for (int L = 0; L <= 2; ++L) {
         if (*level != TC_LEVEL_AUTO && L != *level) continue;
         for (int v = TC_VARIANT_HYBRID; v >= TC_VARIANT_NAIVE; --v) {
-            if (v == TC_VARIANT_HYBRID && L != 2 && *variant == TC_VARIANT_AUTO) continue;  // the same as ABC below two levels
+            if (v == TC_VARIANT_HYBRID && L == 0 && *variant == TC_VARIANT_AUTO) continue;  // the same as ABC without a Strassen level
             if (*variant != TC_VARIANT_AUTO && v != *variant) continue;
             if (L == 0 && v != TC_VARIANT_ABC && *variant == TC_VARIANT_AUTO) continue;  // the variants coincide at level 0
             tc_plan_t cand;

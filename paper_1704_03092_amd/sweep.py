@@ -10,7 +10,7 @@ Inputs are uniform[-1,1) from torch's generator (timing only; parity is the test
 import argparse
 import sys
 
-MODES = [(0, "abc"), (1, "abc"), (1, "ab"), (1, "naive"), (2, "abc"), (2, "ab"), (2, "naive"), (2, "hybrid")]
+MODES = [(0, "abc"), (1, "abc"), (1, "ab"), (1, "naive"), (2, "abc"), (2, "ab"), (2, "naive"), (1, "hybrid"), (2, "hybrid")]
 
 FAMILIES = {
     "square": [(n, n, n) for n in (1024, 2048, 4096, 6144, 8192, 12288, 16384)],

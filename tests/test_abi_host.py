@@ -125,12 +125,12 @@ def test_schedule_satisfies_brent_equations(level, variant):
             blocks.add((ci, cj))
     ws = tc.tc_plan_workspace_bytes(p)
     blk = info["mb"] * info["nb"], info["mb"] * info["kb"], info["kb"] * info["nb"]
-    hybrid_ws = 8 * 4 * (blk[1] + blk[2]) if level == 2 else 0  # a quarter of A and of B; below two levels the same as ABC
+    hybrid_ws = 8 * (4 if level == 2 else 1) * (blk[1] + blk[2])  # one first-level block of A and of B
     assert ws == {"abc": 0, "ab": 8 * blk[0], "naive": 8 * sum(blk), "hybrid": hybrid_ws}[variant]
-    if variant == "hybrid" and level == 2:
-        # 5 + 5 stored operand sums, and for each first-level product the four launches of one-level ABC
-        assert info["n_launches"] == 10 + 7 * 4
-    if variant == "abc" or (variant == "hybrid" and level == 1):
+    if variant == "hybrid":
+        # 5 + 5 stored operand sums; per first-level product one launch, or the four launches of one-level ABC
+        assert info["n_launches"] == 10 + 7 * (4 if level == 2 else 1)
+    if variant == "abc":
         assert info["n_launches"] == (4 if level == 1 else len(by_launch))
         assert info["n_launches"] < 7 ** level
 
@@ -170,9 +170,10 @@ def _oracle_prediction(plan, params):
     sched = tc.tc_plan_schedule(plan)
     mb, nb, kb = info["mb"], info["nb"], info["kb"]
     tiles = math.ceil(mb / 128) * math.ceil(nb / 128)
-    fused_c = info["variant"] == 2 or info["level"] == 0 or (info["variant"] == 3 and info["level"] < 2)
+    fused_c = info["variant"] == 2 or info["level"] == 0
     launches = []
-    if info["variant"] == 3 and info["level"] == 2:
+    if info["variant"] == 3 and info["level"] >= 1:
+        hh = 4 if info["level"] == 2 else 1  # second-level blocks per first-level block
         # first-level operand sums of more than one block are stored (element-wise launches over two-block-square
         # extents); every multiplying launch holds second-level products with two-term sums at most
         import oracle
@@ -186,9 +187,9 @@ def _oracle_prediction(plan, params):
         for r in range(7):
             na, nbt = int(np.count_nonzero(U1[r])), int(np.count_nonzero(V1[r]))
             if na > 1:
-                launches.append({"kind": "add", "elems": (na + 1) * 4 * mb * kb})
+                launches.append({"kind": "add", "elems": (na + 1) * hh * mb * kb})
             if nbt > 1:
-                launches.append({"kind": "add", "elems": (nbt + 1) * 4 * kb * nb})
+                launches.append({"kind": "add", "elems": (nbt + 1) * hh * kb * nb})
             for key in keys[r * per_outer:(r + 1) * per_outer]:
                 launches.append({"kind": "mul", "products": [
                     {"tiles": tiles, "kb": kb, "terms": 2 if max(len(e["a"]) // na, len(e["b"]) // nbt) > 1 else 1,
@@ -222,7 +223,8 @@ def test_model_prediction_matches_the_oracle_model(shape):
         for variant in ("abc", "ab", "naive", "hybrid"):
             plan = _plan(*_gemm_desc(*shape), level=level, variant=variant)
             info = tc.tc_plan_info(plan)
-            if variant == "hybrid" and level == 2 and not (3 * info["mb"] < shape[0] and 3 * info["nb"] < shape[1] and 3 * info["kb"] < shape[2]):
+            g = 1 << info["level"]
+            if variant == "hybrid" and info["level"] >= 1 and not all((g - 1) * info[b] < x for b, x in zip(("mb", "nb", "kb"), shape)):
                 tc.tc_destroy(plan)  # the helper below rebuilds the first level without pruned blocks only
                 continue
             for params in (None, other):
@@ -238,7 +240,7 @@ def test_automatic_choice_is_the_argmin_of_the_model():
         desc = _gemm_desc(*shape)
         times = {}
         for level in (0, 1, 2):
-            for variant in ("abc", "ab", "naive") + (("hybrid",) if level == 2 else ()):
+            for variant in ("abc", "ab", "naive") + (("hybrid",) if level >= 1 else ()):
                 plan = _plan(*desc, level=level, variant=variant)
                 if tc.tc_plan_info(plan)["level"] == level:
                     times[(level, tc.VARIANTS[variant])] = tc.tc_plan_predict(plan)["total"]

@@ -13,7 +13,7 @@ from workloads import from_dense, strides_for_order
 pytestmark = pytest.mark.gpu
 
 TOL = {0: 1e-13, 1: 1e-13, 2: 1e-12}
-MODES = [(0, "abc"), (1, "abc"), (1, "ab"), (1, "naive"), (2, "abc"), (2, "ab"), (2, "naive"), (2, "hybrid")]
+MODES = [(0, "abc"), (1, "abc"), (1, "ab"), (1, "naive"), (1, "hybrid"), (2, "abc"), (2, "ab"), (2, "naive"), (2, "hybrid")]
 
 
 @pytest.fixture(scope="module")
@@ -150,7 +150,7 @@ def test_midsize_every_kernel_family(gpu, idxA, idxB):
             st = strides_for_order(lens, list(range(len(idx))), pad=pad)
             tens.append(workloads.make_tensor(idx, lengths, 77 + tid, tid, kind, st))
         A, B, C = tens
-        for level, variant in ((0, "abc"), (1, "abc"), (2, "abc"), (1, "naive"), (2, "ab"), (2, "hybrid")):
+        for level, variant in ((0, "abc"), (1, "abc"), (2, "abc"), (1, "naive"), (2, "ab"), (1, "hybrid"), (2, "hybrid")):
             _check(gpu, A, B, C, 1.0, 1.0, level, variant, exact=(kind == "smallint"))
 
 

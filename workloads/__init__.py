@@ -218,7 +218,7 @@ _ALL9 = tuple((l, v) for l in (1, 2) for v in ("naive", "ab", "abc"))
 
 def gemm(N: int, seed_off: int = 0, **kw) -> Contraction:
     return Contraction(f"gemm{N}", "ij", "ik", "kj", {"i": N, "j": N, "k": N}, 1.0, 1.0, "uniform",
-                       170403092 + 2 + seed_off, "square GEMM, paper's synthetic square family", ((0, "abc"),) + _ALL9 + ((2, "hybrid"),), **kw)
+                       170403092 + 2 + seed_off, "square GEMM, paper's synthetic square family", ((0, "abc"),) + _ALL9 + ((1, "hybrid"), (2, "hybrid")), **kw)
 
 
 def configs() -> Dict[str, Contraction]:
