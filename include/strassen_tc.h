@@ -162,6 +162,18 @@ size_t tc_plan_workspace_bytes(const tc_plan_t *plan);
 int tc_contract(const tc_plan_t *plan, double alpha, const double *A_dev, const double *B_dev, double beta,
                 double *C_dev, void *workspace_dev, void *stream);
 
+/* Time spent per kind of kernel in one tc_contract() (tc_contract_timed). */
+typedef struct {
+    double fused_ms;        /* the gather + multiply + update kernel (Sec. 4.1, 4.2) */
+    double elementwise_ms;  /* temporaries of the AB / Naive / HYBRID variants, split_k sums, C := beta C */
+    int fused_launches, elementwise_launches;
+} tc_launch_times_t;
+
+/* Same work as tc_contract(), with a HIP event recorded on `stream` after every launch; waits for the last one
+ * and reports the time per kind of kernel.  For benchmarks and tools: it creates and destroys events and blocks. */
+int tc_contract_timed(const tc_plan_t *plan, double alpha, const double *A_dev, const double *B_dev, double beta,
+                      double *C_dev, void *workspace_dev, void *stream, tc_launch_times_t *out);
+
 /* Release the plan and its device tables.  NULL is accepted. */
 int tc_destroy(tc_plan_t *plan);
 

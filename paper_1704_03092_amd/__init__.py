@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
     tc_contract,
+    tc_contract_timed,
     tc_destroy,
     tc_plan,
     tc_plan_info,

@@ -97,6 +97,11 @@ class tc_model_time_t(ctypes.Structure):
                 ("launch", ctypes.c_double)]
 
 
+class tc_launch_times_t(ctypes.Structure):
+    _fields_ = [("fused_ms", ctypes.c_double), ("elementwise_ms", ctypes.c_double), ("fused_launches", ctypes.c_int),
+                ("elementwise_launches", ctypes.c_int)]
+
+
 class TcError(RuntimeError):
     def __init__(self, status: int, what: str):
         super().__init__(f"{what}: {tc_strerror(status)} ({status})")
@@ -120,6 +125,8 @@ def load_library():
         lib.tc_plan_workspace_bytes.argtypes = [vp]
         lib.tc_contract.restype = ci
         lib.tc_contract.argtypes = [vp, dbl, vp, vp, dbl, vp, vp, vp]
+        lib.tc_contract_timed.restype = ci
+        lib.tc_contract_timed.argtypes = [vp, dbl, vp, vp, dbl, vp, vp, vp, ctypes.POINTER(tc_launch_times_t)]
         lib.tc_destroy.restype = ci
         lib.tc_destroy.argtypes = [vp]
         lib.tc_strerror.restype = ctypes.c_char_p
@@ -210,6 +217,16 @@ def tc_contract(plan: Plan, alpha: float, A, B, beta: float, C, workspace=None, 
     rc = load_library().tc_contract(plan.handle, float(alpha), _ptr(A), _ptr(B), float(beta), _ptr(C), _ptr(workspace), _stream(stream))
     if rc != 0:
         raise TcError(rc, "tc_contract")
+
+
+def tc_contract_timed(plan: Plan, alpha: float, A, B, beta: float, C, workspace=None, stream=None) -> dict:
+    """tc_contract with per-launch HIP events; blocks; returns the time per kind of kernel."""
+    out = tc_launch_times_t()
+    rc = load_library().tc_contract_timed(plan.handle, float(alpha), _ptr(A), _ptr(B), float(beta), _ptr(C), _ptr(workspace), _stream(stream),
+                                          ctypes.byref(out))
+    if rc != 0:
+        raise TcError(rc, "tc_contract_timed")
+    return {k: getattr(out, k) for k, _ in tc_launch_times_t._fields_}
 
 
 def tc_destroy(plan: Plan) -> None:

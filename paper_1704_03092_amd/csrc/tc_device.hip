@@ -114,6 +114,11 @@ int dev_upload(void* dst, const void* src, size_t bytes, void* stream) {
 }
 int dev_download(void* dst, const void* src, size_t bytes) { return (int)hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost); }
 int dev_stream_sync(void* stream) { return (int)hipStreamSynchronize((hipStream_t)stream); }
+int dev_event_create(void** e) { return (int)hipEventCreate((hipEvent_t*)e); }
+int dev_event_record(void* e, void* stream) { return (int)hipEventRecord((hipEvent_t)e, (hipStream_t)stream); }
+int dev_event_sync(void* e) { return (int)hipEventSynchronize((hipEvent_t)e); }
+int dev_event_elapsed_ms(float* ms, void* a, void* b) { return (int)hipEventElapsedTime(ms, (hipEvent_t)a, (hipEvent_t)b); }
+int dev_event_destroy(void* e) { return (int)hipEventDestroy((hipEvent_t)e); }
 
 int launch_planner(const BundleDesc* descs_dev, int nvec, int64_t max_total, int bs_block, int64_t* store_dev, void* stream) {
     hipStream_t st = (hipStream_t)stream;

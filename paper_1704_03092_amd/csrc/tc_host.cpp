@@ -908,6 +908,48 @@ int tc_contract(const tc_plan_t* plan, double alpha, const double* A_dev, const 
     return TC_OK;
 }
 
+int tc_contract_timed(const tc_plan_t* plan, double alpha, const double* A_dev, const double* B_dev, double beta, double* C_dev,
+                      void* workspace_dev, void* stream, tc_launch_times_t* out) {
+    if (!plan || !out) return TC_ERR_NULL;
+    if (plan->host_only) return TC_ERR_STATE;
+    std::memset(out, 0, sizeof *out);
+    if (plan->steps.empty()) return TC_OK;
+    if (!C_dev) return TC_ERR_NULL;
+    if (plan->k > 0 && (!A_dev || !B_dev)) return TC_ERR_NULL;
+    if (plan->workspace_bytes > 0 && !workspace_dev) return TC_ERR_WORKSPACE;
+    double* W = (double*)workspace_dev;
+    std::vector<void*> ev(plan->steps.size() + 1, nullptr);
+    int rc = TC_OK;
+    for (void*& e : ev)
+        if (tc::dev_event_create(&e)) rc = TC_ERR_HIP;
+    if (rc == TC_OK && tc::dev_event_record(ev[0], stream)) rc = TC_ERR_HIP;
+    for (size_t i = 0; i < plan->steps.size() && rc == TC_OK; ++i) {
+        const Step& s = plan->steps[i];
+        int err;
+        if (s.kind == STEP_FUSED)
+            err = tc::launch_fused(s.cfg, plan->prods_dev, s.first, s.count, s.rows, s.cols, A_dev, B_dev, C_dev, W, alpha, beta, stream);
+        else
+            err = tc::launch_lincomb(plan->prods_dev, s.first, s.rows, s.cols, s.lanes_along_rows, A_dev, B_dev, C_dev, W, s.src_role, beta,
+                                     stream);
+        if (err || tc::dev_event_record(ev[i + 1], stream)) rc = TC_ERR_HIP;
+    }
+    if (rc == TC_OK && tc::dev_event_sync(ev.back())) rc = TC_ERR_HIP;
+    for (size_t i = 0; i < plan->steps.size() && rc == TC_OK; ++i) {
+        float ms = 0;
+        if (tc::dev_event_elapsed_ms(&ms, ev[i], ev[i + 1])) {
+            rc = TC_ERR_HIP;
+            break;
+        }
+        if (plan->steps[i].kind == STEP_FUSED)
+            out->fused_ms += ms, ++out->fused_launches;
+        else
+            out->elementwise_ms += ms, ++out->elementwise_launches;
+    }
+    for (void* e : ev)
+        if (e) tc::dev_event_destroy(e);
+    return rc;
+}
+
 int tc_destroy(tc_plan_t* plan) {
     release(plan);
     return TC_OK;

@@ -59,6 +59,11 @@ int dev_free(void* p);
 int dev_upload(void* dst, const void* src, size_t bytes, void* stream);
 int dev_download(void* dst, const void* src, size_t bytes);
 int dev_stream_sync(void* stream);
+int dev_event_create(void** e);
+int dev_event_record(void* e, void* stream);
+int dev_event_sync(void* e);
+int dev_event_elapsed_ms(float* ms, void* a, void* b);
+int dev_event_destroy(void* e);
 
 // scatter + block scatter vectors for `nvec` bundles described in device array `descs`
 int launch_planner(const BundleDesc* descs_dev, int nvec, int64_t max_total, int bs_block, int64_t* store_dev, void* stream);
