@@ -184,6 +184,30 @@ def test_split_k(gpu):
     assert oracle.error_metric(logical(C, got_flat), ref.view(), oracle.tensor_norm(A), oracle.tensor_norm(B)) <= TOL[0]
 
 
+def test_contract_timed_matches_contract(gpu):
+    """tc_contract_timed enqueues the same launches: identical bits, and it counts the launches per kind."""
+    import torch
+
+    import paper_1704_03092_amd as tc
+    from gpu_util import to_dev
+
+    c = workloads.Contraction("g", "ij", "ik", "kj", {"i": 520, "j": 390, "k": 260}, seed=11)
+    A, B, C = c.tensors()
+    st = torch.cuda.current_stream()
+    for level, variant, fused, other in ((0, "abc", 1, 0), (1, "abc", 4, 0), (1, "hybrid", 7, 10), (1, "naive", 7, 21)):
+        plan = tc.tc_plan(A, B, C, level, variant, st)
+        nbytes = tc.tc_plan_workspace_bytes(plan)
+        ws = torch.zeros(max(nbytes // 8, 1), dtype=torch.float64, device="cuda")
+        dA, dB, dC1, dC2 = to_dev(A), to_dev(B), to_dev(C), to_dev(C)
+        tc.tc_contract(plan, 1.25, dA, dB, 0.5, dC1, ws, st)
+        times = tc.tc_contract_timed(plan, 1.25, dA, dB, 0.5, dC2, ws, st)
+        torch.cuda.synchronize()
+        tc.tc_destroy(plan)
+        assert torch.equal(dC1, dC2)
+        assert (times["fused_launches"], times["elementwise_launches"]) == (fused, other)
+        assert times["fused_ms"] > 0 and times["elementwise_ms"] >= 0
+
+
 def test_benchmark_index_strings_reduced_sizes(gpu):
     cfgs = workloads.configs()
     small = {
