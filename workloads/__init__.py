@@ -230,7 +230,7 @@ def configs() -> Dict[str, Contraction]:
         c[f"cfg2_{N}"] = gemm(N)
     c["cfg3"] = Contraction("cfg3", "abij", "abef", "efij", {"a": 192, "b": 192, "e": 192, "f": 192, "i": 48, "j": 48},
                             1.0, 1.0, "normal", 170403092 + 3, "CCSD particle-particle ladder shape",
-                            ((0, "abc"), (1, "abc"), (2, "abc"), (2, "hybrid")))
+                            ((0, "abc"), (1, "abc"), (1, "hybrid"), (2, "abc"), (2, "hybrid")))
     c["cfg4a"] = Contraction("cfg4a", "abc", "daec", "ebd", {"a": 96, "b": 96, "c": 96, "d": 64, "e": 64}, 1.0, 1.0, "uniform",
                              170403092 + 4, "permuted strides, conflicting order in the contracted bundle",
                              ((0, "abc"), (1, "abc"), (1, "ab"), (2, "abc")))
@@ -238,7 +238,7 @@ def configs() -> Dict[str, Contraction]:
                              170403092 + 5, "rank-k shape", ((0, "abc"), (1, "abc"), (1, "ab"), (2, "abc")))
     c["cfg5"] = Contraction("cfg5", "abcdef", "agbch", "hdgef", {**{x: 24 for x in "abcdef"}, "g": 96, "h": 96}, 1.0, 1.0, "uniform",
                             170403092 + 6, "6-D contraction",
-                            ((0, "abc"), (1, "ab"), (1, "abc"), (2, "ab"), (2, "abc"), (2, "hybrid")))
+                            ((0, "abc"), (1, "ab"), (1, "abc"), (1, "hybrid"), (2, "ab"), (2, "abc"), (2, "hybrid")))
     return c
 
 
