@@ -93,7 +93,8 @@ struct Smem {
 // Which elements of a KT x 128 operand tile a thread gathers in a k-step.
 //   MODE 0: lanes run along the 128 free entries x (the operand is contiguous along its free bundle)
 //   MODE 1: lanes run along the contracted entries k (contiguous along the contracted bundle); a wave covers 16 k
-//           (one 128-byte line) times 4 x, which also makes the transposing LDS store hit every bank pair twice
+//           (one 128-byte line) times 4 x (8 x with pairs).  With pairs, each half-wave takes half a line (4 pairs)
+//           of 8 columns, so that its 32 transposing LDS stores fall into 32 different bank pairs
 //   VEC   : an element pair per load: (x, x+1) in mode 0, (k, k+1) in mode 1
 // Load e of a thread is element (K0 + CK * e, X0 + CX * e).
 template <int MODE, int KT, bool VEC>
@@ -106,12 +107,12 @@ struct Map {
     __device__ static __forceinline__ int k0(int tid) {
         const int lane = tid & 63, w = tid >> 6;
         if (MODE == 0) return VEC ? (tid >> 6) : (tid >> 7);
-        return VEC ? 2 * ((lane & 7) + 8 * (w % KB)) : (lane & 15) + 16 * (w % KB);
+        return VEC ? 2 * ((lane & 3) + 4 * (lane >> 5) + 8 * (w % KB)) : (lane & 15) + 16 * (w % KB);
     }
     __device__ static __forceinline__ int x0(int tid) {
         const int lane = tid & 63, w = tid >> 6;
         if (MODE == 0) return VEC ? 2 * (tid & 63) : (tid & 127);
-        return VEC ? (lane >> 3) + 8 * (w / KB) : (lane >> 4) + 4 * (w / KB);
+        return VEC ? ((lane >> 2) & 7) + 8 * (w / KB) : (lane >> 4) + 4 * (w / KB);
     }
 };
 
