@@ -121,6 +121,7 @@ struct Bases {
     const int64_t* fix;   // &fix_tab[0][x0]
     const int64_t* step;  // &step_tab[slot 0][0][k0]
     double* stage;        // &tile[buffer 0][k0 * PITCH + x0]
+    int64_t fixv[4];      // lanes along the free entries: every load of a thread has the same x, its table entries live here
 };
 
 // Issue the loads of one k-step for every term; absent terms (index >= nterms) contribute zeros.
@@ -135,7 +136,7 @@ __device__ __forceinline__ void issue_fast(double (&ld)[NT][TM * KT / NTHREADS],
         } else {
 #pragma unroll
             for (int e = 0; e < M::N; ++e) {
-                const int64_t addr = b.fix[t * 128 + M::CX * e] + b.step[slot_off + t * KT + M::CK * e];
+                const int64_t addr = (M::CX == 0 ? b.fixv[t] : b.fix[t * 128 + M::CX * e]) + b.step[slot_off + t * KT + M::CK * e];
                 if (VEC) {
                     const double2_t v = *(gdbl2_t)addr;
                     ld[t][2 * e] = v.x;
@@ -522,6 +523,11 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         st.bb.fix = &S.b_fix[0][0] + MB::x0(tid);
         st.bb.step = &S.b_step[0][0][0] + MB::k0(tid);
         st.bb.stage = &S.b[0][0] + MB::k0(tid) * PITCH + MB::x0(tid);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            st.ba.fixv[t] = (MA::CX == 0 && t < NTA) ? st.ba.fix[t * 128] : 0;
+            st.bb.fixv[t] = (MB::CX == 0 && t < NTB) ? st.bb.fix[t * 128] : 0;
+        }
     }
 
     // ---- prologue: k-step 0 into LDS buffer 0; with two steps in flight also the gather of k-step 1 and the
