@@ -149,6 +149,57 @@ __device__ __forceinline__ void issue_fast(double (&ld)[NT][TM * KT / NTHREADS],
     }
 }
 
+// Gather without tables, for operands whose row and column scatter vectors are both runs of a constant stride
+// (plain matrices, the dense temporaries; what the block scatter vectors of Sec. 2.3 call regular): the address of
+// load e of term t is a wave-uniform base (scalar registers, scalar arithmetic) plus one per-lane 32-bit offset
+// that never changes.  No LDS reads and no vector ALU work per load.  Pairs only (VEC mapping).
+template <int NT>
+struct Affine {
+    uint32_t voff;    // per lane: byte offset of its element pair inside the wave's patch
+    int64_t u0[NT];   // per term: byte address of the wave's patch for load 0 of k-step 0
+    int64_t dE, dS;   // bytes from one load to the next, from one k-step to the next
+};
+
+template <int MODE, int NT, int KT>
+__device__ __forceinline__ void issue_affine(double (&ld)[NT][TM * KT / NTHREADS], const Affine<NT>& a, int target) {
+    typedef Map<MODE, KT, true> M;
+    typedef const __attribute__((address_space(1))) char* gbyte_t;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int64_t ub = a.u0[t] + (int64_t)target * a.dS;
+#pragma unroll
+        for (int e = 0; e < M::N; ++e) {
+            const double2_t v = *(gdbl2_t)((gbyte_t)(ub + e * a.dE) + a.voff);
+            ld[t][2 * e] = v.x;
+            ld[t][2 * e + 1] = v.y;
+        }
+    }
+}
+
+// Per-operand set-up of the table-free gather.  sx / sk: element strides along the free / the contracted bundle;
+// offx / offk: first free / contracted entry of each term; tile0: first free entry of the tile; w: wave index.
+template <int MODE, int NT, int KT>
+__device__ __forceinline__ void setup_affine(Affine<NT>& a, const double* base, int64_t sx, int64_t sk, const int64_t* offx, const int64_t* offk,
+                                             int64_t tile0, int lane, int w) {
+    typedef Map<MODE, KT, true> M;
+    constexpr int KB = KT / 16;
+    int64_t wx, wk;
+    if (MODE == 0) {
+        a.voff = (uint32_t)(8 * (2 * lane) * sx);
+        wx = 0;
+        wk = w;
+        a.dE = 8 * M::CK * sk;
+    } else {
+        a.voff = (uint32_t)(8 * (2 * ((lane & 3) + 4 * (lane >> 5)) * sk + ((lane >> 2) & 7) * sx));
+        wx = 8 * (w / KB);
+        wk = 16 * (w % KB);
+        a.dE = 8 * M::CX * sx;
+    }
+    a.dS = 8 * KT * sk;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) a.u0[t] = (int64_t)base + 8 * ((offx[t] + tile0 + wx) * sx + (offk[t] + wk) * sk);
+}
+
 // Signed sum of the terms (the operand sum of Sec. 4.1) into the LDS tile.
 template <int MODE, int NT, int KT, bool VEC, bool UNIT>
 __device__ __forceinline__ void stage_fast(const double (&ld)[NT][TM * KT / NTHREADS], double* __restrict__ dst, const double* __restrict__ coef) {
@@ -248,11 +299,18 @@ struct State {
     double la[D][NTA][NE], lb[D][NTB][NE];  // register sets of the gathers in flight
     unsigned pa[D], pb[D];
     bool issued_fast[D];       // the loads of a set were issued without padding checks
+    Affine<NTA> afa;           // table-free gather (valid when the product qualifies)
+    Affine<NTB> afb;
 
     // gather of k-step `target` into register set SET, with the table slot SLOT (= target % 2).
     // FAST: the caller knows that the k-step has no padding (target < kfull); otherwise that is decided here.
-    template <int SET, int SLOT, bool FAST>
+    template <int SET, int SLOT, bool FAST, bool AFF = false>
     __device__ __forceinline__ void issue(int target) {
+        if constexpr (FAST && AFF) {
+            issue_affine<AMODE, NTA, KT>(la[SET], afa, target);
+            issue_affine<BMODE, NTB, KT>(lb[SET], afb, target);
+            return;
+        }
         if (!FAST) issued_fast[SET] = target < kfull;
         if (FAST || issued_fast[SET]) {
             issue_fast<AMODE, NTA, KT, VA, CF::EXACT>(la[SET], ba, SLOT * NTA * KT, nA);
@@ -314,7 +372,7 @@ struct State {
     //        step ago), and set CUR ^ 1 (k-step step + 1, issued one step ago) is stored to LDS buffer CUR ^ 1.
     // D = 1: the loads of step + 1 are issued and, after the last group, stored.
     // ROLE: 0 = first wave of the SIMD, 1 = second, 2 = decided at run time (member `early`).
-    template <int CUR, int DONE, int ROLE, bool FAST, bool UNIT>
+    template <int CUR, int DONE, int ROLE, bool FAST, bool UNIT, bool AFF>
     __device__ __forceinline__ void between_groups(int step) {
         constexpr int NXT = CUR ^ 1;
         constexpr int ISET = (D == 2) ? CUR : 0, SSET = (D == 2) ? NXT : 0, ISLOT = (D == 2) ? CUR : NXT;
@@ -330,19 +388,19 @@ struct State {
         }
         if constexpr (ROLE != 1 && DONE == 0) {
             pin();
-            if (ROLE == 0 || early) issue<ISET, ISLOT, FAST>(step + D);
+            if (ROLE == 0 || early) issue<ISET, ISLOT, FAST, AFF>(step + D);
             pin();
         }
         if constexpr (ROLE != 0 && DONE == CF::ISSUE_LATE) {
             pin();
-            if (ROLE == 1 || !early) issue<ISET, ISLOT, FAST>(step + D);
+            if (ROLE == 1 || !early) issue<ISET, ISLOT, FAST, AFF>(step + D);
             pin();
         }
     }
 
     // instruction groups Q .. NQ-1 of the k-step in LDS buffer CUR; the fragments of group Q are in af/bf[Q % 2] and
     // those of group Q + 1 are read while group Q multiplies
-    template <int CUR, int Q, int ROLE, bool FAST, bool UNIT>
+    template <int CUR, int Q, int ROLE, bool FAST, bool UNIT, bool AFF>
     __device__ __forceinline__ void groups(double (&af)[2][4], double (&bf)[2][8], int step) {
         if constexpr (Q < NQ) {
             if constexpr (Q + 1 < NQ) read_frags<CUR, Q + 1>(af[(Q + 1) & 1], bf[(Q + 1) & 1]);
@@ -350,24 +408,24 @@ struct State {
             // keeps the two from drifting far apart (measured +1.5 %; with D = 1 it costs 2 %)
             if constexpr (D == 2 && (Q * 2) % NQ == 0) __builtin_amdgcn_s_setprio(1 - (Q * 2) / NQ);
             multiply(af[Q & 1], bf[Q & 1]);
-            between_groups<CUR, Q + 1, ROLE, FAST, UNIT>(step);
-            groups<CUR, Q + 1, ROLE, FAST, UNIT>(af, bf, step);
+            between_groups<CUR, Q + 1, ROLE, FAST, UNIT, AFF>(step);
+            groups<CUR, Q + 1, ROLE, FAST, UNIT, AFF>(af, bf, step);
         }
     }
 
     // One k-step.  The scatter entries of k-step step + D + 1 are fetched first (so that waiting for them at the end
     // of the step does not wait for the gather issued after them) and stored to the free table slot at the end.
-    template <int CUR, int ROLE, bool FAST, bool UNIT>
+    template <int CUR, int ROLE, bool FAST, bool UNIT, bool AFF>
     __device__ __forceinline__ void step_body(int step) {
         constexpr int ESLOT = (D == 2) ? (CUR ^ 1) : CUR;
         const int kn = (step + D + 1) * KT;
         const bool have = kn < ent_limit;
         const int64_t raw_entry = ent_ptr[have ? kn : 0];  // unconditional load: ent_ptr always points at readable memory
 
-        between_groups<CUR, 0, ROLE, FAST, UNIT>(step);
+        between_groups<CUR, 0, ROLE, FAST, UNIT, AFF>(step);
         double af[2][4], bf[2][8];
         read_frags<CUR, 0>(af[0], bf[0]);
-        groups<CUR, 0, ROLE, FAST, UNIT>(af, bf, step);
+        groups<CUR, 0, ROLE, FAST, UNIT, AFF>(af, bf, step);
 
         ent_dst[ESLOT ? ent_stride : 0] = have ? raw_entry * 8 : kSentinel;  // every thread stores: no branch around the wait
         __syncthreads();
@@ -376,19 +434,29 @@ struct State {
     // k-steps [0, end) (end even) of a tile whose gathers up to k-step end + D - 1 need no padding checks.  The
     // wave's role is a compile-time property of this loop and there is no control flow inside it, so the compiler's
     // wait counts for the loads in flight are exact.
-    template <int ROLE, bool UNIT>
+    template <int ROLE, bool UNIT, bool AFF>
     __device__ __forceinline__ void run_fast(int end) {
         for (int step = 0; step < end; step += 2) {
-            step_body<0, ROLE, true, UNIT>(step);
-            step_body<1, ROLE, true, UNIT>(step + 1);
+            step_body<0, ROLE, true, UNIT, AFF>(step);
+            step_body<1, ROLE, true, UNIT, AFF>(step + 1);
         }
+    }
+    template <int ROLE, bool UNIT>
+    __device__ __forceinline__ void run_fast(int end, bool affine) {
+        if constexpr (VA && VB) {
+            if (affine) {
+                run_fast<ROLE, UNIT, true>(end);
+                return;
+            }
+        }
+        run_fast<ROLE, UNIT, false>(end);
     }
 
     // k-steps [begin, nk) (both even): padding decided per k-step
     __device__ __forceinline__ void run_checked(int begin) {
         for (int step = begin; step < nk; step += 2) {
-            step_body<0, 2, false, false>(step);
-            step_body<1, 2, false, false>(step + 1);
+            step_body<0, 2, false, false, false>(step);
+            step_body<1, 2, false, false, false>(step + 1);
         }
     }
 };
@@ -553,18 +621,31 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     // (sums whose terms are counted at run time only occur for blocks a few tiles wide: they take the general loop)
     int nfast = CF::EXACT ? st.kfull - D : 0;
     nfast = nfast < 2 ? 0 : (nfast & ~1);
+    // table-free gather for products whose operands are both plain strided matrices (and gathered pair-wise)
+    constexpr int64_t kStrideLimit = (int64_t)1 << 20;  // keeps the per-lane byte offset within 32 bits
+    bool affine = false;
+    if constexpr (VA && VB && CF::EXACT) {
+        affine = P.A.rs_stride >= 0 && P.A.cs_stride >= 0 && P.B.rs_stride >= 0 && P.B.cs_stride >= 0 && P.A.rs_stride < kStrideLimit &&
+                 P.A.cs_stride < kStrideLimit && P.B.rs_stride < kStrideLimit && P.B.cs_stride < kStrideLimit;
+        if (affine) {
+            const int wu = __builtin_amdgcn_readfirstlane(wave);
+            // A: free bundle = rows, contracted = columns; B: free bundle = columns, contracted = rows
+            setup_affine<AMODE, NTA, KT>(st.afa, Abase, P.A.rs_stride, P.A.cs_stride, P.A.roff, P.A.coff, i0, lane, wu);
+            setup_affine<BMODE, NTB, KT>(st.afb, Bbase, P.B.cs_stride, P.B.rs_stride, P.B.coff, P.B.roff, j0, lane, wu);
+        }
+    }
     if (nfast > 0) {
         const bool role0 = __builtin_amdgcn_readfirstlane(wm) == 0;
         if (CF::EXACT && st.unitA && st.unitB) {  // a loop of its own: no multiply (or no arithmetic at all) per element
             if (role0)
-                st.template run_fast<0, CF::EXACT>(nfast);
+                st.template run_fast<0, CF::EXACT>(nfast, affine);
             else
-                st.template run_fast<1, CF::EXACT>(nfast);
+                st.template run_fast<1, CF::EXACT>(nfast, affine);
         } else {
             if (role0)
-                st.template run_fast<0, false>(nfast);
+                st.template run_fast<0, false>(nfast, affine);
             else
-                st.template run_fast<1, false>(nfast);
+                st.template run_fast<1, false>(nfast, affine);
         }
         if constexpr (D == 2) st.issued_fast[1] = true;  // the gather of k-step nfast + 1 is in flight
     }

@@ -164,6 +164,21 @@ BundleDesc make_dense(int64_t len, int64_t stride) {
     return b;
 }
 
+// Stride s with scat[i] == i * s for every entry of the bundle's scatter vector (its dimensions, fastest first, merge
+// into one run: each stride is the previous stride times the previous length), or -1.
+int64_t affine_stride(const BundleDesc& b) {
+    int64_t stride = -1, next = 0;
+    for (int d = 0; d < b.ndim; ++d) {
+        if (b.len[d] <= 1) continue;
+        if (stride < 0)
+            stride = b.stride[d];
+        else if (b.stride[d] != next)
+            return -1;
+        next = b.stride[d] * b.len[d];
+    }
+    return stride < 0 ? 0 : stride;
+}
+
 void block_tables(int level, std::vector<std::vector<int>>& U, std::vector<std::vector<int>>& V, std::vector<std::vector<int>>& W) {
     // L-level coefficients as the Kronecker product of the one-level triples, on the 2^L x 2^L block grid.
     int g = 1 << level, R = 1;
@@ -207,6 +222,7 @@ void set_operand(Operand& op, const int64_t* rs, const int64_t* cs, int64_t rs_l
     op.cs_len = cs_len;
     op.space = space;
     op.base_off = base_off;
+    op.rs_stride = op.cs_stride = -1;
 }
 
 void add_term(Operand& op, int64_t roff, int64_t coff, double coef) {
@@ -375,6 +391,11 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         if (max_total > 0 && tc::launch_planner(p->bundles_dev, V_COUNT, max_total, p->bs_block, p->store_dev, stream)) return TC_ERR_HIP;
     }
     auto vec = [p](int id) -> const int64_t* { return p->store_dev ? p->store_dev + p->bundles[id].out_off : nullptr; };
+    auto setop = [&](Operand& op, int rs_id, int cs_id, int64_t rs_len, int64_t cs_len, int space, int64_t base_off) {
+        set_operand(op, vec(rs_id), vec(cs_id), rs_len, cs_len, space, base_off);
+        op.rs_stride = affine_stride(p->bundles[rs_id]);
+        op.cs_stride = affine_stride(p->bundles[cs_id]);
+    };
 
     struct Pending {
         Product pr;
@@ -433,14 +454,14 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
                     // temporaries: dense, column-major, one block extent each
                     Product acc;  // M -> destinations of C
                     std::memset(&acc, 0, sizeof acc);
-                    set_operand(acc.A, vec(V_RSM), vec(V_CSM), p->mb, p->nb, 1, p->wsM);
+                    setop(acc.A, V_RSM, V_CSM, p->mb, p->nb, 1, p->wsM);
                     add_term(acc.A, 0, 0, 1.0);
                     acc.C = q.pr.C;
                     acc.mb = p->mb;
                     acc.nb = p->nb;
                     acc.first_mask = first_mask;
                     Product mul = q.pr;  // (sum A)(sum B) -> M
-                    set_operand(mul.C, vec(V_RSM), vec(V_CSM), p->mb, p->nb, 1, p->wsM);
+                    setop(mul.C, V_RSM, V_CSM, p->mb, p->nb, 1, p->wsM);
                     add_term(mul.C, 0, 0, 1.0);
                     mul.first_mask = 1;
                     mul.overwrite = 1;
@@ -451,11 +472,11 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
                         std::memset(&sa, 0, sizeof sa);
                         std::memset(&sb, 0, sizeof sb);
                         sa.A = q.pr.A;
-                        set_operand(sa.C, vec(V_RSTA), vec(V_CSTA), p->mb, p->kb, 1, p->wsTA);
+                        setop(sa.C, V_RSTA, V_CSTA, p->mb, p->kb, 1, p->wsTA);
                         add_term(sa.C, 0, 0, 1.0);
                         sa.mb = p->mb, sa.nb = p->kb, sa.first_mask = 1, sa.overwrite = 1;
                         sb.A = q.pr.B;
-                        set_operand(sb.C, vec(V_RSTB), vec(V_CSTB), p->kb, p->nb, 1, p->wsTB);
+                        setop(sb.C, V_RSTB, V_CSTB, p->kb, p->nb, 1, p->wsTB);
                         add_term(sb.C, 0, 0, 1.0);
                         sb.mb = p->kb, sb.nb = p->nb, sb.first_mask = 1, sb.overwrite = 1;
                         int i0 = (int)p->prods.size();
@@ -463,9 +484,9 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
                         p->prods.push_back(sb);
                         p->steps.push_back(Step{STEP_LINCOMB, i0, 1, {}, p->mb, p->kb, p->a_mode == 0 ? 1 : 0, 0});
                         p->steps.push_back(Step{STEP_LINCOMB, i0 + 1, 1, {}, p->kb, p->nb, p->b_mode == 1 ? 1 : 0, 1});
-                        set_operand(mul.A, vec(V_RSTA), vec(V_CSTA), p->mb, p->kb, 1, p->wsTA);
+                        setop(mul.A, V_RSTA, V_CSTA, p->mb, p->kb, 1, p->wsTA);
                         add_term(mul.A, 0, 0, 1.0);
-                        set_operand(mul.B, vec(V_RSTB), vec(V_CSTB), p->kb, p->nb, 1, p->wsTB);
+                        setop(mul.B, V_RSTB, V_CSTB, p->kb, p->nb, 1, p->wsTB);
                         add_term(mul.B, 0, 0, 1.0);
                         cfg = tc::FusedConfig{0, 1, 1, 1, 1, 1, 1, 1, 0};  // dense temporaries: block extents are multiples of 16
                     } else {
@@ -498,7 +519,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         std::memset(&pr, 0, sizeof pr);
         set_operand(pr.A, nullptr, nullptr, 0, 0, 0, 0);
         set_operand(pr.B, nullptr, nullptr, 0, 0, 0, 0);
-        set_operand(pr.C, vec(V_RSC), vec(V_CSC), p->m, p->n, 0, 0);
+        setop(pr.C, V_RSC, V_CSC, p->m, p->n, 0, 0);
         add_term(pr.C, 0, 0, 1.0);
         pr.mb = p->m;
         pr.nb = p->n;
@@ -512,11 +533,11 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         for (int s = 0; s < split; ++s) {
             Product mul;
             std::memset(&mul, 0, sizeof mul);
-            set_operand(mul.A, vec(V_RSA), vec(V_CSA), p->m, p->k, 0, 0);
+            setop(mul.A, V_RSA, V_CSA, p->m, p->k, 0, 0);
             add_term(mul.A, 0, s * kc, 1.0);
-            set_operand(mul.B, vec(V_RSB), vec(V_CSB), p->k, p->n, 0, 0);
+            setop(mul.B, V_RSB, V_CSB, p->k, p->n, 0, 0);
             add_term(mul.B, s * kc, 0, 1.0);
-            set_operand(mul.C, vec(V_RSM), vec(V_CSM), p->mb, split * p->nb, 1, p->wsM);
+            setop(mul.C, V_RSM, V_CSM, p->mb, split * p->nb, 1, p->wsM);
             add_term(mul.C, 0, s * p->nb, 1.0);
             mul.mb = p->mb, mul.nb = p->nb, mul.kb = kc;
             mul.first_mask = 1, mul.overwrite = 1;
@@ -533,9 +554,9 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         p->steps.push_back(Step{STEP_FUSED, first, split, cfg, p->mb, p->nb, 0, 0});
         Product acc;
         std::memset(&acc, 0, sizeof acc);
-        set_operand(acc.A, vec(V_RSM), vec(V_CSM), p->mb, split * p->nb, 1, p->wsM);
+        setop(acc.A, V_RSM, V_CSM, p->mb, split * p->nb, 1, p->wsM);
         for (int s = 0; s < split; ++s) add_term(acc.A, 0, s * p->nb, 1.0);
-        set_operand(acc.C, vec(V_RSC), vec(V_CSC), p->m, p->n, 0, 0);
+        setop(acc.C, V_RSC, V_CSC, p->m, p->n, 0, 0);
         add_term(acc.C, 0, 0, 1.0);
         acc.mb = p->mb, acc.nb = p->nb;
         acc.first_mask = 1;
@@ -566,7 +587,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
             if (oa.empty() || ob.empty() || oc.empty()) continue;
             // where the second level reads its operands: (vectors, lengths, space, offset of the first-level block, real extents)
             struct Src {
-                const int64_t *rs, *cs;
+                int rs, cs;  // vector ids
                 int64_t rs_len, cs_len, r0, c0, rows, cols;
                 int space;
                 int64_t base;
@@ -577,51 +598,51 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
             sa.direct = oa.size() == 1 && oa[0].sign == 1;
             sb.direct = ob.size() == 1 && ob[0].sign == 1;
             if (sa.direct) {
-                sa = Src{vec(V_RSA), vec(V_CSA), p->m, p->k, oa[0].r * MB, oa[0].c * KB, real(p->m, oa[0].r * MB, MB), real(p->k, oa[0].c * KB, KB), 0, 0, true};
+                sa = Src{V_RSA, V_CSA, p->m, p->k, oa[0].r * MB, oa[0].c * KB, real(p->m, oa[0].r * MB, MB), real(p->k, oa[0].c * KB, KB), 0, 0, true};
             } else {
                 Product sum;
                 std::memset(&sum, 0, sizeof sum);
-                set_operand(sum.A, vec(V_RSA), vec(V_CSA), p->m, p->k, 0, 0);
+                setop(sum.A, V_RSA, V_CSA, p->m, p->k, 0, 0);
                 int64_t rows = 0, cols = 0;
                 for (const Blk& b : oa) {
                     add_term(sum.A, b.r * MB, b.c * KB, b.sign);
                     rows = std::max(rows, real(p->m, b.r * MB, MB));
                     cols = std::max(cols, real(p->k, b.c * KB, KB));
                 }
-                set_operand(sum.C, vec(V_RSTA), vec(V_CSTA), MB, KB, 1, p->wsTA);
+                setop(sum.C, V_RSTA, V_CSTA, MB, KB, 1, p->wsTA);
                 add_term(sum.C, 0, 0, 1.0);
                 sum.mb = MB, sum.nb = KB, sum.first_mask = 1, sum.overwrite = 1;
                 p->steps.push_back(Step{STEP_LINCOMB, (int)p->prods.size(), 1, {}, MB, KB, p->a_mode == 0 ? 1 : 0, 0});
                 p->prods.push_back(sum);
-                sa = Src{vec(V_RSTA), vec(V_CSTA), MB, KB, 0, 0, rows, cols, 1, p->wsTA, false};
+                sa = Src{V_RSTA, V_CSTA, MB, KB, 0, 0, rows, cols, 1, p->wsTA, false};
             }
             if (sb.direct) {
-                sb = Src{vec(V_RSB), vec(V_CSB), p->k, p->n, ob[0].r * KB, ob[0].c * NB, real(p->k, ob[0].r * KB, KB), real(p->n, ob[0].c * NB, NB), 0, 0, true};
+                sb = Src{V_RSB, V_CSB, p->k, p->n, ob[0].r * KB, ob[0].c * NB, real(p->k, ob[0].r * KB, KB), real(p->n, ob[0].c * NB, NB), 0, 0, true};
             } else {
                 Product sum;
                 std::memset(&sum, 0, sizeof sum);
-                set_operand(sum.A, vec(V_RSB), vec(V_CSB), p->k, p->n, 0, 0);
+                setop(sum.A, V_RSB, V_CSB, p->k, p->n, 0, 0);
                 int64_t rows = 0, cols = 0;
                 for (const Blk& b : ob) {
                     add_term(sum.A, b.r * KB, b.c * NB, b.sign);
                     rows = std::max(rows, real(p->k, b.r * KB, KB));
                     cols = std::max(cols, real(p->n, b.c * NB, NB));
                 }
-                set_operand(sum.C, vec(V_RSTB), vec(V_CSTB), KB, NB, 1, p->wsTB);
+                setop(sum.C, V_RSTB, V_CSTB, KB, NB, 1, p->wsTB);
                 add_term(sum.C, 0, 0, 1.0);
                 sum.mb = KB, sum.nb = NB, sum.first_mask = 1, sum.overwrite = 1;
                 p->steps.push_back(Step{STEP_LINCOMB, (int)p->prods.size(), 1, {}, KB, NB, p->b_mode == 1 ? 1 : 0, 1});
                 p->prods.push_back(sum);
-                sb = Src{vec(V_RSTB), vec(V_CSTB), KB, NB, 0, 0, rows, cols, 1, p->wsTB, false};
+                sb = Src{V_RSTB, V_CSTB, KB, NB, 0, 0, rows, cols, 1, p->wsTB, false};
             }
             std::vector<Pending> list;
             for (int q = 0; q < R2; ++q) {
                 Pending e;
                 std::memset(&e.pr, 0, sizeof e.pr);
                 std::memset(&e.view, 0, sizeof e.view);
-                set_operand(e.pr.A, sa.rs, sa.cs, sa.rs_len, sa.cs_len, sa.space, sa.base);
-                set_operand(e.pr.B, sb.rs, sb.cs, sb.rs_len, sb.cs_len, sb.space, sb.base);
-                set_operand(e.pr.C, vec(V_RSC), vec(V_CSC), p->m, p->n, 0, 0);
+                setop(e.pr.A, sa.rs, sa.cs, sa.rs_len, sa.cs_len, sa.space, sa.base);
+                setop(e.pr.B, sb.rs, sb.cs, sb.rs_len, sb.cs_len, sb.space, sb.base);
+                setop(e.pr.C, V_RSC, V_CSC, p->m, p->n, 0, 0);
                 e.pr.mb = p->mb, e.pr.nb = p->nb, e.pr.kb = p->kb;
                 for (int i = 0; i < h; ++i)
                     for (int j = 0; j < h; ++j) {
@@ -669,9 +690,9 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
             Pending e;
             std::memset(&e.pr, 0, sizeof e.pr);
             std::memset(&e.view, 0, sizeof e.view);
-            set_operand(e.pr.A, vec(V_RSA), vec(V_CSA), p->m, p->k, 0, 0);
-            set_operand(e.pr.B, vec(V_RSB), vec(V_CSB), p->k, p->n, 0, 0);
-            set_operand(e.pr.C, vec(V_RSC), vec(V_CSC), p->m, p->n, 0, 0);
+            setop(e.pr.A, V_RSA, V_CSA, p->m, p->k, 0, 0);
+            setop(e.pr.B, V_RSB, V_CSB, p->k, p->n, 0, 0);
+            setop(e.pr.C, V_RSC, V_CSC, p->m, p->n, 0, 0);
             e.pr.mb = p->mb;
             e.pr.nb = p->nb;
             e.pr.kb = p->kb;

@@ -21,6 +21,8 @@ struct Operand {
     int32_t space;      // 0: the caller's tensor (A, B or C by role); 1: the workspace
     int32_t nterms;
     int64_t base_off;   // element offset of the matrix view inside its space
+    int64_t rs_stride;  // >= 0: rs[i] == i * rs_stride for every i (the bundle is one run of a constant stride); -1 otherwise
+    int64_t cs_stride;
     int64_t roff[kMaxTerms];  // first row of each block
     int64_t coff[kMaxTerms];  // first column of each block
     double coef[kMaxTerms];   // +1 / -1
