@@ -90,8 +90,16 @@ typedef struct {
     int split_k;    /* level 0 only: 0 or 1 = off; 2..4 = cut the contracted bundle into that many chunks whose products
                      * run side by side into dense temporaries and are summed into C by one element-wise pass (for
                      * shapes with too few 128 x 128 tiles to fill the device; needs workspace; not from the paper);
-                     * -1 = as many chunks as the performance model likes best */
-    int reserved[4];
+                     * -1 = as many chunks as the performance model likes best (1 when tail_split is automatic:
+                     * the tail split then does this job inside the kernel) */
+    int tail_split; /* 0 = automatic: where the tiles of a launch do not fill a whole number of rounds of the device's
+                     * compute units, the left-over tiles are cut along the contracted bundle into chunks computed by
+                     * one workgroup each, and a small second kernel adds the chunks (in a fixed order: results are
+                     * reproducible) and updates the destinations; the chunk count is the one the performance model
+                     * likes best, possibly none; needs workspace for the chunks (not from the paper);
+                     * -1 = never; 2..16 = that many chunks (each a multiple of 64 entries long, so possibly fewer)
+                     * in every launch that has a tail, whatever the model says (for tests and measurements) */
+    int reserved[3];
 } tc_options_t;
 
 /* Facts about a plan (tc_plan_info). */
@@ -134,10 +142,26 @@ typedef struct {
     int reserved[3];
 } tc_model_params_t;
 
+/* One kernel launch of the plan's schedule, for inspection (tc_plan_launch). */
+typedef struct {
+    int kind;             /* 0: fused kernel (products), 1: element-wise kernel */
+    int n_products;       /* fused: products sharing the launch */
+    int max_terms;        /* fused: largest number of blocks in an operand sum of the launch */
+    int tail_tiles;       /* fused: tiles cut into chunks (0: none); a split launch is followed by the kernel that adds the chunks */
+    int tail_chunks;      /* chunks per tail tile */
+    int reserved[3];
+    int64_t rows, cols;   /* extents of one product (fused) or of the pass (element-wise) */
+    int64_t depth;        /* fused: contracted extent of one product */
+    int64_t tiles;        /* fused: 128 x 128 tiles of the launch */
+    int64_t tail_kc;      /* contracted entries per chunk */
+} tc_launch_info_t;
+
 /* Modelled time of one tc_contract() with beta != 0, in seconds, split as in Sec. 5 eq. (2)-(4):
  * arith = W_a^x T_a^x (whole waves of tiles), c_update = W_m^{C x} T_m^{C x} (destination updates of the products),
  * temporaries = the T_m^{+} terms (element-wise passes of the AB and Naive variants), launch = launches * t_launch.
- * Reading A and B is taken as hidden behind the matrix cores. */
+ * Reading A and B is taken as hidden behind the matrix cores.  A launch that splits its tail counts its whole tiles in
+ * whole waves of full depth plus the chunks in whole waves of chunk depth (arith), the chunks written and read back
+ * (temporaries) and one more launch. */
 typedef struct {
     double total, arith, c_update, temporaries, launch;
 } tc_model_time_t;
@@ -151,8 +175,9 @@ int tc_plan(tc_plan_t **plan_out, const tc_tensor_desc_t *A, const tc_tensor_des
 int tc_plan_ex(tc_plan_t **plan_out, const tc_tensor_desc_t *A, const tc_tensor_desc_t *B, const tc_tensor_desc_t *C,
                int level, int variant, const tc_options_t *opts, void *stream);
 
-/* Bytes of device workspace tc_contract() needs (0 for the ABC variant and for level 0 without split_k;
- * AB: one block of C; Naive: plus one block of A and of B; HYBRID: one first-level block of A and of B). */
+/* Bytes of device workspace tc_contract() needs: the temporaries of the variant (none for ABC and for level 0 without
+ * split_k; AB: one block of C; Naive: plus one block of A and of B; HYBRID: one first-level block of A and of B) plus,
+ * where a launch splits its tail (tc_options_t.tail_split), 128 KiB per chunk of a tail tile (at most 128 MiB). */
 size_t tc_plan_workspace_bytes(const tc_plan_t *plan);
 
 /* C := alpha * A * B + beta * C.  A_dev, B_dev, C_dev, workspace_dev are device pointers owned by the caller;
@@ -188,6 +213,8 @@ int tc_plan_predict(const tc_plan_t *plan, const tc_model_params_t *params, tc_m
 int tc_plan_info(const tc_plan_t *plan, tc_plan_info_t *out);
 /* Schedule entry `index` (0 <= index < n_products). */
 int tc_plan_schedule(const tc_plan_t *plan, int index, tc_product_t *out);
+/* Launch `index` (0 <= index < n_launches; a fused launch that splits its tail counts once). */
+int tc_plan_launch(const tc_plan_t *plan, int index, tc_launch_info_t *out);
 /* Copy one planner output to host memory: which = 0..5 scatter vectors rscat_A, cscat_A, rscat_B, cscat_B, rscat_C, cscat_C;
  * 6..11 the block scatter vectors rbs_A, cbs_A, rbs_B, cbs_B, rbs_C, cbs_C (Sec. 2.3).  Returns the number of entries
  * (also when host_out is NULL), or a negative status; copies at most `capacity` entries.  Synchronous. */

@@ -118,6 +118,12 @@ def granular_time(launches: Sequence[dict], p: MachineParams) -> Dict[str, float
     k_C = kb (one update per tile): c_elems * tau_b.  Reading A and B (T_m^{A x}, T_m^{B x}) is taken as hidden behind
     the matrix cores (weight 0).  An element-wise launch is {"kind": "add", "elems": elements read or written}: the
     T_m^{+} terms, elems * tau_b.  Every launch costs t_launch.
+
+    A multiplying launch may carry "tail": {"tiles": r, "chunks": s, "kc": kc}: r of its tiles are cut along the
+    contracted bundle into s chunks of kc entries, computed by one unit each and stored; a further launch reads them
+    back and adds them.  The whole tiles then count in whole waves of depth kb, the r * s chunks in whole waves of
+    depth kc, the chunks written and read back are a T_m^{+} term (2 * r * s * tile_m * tile_n elements), and the
+    second launch costs t_launch.
     """
     tau_b = 8.0 / (p.rho_b * p.bandwidth)
     out = {"arith": 0.0, "c_update": 0.0, "temporaries": 0.0, "launch": 0.0}
@@ -130,8 +136,18 @@ def granular_time(launches: Sequence[dict], p: MachineParams) -> Dict[str, float
             terms = max(q["terms"] for q in L["products"])
             rho = p.rho_a[0] if terms <= 1 else p.rho_a[1] if terms <= 2 else p.rho_a[2]
             kb = L["products"][0]["kb"]
-            waves = math.ceil(tiles / p.units)
-            out["arith"] += waves * (p.units * 2.0 * p.tile_m * p.tile_n * kb / (rho * p.peak_flops) + p.t_tile)
+
+            def wave(depth):
+                return p.units * 2.0 * p.tile_m * p.tile_n * depth / (rho * p.peak_flops) + p.t_tile
+
+            tail = L.get("tail")
+            whole = tiles - (tail["tiles"] if tail else 0)
+            out["arith"] += math.ceil(whole / p.units) * wave(kb)
+            if tail:
+                pieces = tail["tiles"] * tail["chunks"]
+                out["arith"] += math.ceil(pieces / p.units) * wave(tail["kc"])
+                out["temporaries"] += 2.0 * pieces * p.tile_m * p.tile_n * tau_b
+                out["launch"] += p.t_launch
             out["c_update"] += sum(q["c_elems"] for q in L["products"]) * tau_b
         else:
             out["temporaries"] += L["elems"] * tau_b

@@ -70,7 +70,13 @@ class tc_tensor_desc_t(ctypes.Structure):
 
 class tc_options_t(ctypes.Structure):
     _fields_ = [("bs_block", ctypes.c_int), ("host_only", ctypes.c_int), ("no_merge", ctypes.c_int), ("split_k", ctypes.c_int),
-                ("reserved", ctypes.c_int * 4)]
+                ("tail_split", ctypes.c_int), ("reserved", ctypes.c_int * 3)]
+
+
+class tc_launch_info_t(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int), ("n_products", ctypes.c_int), ("max_terms", ctypes.c_int), ("tail_tiles", ctypes.c_int),
+                ("tail_chunks", ctypes.c_int), ("reserved", ctypes.c_int * 3), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("depth", ctypes.c_int64), ("tiles", ctypes.c_int64), ("tail_kc", ctypes.c_int64)]
 
 
 class tc_plan_info_t(ctypes.Structure):
@@ -135,6 +141,8 @@ def load_library():
         lib.tc_plan_info.argtypes = [vp, ctypes.POINTER(tc_plan_info_t)]
         lib.tc_plan_schedule.restype = ci
         lib.tc_plan_schedule.argtypes = [vp, ci, ctypes.POINTER(tc_product_t)]
+        lib.tc_plan_launch.restype = ci
+        lib.tc_plan_launch.argtypes = [vp, ci, ctypes.POINTER(tc_launch_info_t)]
         lib.tc_model_defaults.restype = ci
         lib.tc_model_defaults.argtypes = [ctypes.POINTER(tc_model_params_t)]
         lib.tc_plan_predict.restype = ci
@@ -190,8 +198,9 @@ class Plan:
 
 
 def tc_plan(A, B, C, level: int = 0, variant="abc", stream=None, bs_block: int = 0, host_only: bool = False,
-            no_merge: bool = False, split_k: int = 0) -> Plan:
-    """A, B, C: (labels, lengths, strides) triples or objects with .idx/.lens/.strides."""
+            no_merge: bool = False, split_k: int = 0, tail_split: int = 0) -> Plan:
+    """A, B, C: (labels, lengths, strides) triples or objects with .idx/.lens/.strides.
+    tail_split: 0 = automatic, -1 = never, 2..16 = forced chunk count (see tc_options_t)."""
     lib = load_library()
     ds = []
     for T in (A, B, C):
@@ -201,7 +210,7 @@ def tc_plan(A, B, C, level: int = 0, variant="abc", stream=None, bs_block: int =
             ds.append(_desc(*T))
     v = VARIANTS[variant] if isinstance(variant, str) else int(variant)
     out = ctypes.c_void_p()
-    opts = tc_options_t(int(bs_block), int(bool(host_only)), int(bool(no_merge)), int(split_k))
+    opts = tc_options_t(int(bs_block), int(bool(host_only)), int(bool(no_merge)), int(split_k), int(tail_split))
     rc = lib.tc_plan_ex(ctypes.byref(out), ctypes.byref(ds[0]), ctypes.byref(ds[1]), ctypes.byref(ds[2]), int(level), v,
                         ctypes.byref(opts), _stream(stream))
     if rc != 0:
@@ -266,6 +275,19 @@ def tc_plan_predict(plan: Plan, params: Optional[dict] = None) -> dict:
     if rc != 0:
         raise TcError(rc, "tc_plan_predict")
     return {k: getattr(out, k) for k, _ in tc_model_time_t._fields_}
+
+
+def tc_plan_launches(plan: Plan) -> list:
+    """Every launch of the schedule (tc_plan_launch) as a dict."""
+    lib = load_library()
+    out = []
+    for i in range(tc_plan_info(plan)["n_launches"]):
+        L = tc_launch_info_t()
+        rc = lib.tc_plan_launch(plan.handle, i, ctypes.byref(L))
+        if rc != 0:
+            raise TcError(rc, "tc_plan_launch")
+        out.append({k: getattr(L, k) for k, _ in tc_launch_info_t._fields_ if k != "reserved"})
+    return out
 
 
 def tc_plan_schedule(plan: Plan) -> list:

@@ -1,4 +1,5 @@
-// Device side of libstrassen_tc (gfx950 / CDNA4 only), except the fused kernel (tc_fused.h).
+// Device side of libstrassen_tc (gfx950 / CDNA4 only), except the fused kernel (tc_fused.h; its launchers are
+// instantiated one family per translation unit, tc_fused_*.hip).
 //
 //  planner kernels   scatter vectors and block scatter vectors of the matrix view (Sec. 2.3)
 //  lincomb kernel    element-wise  dst_d = g_d * (sum_t c_t src_t) + f_d * dst_d  on matrix views; used for
@@ -7,6 +8,7 @@
 //  launchers         thin host wrappers the planner code in tc_host.cpp calls
 #include <hip/hip_runtime.h>
 
+#include "tc_fused.h"
 #include "tc_internal.h"
 
 namespace tc {
@@ -134,22 +136,21 @@ int launch_planner(const BundleDesc* descs_dev, int nvec, int64_t max_total, int
     return (int)hipGetLastError();
 }
 
-namespace fused {
-constexpr int kTile = 128;
-template <int NTA, int NTB, bool EXACT>
-int launch_family(int a_mode, int b_mode, int vec, int c_mode, const Product* prods, int first, int count, int tiles_m, int tiles_n,
-                  const double* A, const double* B, double* C, double* W, double alpha, double beta, hipStream_t stream);
-}  // namespace fused
-
 int launch_fused(const FusedConfig& cfg, const Product* prods_dev, int first, int count, int64_t mb, int64_t nb, const double* A,
-                 const double* B, double* C, double* W, double alpha, double beta, void* stream) {
-    const int64_t tiles_m = (mb + fused::kTile - 1) / fused::kTile, tiles_n = (nb + fused::kTile - 1) / fused::kTile;
+                 const double* B, double* C, double* W, double alpha, double beta, int tail_tiles, int tail_chunks, int64_t tail_kc,
+                 int64_t partial_off, void* stream) {
+    const int64_t tiles_m = (mb + fused::TM - 1) / fused::TM, tiles_n = (nb + fused::TN - 1) / fused::TN;
     if (tiles_m <= 0 || tiles_n <= 0 || tiles_m > (1 << 20) || tiles_n > (1 << 20)) return (int)hipErrorInvalidValue;
+    if (tail_tiles < 0 || tail_kc < 0 || tail_kc > 0x7fffffff || (tail_tiles > 0 && !W)) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
     const int vec = (cfg.a_vec ? 1 : 0) | (cfg.b_vec ? 2 : 0);  // pair-wise gathers (pairs are 8-byte aligned)
     const int tm = (int)tiles_m, tn = (int)tiles_n;
-#define TC_FAMILY(NA, NB, EX) \
-    return fused::launch_family<NA, NB, EX>(cfg.a_mode, cfg.b_mode, vec, cfg.c_mode, prods_dev, first, count, tm, tn, A, B, C, W, alpha, beta, st)
+    const fused::TailSplit tail{tail_tiles, tail_chunks, (int)tail_kc, tail_tiles > 0 ? W + partial_off : nullptr};
+    int err = (int)hipErrorInvalidValue;
+#define TC_FAMILY(NA, NB, EX)                                                                                                             \
+    err = fused::launch_family<NA, NB, EX>(cfg.a_mode, cfg.b_mode, vec, cfg.c_mode, prods_dev, first, count, tm, tn, A, B, C, W, alpha, beta, \
+                                           tail, st);                                                                                      \
+    break
     switch (cfg.nta * 8 + cfg.ntb) {
         case 0: TC_FAMILY(4, 4, false);
         case 1 * 8 + 1: TC_FAMILY(1, 1, true);
@@ -161,9 +162,18 @@ int launch_fused(const FusedConfig& cfg, const Product* prods_dev, int first, in
         case 2 * 8 + 4: TC_FAMILY(2, 4, true);
         case 4 * 8 + 2: TC_FAMILY(4, 2, true);
         case 4 * 8 + 4: TC_FAMILY(4, 4, true);
-        default: return (int)hipErrorInvalidValue;
+        default: break;
     }
 #undef TC_FAMILY
+    if (err || tail_tiles == 0) return err;
+    const int main_count = (int)((int64_t)count * tm * tn - tail_tiles);
+    if (cfg.c_mode == 0)
+        hipLaunchKernelGGL(fused::tail_fixup_kernel<true>, dim3((unsigned)tail_tiles), dim3(fused::NTHREADS), 0, st, prods_dev, first, tm, tn,
+                           main_count, tail_tiles, tail_chunks, tail.partial, C, W, alpha, beta);
+    else
+        hipLaunchKernelGGL(fused::tail_fixup_kernel<false>, dim3((unsigned)tail_tiles), dim3(fused::NTHREADS), 0, st, prods_dev, first, tm, tn,
+                           main_count, tail_tiles, tail_chunks, tail.partial, C, W, alpha, beta);
+    return (int)hipGetLastError();
 }
 
 int launch_lincomb(const Product* prods_dev, int index, int64_t mb, int64_t nb, int lanes_along_rows, const double* A, const double* B,

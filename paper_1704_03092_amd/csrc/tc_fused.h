@@ -461,33 +461,64 @@ struct State {
     }
 };
 
+// Which tile a logical workgroup id stands for: product pidx of the launch, tile row tm, tile column tn.  Ids walk
+// GROUP_M tile rows at a time, so that workgroups resident together share A and B panels in their XCD's L2.
+struct TileId {
+    int pidx, tm, tn;
+};
+__device__ __forceinline__ TileId tile_of(int lid, int tiles_m, int tiles_n) {
+    const int per_prod = tiles_m * tiles_n;
+    TileId t;
+    t.pidx = lid / per_prod;
+    int rem = lid - t.pidx * per_prod;
+    const int gsz = GROUP_M * tiles_n;
+    const int grp = rem / gsz;
+    const int gm0 = grp * GROUP_M;
+    const int gh = (tiles_m - gm0) < GROUP_M ? (tiles_m - gm0) : GROUP_M;
+    rem -= grp * gsz;
+    t.tm = gm0 + rem % gh;
+    t.tn = rem / gh;
+    return t;
+}
+
+// Workgroups [0, main_count) compute one whole tile each.  The tiles left over after the last full round of the
+// machine (tail_tiles of them, logical ids main_count ...) are cut along the contracted bundle into chunks of tail_kc
+// entries, one workgroup per (tile, chunk): workgroup main_count + c * tail_tiles + t stores the raw accumulators of
+// chunk c of tail tile t as a dense 128 x 128 tile at partial + 16384 * (c * tail_tiles + t); tail_fixup_kernel adds
+// the chunks in a fixed order and updates the destinations.
 template <int AMODE, int BMODE, class CF, bool VA, bool VB>
 __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __restrict__ prods, int first, int tiles_m, int tiles_n,
                                                             const double* __restrict__ Au, const double* __restrict__ Bu,
-                                                            double* __restrict__ Cu, double* __restrict__ W, double alpha, double beta, int c_mode) {
+                                                            double* __restrict__ Cu, double* __restrict__ W, double alpha, double beta, int c_mode,
+                                                            int main_count, int tail_tiles, int tail_kc, double* __restrict__ partial) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     Smem<CF>& S = *reinterpret_cast<Smem<CF>*>(smem_raw);
     const int tid = threadIdx.x;
     typedef State<AMODE, BMODE, CF, VA, VB> St;
     constexpr int KT = CF::KT, NTA = CF::NTA, NTB = CF::NTB, D = CF::D;
 
-    // ---- which tile: spread consecutive logical ids over one XCD (block b runs on XCD b % 8), then walk
-    //      GROUP_M tile rows at a time so that co-resident workgroups share A and B panels in that XCD's L2 ----
-    const int total = gridDim.x, bid = blockIdx.x;
-    const int q8 = total >> 3, r8 = total & 7, xcd = bid & 7;
-    const int lid = xcd * q8 + (xcd < r8 ? xcd : r8) + (bid >> 3);
-    const int per_prod = tiles_m * tiles_n;
-    const int pidx = lid / per_prod;
-    int rem = lid - pidx * per_prod;
-    const int gsz = GROUP_M * tiles_n;
-    const int grp = rem / gsz;
-    const int gm0 = grp * GROUP_M;
-    const int gh = (tiles_m - gm0) < GROUP_M ? (tiles_m - gm0) : GROUP_M;
-    rem -= grp * gsz;
-    const int tm = gm0 + rem % gh, tn = rem / gh;
-    const Product& P = prods[first + pidx];
-    const int64_t i0 = (int64_t)tm * TM, j0 = (int64_t)tn * TN;
+    // ---- which tile: spread consecutive logical ids over one XCD (block b runs on XCD b % 8) ----
+    const int bid = blockIdx.x;
+    const bool part = bid >= main_count;  // a chunk of a tail tile
+    int lid;
+    int64_t kbeg = 0;
+    if (!part) {
+        const int q8 = main_count >> 3, r8 = main_count & 7, xcd = bid & 7;
+        lid = xcd * q8 + (xcd < r8 ? xcd : r8) + (bid >> 3);
+    } else {
+        const int u = bid - main_count;
+        lid = main_count + u % tail_tiles;
+        kbeg = (int64_t)(u / tail_tiles) * tail_kc;
+    }
+    const TileId tile = tile_of(lid, tiles_m, tiles_n);
+    const Product& P = prods[first + tile.pidx];
+    const int64_t i0 = (int64_t)tile.tm * TM, j0 = (int64_t)tile.tn * TN;
     const int nA = CF::EXACT ? NTA : P.A.nterms, nB = CF::EXACT ? NTB : P.B.nterms;
+    const int64_t kb = part ? min64(P.kb - kbeg, (int64_t)tail_kc) : P.kb;  // contracted entries of this workgroup
+    // a chunk sees the contracted bundle from entry kbeg on: shifted vectors, shortened lengths
+    const int64_t* const acs = P.A.cs + kbeg;
+    const int64_t* const brs = P.B.rs + kbeg;
+    const int64_t acs_len = P.A.cs_len - kbeg, brs_len = P.B.rs_len - kbeg;
 
     St st;
     st.S = &S;
@@ -495,7 +526,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     st.tid = tid;
     st.nA = nA;
     st.nB = nB;
-    st.nk = (int)((P.kb + KT - 1) / KT);
+    st.nk = (int)((kb + KT - 1) / KT);
     st.nk += st.nk & 1;  // the k loop runs two steps per trip; a k-step past the end gathers only zero padding
     st.unitA = P.A.coef[0] == 1.0;
     st.unitB = P.B.coef[0] == 1.0;
@@ -514,18 +545,18 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     }
 
     // ---- tile-fixed gather tables; how much of the tile and of the k range is free of zero padding ----
-    int64_t klimit = P.kb;       // k entries that are real in every term of both operands
+    int64_t klimit = kb;         // k entries that are real in every term of both operands
     bool tile_full = true;       // every row and column of the tile is real in every term
 #pragma unroll
     for (int t = 0; t < NTA; ++t)
         if (t < nA) {
-            klimit = min64(klimit, P.A.cs_len - P.A.coff[t]);
+            klimit = min64(klimit, acs_len - P.A.coff[t]);
             tile_full = tile_full && (i0 + TM <= min64(P.mb, P.A.rs_len - P.A.roff[t]));
         }
 #pragma unroll
     for (int t = 0; t < NTB; ++t)
         if (t < nB) {
-            klimit = min64(klimit, P.B.rs_len - P.B.roff[t]);
+            klimit = min64(klimit, brs_len - P.B.roff[t]);
             tile_full = tile_full && (j0 + TN <= min64(P.nb, P.B.cs_len - P.B.coff[t]));
         }
     st.kfull = tile_full ? (int)(klimit / KT) : 0;  // k-steps [0, kfull) need no checks
@@ -559,8 +590,11 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
             st.ent_stride = (isB ? NTB : NTA) * KT;
             if (t < (isB ? nB : nA)) {
                 const int64_t off0 = isB ? op.roff[t] : op.coff[t];
-                st.ent_ptr = as_global(isB ? op.rs : op.cs) + off0 + kl;
-                st.ent_limit = (int)(min64(P.kb, (isB ? op.rs_len : op.cs_len) - off0) - kl);
+                const int64_t avail = min64(kb, (isB ? brs_len : acs_len) - off0) - kl;
+                if (avail > 0) {  // otherwise the thread keeps the dummy target and stores sentinels
+                    st.ent_ptr = as_global(isB ? brs : acs) + off0 + kl;
+                    st.ent_limit = (int)avail;
+                }
             }
         }
     }
@@ -630,8 +664,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         if (affine) {
             const int wu = __builtin_amdgcn_readfirstlane(wave);
             // A: free bundle = rows, contracted = columns; B: free bundle = columns, contracted = rows
-            setup_affine<AMODE, NTA, KT>(st.afa, Abase, P.A.rs_stride, P.A.cs_stride, P.A.roff, P.A.coff, i0, lane, wu);
-            setup_affine<BMODE, NTB, KT>(st.afb, Bbase, P.B.cs_stride, P.B.rs_stride, P.B.coff, P.B.roff, j0, lane, wu);
+            setup_affine<AMODE, NTA, KT>(st.afa, Abase + kbeg * P.A.cs_stride, P.A.rs_stride, P.A.cs_stride, P.A.roff, P.A.coff, i0, lane, wu);
+            setup_affine<BMODE, NTB, KT>(st.afb, Bbase + kbeg * P.B.rs_stride, P.B.cs_stride, P.B.rs_stride, P.B.coff, P.B.roff, j0, lane, wu);
         }
     }
     if (nfast > 0) {
@@ -660,18 +694,29 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     int64_t(*c_rs)[TM] = S.c_rs;
     int64_t(*c_cs)[TN] = S.c_cs;
     double* otile = &S.a[0][0];  // [CP columns][OPITCH], rows fastest
-    const int nC = P.C.nterms;
+    // A chunk of a tail tile has one destination: its dense slot of the partial buffer, contiguous along the
+    // direction c_mode makes the lanes run, written as is (no alpha, no previous contents).
+    const int nC = part ? 1 : P.C.nterms;
     for (int e = tid; e < MAXC * TM; e += NTHREADS) {
         const int d = e / TM, x = e % TM;
         const int64_t gi = i0 + x, gj = j0 + x;
         int64_t val = kSentinel;
-        if (d < nC && gi < P.mb && P.C.roff[d] + gi < P.C.rs_len) val = as_global(P.C.rs)[P.C.roff[d] + gi];
+        if (part) {
+            if (d == 0) val = c_mode == 0 ? x : TN * x;
+        } else if (d < nC && gi < P.mb && P.C.roff[d] + gi < P.C.rs_len) {
+            val = as_global(P.C.rs)[P.C.roff[d] + gi];
+        }
         c_rs[d][x] = val;
         val = kSentinel;
-        if (d < nC && gj < P.nb && P.C.coff[d] + gj < P.C.cs_len) val = as_global(P.C.cs)[P.C.coff[d] + gj];
+        if (part) {
+            if (d == 0) val = c_mode == 0 ? TM * x : x;
+        } else if (d < nC && gj < P.nb && P.C.coff[d] + gj < P.C.cs_len) {
+            val = as_global(P.C.cs)[P.C.coff[d] + gj];
+        }
         c_cs[d][x] = val;
     }
-    double* Cbase = (P.C.space == 0 ? Cu : W) + P.C.base_off;
+    double* Cbase = part ? partial + (int64_t)(bid - main_count) * (TM * TN) : (P.C.space == 0 ? Cu : W) + P.C.base_off;
+    if (part) alpha = 1.0;
     const int dj = lane & 3, dblk = (lane >> 2) & 3, di = lane >> 4;
 #pragma unroll 1
     for (int pass = 0; pass < NPASS; ++pass) {
@@ -689,8 +734,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         }
         __syncthreads();
         for (int d = 0; d < nC; ++d) {
-            const double g = P.C.coef[d];
-            const double f = P.overwrite ? 0.0 : (((P.first_mask >> d) & 1u) ? beta : 1.0);
+            const double g = part ? 1.0 : P.C.coef[d];
+            const double f = (part || P.overwrite) ? 0.0 : (((P.first_mask >> d) & 1u) ? beta : 1.0);
             constexpr int BATCH = CP / 4;  // elements per thread, destination and pass: all their loads are issued together
             static_assert(BATCH == TM / (NTHREADS / CP), "both thread mappings cover the pass");
             if (c_mode == 0) {
@@ -735,9 +780,16 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     }
 }
 
+// Tail of a launch cut into chunks (see fused_kernel): tiles = tail tiles, chunks per tile, kc = entries per chunk
+// (a multiple of 64), partial = room for tiles * chunks dense 128 x 128 tiles.  tiles = 0: every tile is computed whole.
+struct TailSplit {
+    int tiles, chunks, kc;
+    double* partial;
+};
+
 template <int AMODE, int BMODE, class CF, bool VA, bool VB>
 int launch_one(const Product* prods, int first, int count, int tiles_m, int tiles_n, const double* A, const double* B, double* C,
-               double* W, double alpha, double beta, int c_mode, hipStream_t stream) {
+               double* W, double alpha, double beta, int c_mode, const TailSplit& tail, hipStream_t stream) {
     static bool configured = false;
     static_assert(sizeof(Smem<CF>) <= 160 * 1024, "LDS budget of one CU");
     const size_t smem = sizeof(Smem<CF>);
@@ -747,9 +799,14 @@ int launch_one(const Product* prods, int first, int count, int tiles_m, int tile
         if (e != hipSuccess) return (int)e;
         configured = true;
     }
-    const int64_t blocks = (int64_t)count * tiles_m * tiles_n;
-    if (blocks <= 0 || blocks > 0x7fffffff) return (int)hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), smem, stream, prods, first, tiles_m, tiles_n, A, B, C, W, alpha, beta, c_mode);
+    const int64_t total = (int64_t)count * tiles_m * tiles_n;
+    if (total <= 0 || tail.tiles < 0 || tail.tiles > total) return (int)hipErrorInvalidValue;
+    if (tail.tiles > 0 && (tail.chunks < 2 || tail.kc < 64 || tail.kc % 64 != 0 || !tail.partial)) return (int)hipErrorInvalidValue;
+    const int64_t main_count = total - tail.tiles;
+    const int64_t blocks = main_count + (int64_t)tail.tiles * tail.chunks;
+    if (blocks > 0x7fffffff) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), smem, stream, prods, first, tiles_m, tiles_n, A, B, C, W, alpha, beta, c_mode,
+                       (int)main_count, tail.tiles, tail.kc, tail.partial);
     return (int)hipGetLastError();
 }
 
@@ -757,17 +814,17 @@ int launch_one(const Product* prods, int first, int count, int tiles_m, int tile
 // bit 1 = of B.
 template <int NTA, int NTB, bool EXACT>
 int launch_family(int a_mode, int b_mode, int vec, int c_mode, const Product* prods, int first, int count, int tiles_m, int tiles_n,
-                  const double* A, const double* B, double* C, double* W, double alpha, double beta, hipStream_t stream);
+                  const double* A, const double* B, double* C, double* W, double alpha, double beta, const TailSplit& tail, hipStream_t stream);
 
 #define TC_FUSED_CASE(AM, BM, VA, VB) \
     case ((AM) * 8 + (BM) * 4 + (VA) * 2 + (VB)): \
-        return launch_one<AM, BM, CF, (VA) != 0, (VB) != 0>(prods, first, count, tiles_m, tiles_n, A, B, C, W, alpha, beta, c_mode, stream);
+        return launch_one<AM, BM, CF, (VA) != 0, (VB) != 0>(prods, first, count, tiles_m, tiles_n, A, B, C, W, alpha, beta, c_mode, tail, stream);
 
 #define TC_FUSED_DEFINE_LAUNCH(NTAV, NTBV, EXACTV)                                                                                   \
     template <>                                                                                                                      \
     int launch_family<NTAV, NTBV, EXACTV>(int a_mode, int b_mode, int vec, int c_mode, const Product* prods, int first, int count,   \
                                           int tiles_m, int tiles_n, const double* A, const double* B, double* C, double* W,          \
-                                          double alpha, double beta, hipStream_t stream) {                                           \
+                                          double alpha, double beta, const TailSplit& tail, hipStream_t stream) {                    \
         typedef Cfg<NTAV, NTBV, EXACTV> CF;                                                                                          \
         switch (a_mode * 8 + b_mode * 4 + (vec & 1) * 2 + ((vec >> 1) & 1)) {                                                        \
             TC_FUSED_CASE(0, 0, 0, 0) TC_FUSED_CASE(0, 0, 0, 1) TC_FUSED_CASE(0, 0, 1, 0) TC_FUSED_CASE(0, 0, 1, 1)                  \
@@ -777,6 +834,51 @@ int launch_family(int a_mode, int b_mode, int vec, int c_mode, const Product* pr
         }                                                                                                                            \
         return (int)hipErrorInvalidValue;                                                                                            \
     }
+
+// Sum of the chunks of every tail tile, in chunk order, added to the destinations exactly as the fused kernel's
+// epilogue does for a whole tile (Sec. 4.2).  One workgroup per tail tile.  LANES_ROWS: lanes run along the tile's
+// rows (the partial tiles were written with c_mode 0, rows contiguous); otherwise along its columns.
+template <bool LANES_ROWS>
+__global__ __launch_bounds__(NTHREADS) void tail_fixup_kernel(const Product* __restrict__ prods, int first, int tiles_m, int tiles_n,
+                                                              int main_count, int tail_tiles, int chunks, const double* __restrict__ partial,
+                                                              double* __restrict__ Cu, double* __restrict__ W, double alpha, double beta) {
+    const int t = blockIdx.x, tid = threadIdx.x;
+    const TileId tile = tile_of(main_count + t, tiles_m, tiles_n);
+    const Product& P = prods[first + tile.pidx];
+    const int64_t i0 = (int64_t)tile.tm * TM, j0 = (int64_t)tile.tn * TN;
+    double* Cbase = (P.C.space == 0 ? Cu : W) + P.C.base_off;
+    const int nC = P.C.nterms;
+    const int fast = tid & 127, sg = tid >> 7;  // position along the lanes' direction; the other direction: sg + 4 j
+    const int64_t gfast = (LANES_ROWS ? i0 : j0) + fast;
+    const int64_t lim_fast = LANES_ROWS ? P.mb : P.nb;
+    int64_t fix[MAXC];
+#pragma unroll
+    for (int d = 0; d < MAXC; ++d) {
+        fix[d] = kSentinel;
+        if (d < nC && gfast < lim_fast) {
+            const int64_t g = (LANES_ROWS ? P.C.roff[d] : P.C.coff[d]) + gfast;
+            if (g < (LANES_ROWS ? P.C.rs_len : P.C.cs_len)) fix[d] = as_global(LANES_ROWS ? P.C.rs : P.C.cs)[g];
+        }
+    }
+    const int64_t lim_slow = LANES_ROWS ? P.nb : P.mb;
+    for (int j = 0; j < TM / 4; ++j) {
+        const int slow = sg + 4 * j;
+        const int64_t gslow = (LANES_ROWS ? j0 : i0) + slow;
+        if (gslow >= lim_slow) continue;
+        const double* src = partial + (int64_t)t * (TM * TN) + slow * 128 + fast;
+        double v = src[0];
+        for (int c = 1; c < chunks; ++c) v += src[(int64_t)c * tail_tiles * (TM * TN)];
+        v *= alpha;
+        for (int d = 0; d < nC; ++d) {
+            const int64_t g = (LANES_ROWS ? P.C.coff[d] : P.C.roff[d]) + gslow;
+            if (fix[d] < 0 || g >= (LANES_ROWS ? P.C.cs_len : P.C.rs_len)) continue;
+            const int64_t off = fix[d] + as_global(LANES_ROWS ? P.C.cs : P.C.rs)[g];
+            const double f = P.overwrite ? 0.0 : (((P.first_mask >> d) & 1u) ? beta : 1.0);
+            const double gv = P.C.coef[d] * v;
+            Cbase[off] = (f == 0.0) ? gv : __builtin_fma(f, Cbase[off], gv);
+        }
+    }
+}
 
 }  // namespace fused
 }  // namespace tc

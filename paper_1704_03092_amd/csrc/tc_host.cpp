@@ -37,6 +37,9 @@ struct Step {
     int64_t rows, cols;   // extents
     int lanes_along_rows; // STEP_LINCOMB
     int src_role;         // STEP_LINCOMB: which caller tensor a space-0 source refers to (0 = A, 1 = B)
+    // STEP_FUSED: the last tail_tiles tiles are cut into tail_chunks chunks of tail_kc contracted entries (0: none)
+    int tail_tiles = 0, tail_chunks = 0;
+    int64_t tail_kc = 0;
 };
 
 // vector ids inside the plan's store
@@ -60,6 +63,7 @@ struct tc_plan {
     int n_launches = 0;
     size_t workspace_bytes = 0;
     int64_t wsM = 0, wsTA = 0, wsTB = 0;  // offsets (elements) of the temporaries inside the workspace
+    int64_t wsPart = 0;                   // offset of the chunks of split tail tiles
     // device
     std::vector<BundleDesc> bundles;      // V_COUNT entries (temporaries may be unused: total = 0)
     int64_t store_entries = 0;
@@ -249,6 +253,9 @@ void lead_with_plus(Operand& op) {
 // in the family that counts terms at run time (key 0).
 int terms_class(int n_a, int n_b) { return (n_a != 3 && n_b != 3) ? 8 * n_a + n_b : 0; }
 
+extern const tc_model_params_t kDefaultModel;
+void choose_tail(const tc_plan_t* p, Step& s, const tc_model_params_t& mp, int forced);
+
 int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const tc_tensor_desc_t* C, int level, int variant,
                const tc_options_t* opts, void* stream) {
     int rc;
@@ -257,8 +264,11 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     if (variant < TC_VARIANT_NAIVE || variant > TC_VARIANT_HYBRID) return TC_ERR_VARIANT;
     p->bs_block = 16;
     bool no_merge = false;
+    int tail_mode = 0;  // 0: the model decides, -1: never, 2..16: that many chunks wherever a launch has a tail
     int split = 1;
     if (opts) {
+        if (opts->tail_split < -1 || opts->tail_split == 1 || opts->tail_split > 16) return TC_ERR_STATE;
+        tail_mode = opts->tail_split;
         if (opts->bs_block < 0 || opts->bs_block > (1 << 20)) return TC_ERR_STATE;
         if (opts->bs_block > 0) p->bs_block = opts->bs_block;
         p->host_only = opts->host_only != 0;
@@ -724,6 +734,17 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         emit(list, base_cfg, variant == TC_VARIANT_ABC || level == 0);
     }
     p->n_launches = (int)p->steps.size();
+    // ---- tails: launches whose tiles do not fill whole rounds of the compute units ----
+    if (tail_mode >= 0) {
+        int64_t chunks = 0;
+        for (Step& s : p->steps)
+            if (s.kind == STEP_FUSED) {
+                choose_tail(p, s, kDefaultModel, tail_mode);
+                chunks = std::max<int64_t>(chunks, (int64_t)s.tail_tiles * s.tail_chunks);
+            }
+        p->wsPart = (int64_t)(p->workspace_bytes / sizeof(double));
+        p->workspace_bytes += (size_t)chunks * 128 * 128 * sizeof(double);
+    }
     if (!p->host_only && !p->prods.empty()) {
         if (tc::dev_malloc((void**)&p->prods_dev, sizeof(Product) * p->prods.size())) return TC_ERR_HIP;
         if (tc::dev_upload(p->prods_dev, p->prods.data(), sizeof(Product) * p->prods.size(), stream)) return TC_ERR_HIP;
@@ -748,7 +769,7 @@ void copy_labels(char* out, const std::vector<Dim>& b) {
 
 // ---- performance model (Sec. 5) on the plan's schedule ----
 // Defaults fitted to the measured grid of paper_1704_03092_amd/sweep.py on one MI355X (RMS error of log time 7 %).
-const tc_model_params_t kDefaultModel = {
+extern const tc_model_params_t kDefaultModel = {
     78.6e12,               // published FP64 matrix peak
     {0.88, 0.80, 0.72},    // fused kernel with 1 / 2 / 4-term operand sums
     8.0e12,                // HBM3E
@@ -757,29 +778,88 @@ const tc_model_params_t kDefaultModel = {
     5.0e-6,                // per wave of tiles: gather tables, pipeline fill, destination update
     256, {0, 0, 0}};
 
+// What the model needs to know of a fused launch.
+struct FusedShape {
+    int64_t tiles, kb;
+    int terms;
+    double c_elems;
+};
+
+FusedShape fused_shape(const tc_plan_t* p, const Step& s) {
+    FusedShape f{0, 0, 1, 0.0};
+    f.tiles = (int64_t)s.count * ((s.rows + 127) / 128) * ((s.cols + 127) / 128);
+    for (int i = s.first; i < s.first + s.count; ++i) {
+        const Product& q = p->prods[i];
+        f.terms = std::max(f.terms, std::max(q.A.nterms, q.B.nterms));
+        f.kb = q.kb;
+        f.c_elems += (q.overwrite ? 1.0 : 2.0) * q.C.nterms * (double)q.mb * (double)q.nb;
+    }
+    return f;
+}
+
+// Modelled time of a fused launch except its destination updates: whole tiles in whole waves of `units` tiles, the
+// chunks of the tail tiles in whole waves of their own depth, the chunks written and read back, the second launch.
+struct TailCost {
+    double arith, temporaries, launch;
+    double total() const { return arith + temporaries + launch; }
+};
+
+TailCost fused_cost(const tc_model_params_t& mp, const FusedShape& f, int64_t tail_tiles, int64_t chunks, int64_t kc) {
+    const double rho = f.terms <= 1 ? mp.rho_a[0] : f.terms <= 2 ? mp.rho_a[1] : mp.rho_a[2];
+    auto wave = [&](int64_t depth) { return mp.units * 2.0 * 128.0 * 128.0 * (double)depth / (rho * mp.peak_flops) + mp.t_tile; };
+    TailCost c{0, 0, mp.t_launch};
+    const int64_t whole = f.tiles - tail_tiles;
+    c.arith = (double)((whole + mp.units - 1) / mp.units) * wave(f.kb);
+    if (tail_tiles > 0) {
+        c.arith += (double)((tail_tiles * chunks + mp.units - 1) / mp.units) * wave(kc);
+        c.temporaries = 2.0 * (double)(tail_tiles * chunks) * 128.0 * 128.0 * 8.0 / (mp.rho_b * mp.bandwidth);
+        c.launch += mp.t_launch;
+    }
+    return c;
+}
+
+// The tail of a launch: the tiles beyond the last full round of the compute units.  Cut into 2..16 chunks of at
+// least 256 contracted entries (a multiple of 64) if the model says that this is faster than running them whole.
+// forced >= 2: that many chunks (of at least 64 entries) whatever the model says.
+void choose_tail(const tc_plan_t* p, Step& s, const tc_model_params_t& mp, int forced) {
+    s.tail_tiles = s.tail_chunks = 0;
+    s.tail_kc = 0;
+    const FusedShape f = fused_shape(p, s);
+    const int64_t r = f.tiles % mp.units;
+    if (f.tiles <= 0 || r == 0 || f.tiles > 0x7fffffff) return;
+    double best = fused_cost(mp, f, 0, 0, 0).total();
+    for (int64_t want = forced ? forced : 2; want <= (forced ? forced : 16); ++want) {
+        const int64_t kc = round_up((f.kb + want - 1) / want, 64);
+        if (!forced && kc < 256) break;
+        const int64_t chunks = (f.kb + kc - 1) / kc;
+        if (chunks < 2 || r * chunks > 1024) continue;
+        const double t = fused_cost(mp, f, r, chunks, kc).total();
+        if (forced || t < best) {
+            best = t;
+            s.tail_tiles = (int)r;
+            s.tail_chunks = (int)chunks;
+            s.tail_kc = kc;
+        }
+    }
+}
+
 void predict(const tc_plan_t* p, const tc_model_params_t& mp, tc_model_time_t* out) {
     const double tau_b = 8.0 / (mp.rho_b * mp.bandwidth);
     tc_model_time_t t = {0, 0, 0, 0, 0};
     for (const Step& s : p->steps) {
-        t.launch += mp.t_launch;
         if (s.kind == STEP_FUSED) {
-            const int64_t tiles_m = (s.rows + 127) / 128, tiles_n = (s.cols + 127) / 128;
-            const int64_t tiles = (int64_t)s.count * tiles_m * tiles_n;
-            int terms = 1;
-            double c_elems = 0;
-            int64_t kb = 0;
-            for (int i = s.first; i < s.first + s.count; ++i) {
-                const Product& q = p->prods[i];
-                terms = std::max(terms, std::max(q.A.nterms, q.B.nterms));
-                kb = q.kb;
-                c_elems += (q.overwrite ? 1.0 : 2.0) * q.C.nterms * (double)q.mb * (double)q.nb;
+            const FusedShape f = fused_shape(p, s);
+            if (f.tiles == 0) {
+                t.launch += mp.t_launch;
+                continue;
             }
-            if (tiles == 0) continue;
-            const double rho = terms <= 1 ? mp.rho_a[0] : terms <= 2 ? mp.rho_a[1] : mp.rho_a[2];
-            const int64_t waves = (tiles + mp.units - 1) / mp.units;
-            t.arith += (double)waves * (mp.units * 2.0 * 128.0 * 128.0 * (double)kb / (rho * mp.peak_flops) + mp.t_tile);
-            t.c_update += c_elems * tau_b;
+            const TailCost c = fused_cost(mp, f, s.tail_tiles, s.tail_chunks, s.tail_kc);
+            t.arith += c.arith;
+            t.temporaries += c.temporaries;
+            t.launch += c.launch;
+            t.c_update += f.c_elems * tau_b;
         } else {
+            t.launch += mp.t_launch;
             const Product& q = p->prods[s.first];
             const double elems = (q.A.nterms + (q.overwrite ? 1.0 : 2.0) * q.C.nterms) * (double)s.rows * (double)s.cols;
             t.temporaries += elems * tau_b;
@@ -818,8 +898,10 @@ int choose_by_model(const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const 
     tc_options_t o0 = o;  // level 0 competes with the split it would run with
     if (o.split_k == -1) {
         o0.split_k = 1;
-        int rc = choose_split(A, B, C, TC_VARIANT_ABC, &o0);
-        if (rc != TC_OK) return rc;
+        if (o.tail_split != 0) {  // (the automatic tail split does that job inside the kernel)
+            int rc = choose_split(A, B, C, TC_VARIANT_ABC, &o0);
+            if (rc != TC_OK) return rc;
+        }
         o.split_k = 1;
     }
     double best = 0;
@@ -882,7 +964,7 @@ int tc_plan_ex(tc_plan_t** plan_out, const tc_tensor_desc_t* A, const tc_tensor_
         if (opts) o = *opts;
         if (o.split_k == -1) {
             o.split_k = 1;
-            if (level == 0) {
+            if (level == 0 && o.tail_split != 0) {
                 int rc = choose_split(A, B, C, variant, &o);
                 if (rc != TC_OK) return rc;
             }
@@ -908,6 +990,16 @@ int tc_plan(tc_plan_t** plan_out, const tc_tensor_desc_t* A, const tc_tensor_des
 
 size_t tc_plan_workspace_bytes(const tc_plan_t* plan) { return plan ? plan->workspace_bytes : 0; }
 
+namespace {
+int run_step(const tc_plan_t* plan, const Step& s, double alpha, const double* A_dev, const double* B_dev, double beta, double* C_dev, double* W,
+             void* stream) {
+    if (s.kind == STEP_FUSED)
+        return tc::launch_fused(s.cfg, plan->prods_dev, s.first, s.count, s.rows, s.cols, A_dev, B_dev, C_dev, W, alpha, beta, s.tail_tiles,
+                                s.tail_chunks, s.tail_kc, plan->wsPart, stream);
+    return tc::launch_lincomb(plan->prods_dev, s.first, s.rows, s.cols, s.lanes_along_rows, A_dev, B_dev, C_dev, W, s.src_role, beta, stream);
+}
+}  // namespace
+
 int tc_contract(const tc_plan_t* plan, double alpha, const double* A_dev, const double* B_dev, double beta, double* C_dev,
                 void* workspace_dev, void* stream) {
     if (!plan) return TC_ERR_NULL;
@@ -917,15 +1009,8 @@ int tc_contract(const tc_plan_t* plan, double alpha, const double* A_dev, const 
     if (plan->k > 0 && (!A_dev || !B_dev)) return TC_ERR_NULL;
     if (plan->workspace_bytes > 0 && !workspace_dev) return TC_ERR_WORKSPACE;
     double* W = (double*)workspace_dev;
-    for (const Step& s : plan->steps) {
-        int err;
-        if (s.kind == STEP_FUSED)
-            err = tc::launch_fused(s.cfg, plan->prods_dev, s.first, s.count, s.rows, s.cols, A_dev, B_dev, C_dev, W, alpha, beta, stream);
-        else
-            err = tc::launch_lincomb(plan->prods_dev, s.first, s.rows, s.cols, s.lanes_along_rows, A_dev, B_dev, C_dev, W, s.src_role, beta,
-                                     stream);
-        if (err) return TC_ERR_HIP;
-    }
+    for (const Step& s : plan->steps)
+        if (run_step(plan, s, alpha, A_dev, B_dev, beta, C_dev, W, stream)) return TC_ERR_HIP;
     return TC_OK;
 }
 
@@ -945,14 +1030,7 @@ int tc_contract_timed(const tc_plan_t* plan, double alpha, const double* A_dev, 
         if (tc::dev_event_create(&e)) rc = TC_ERR_HIP;
     if (rc == TC_OK && tc::dev_event_record(ev[0], stream)) rc = TC_ERR_HIP;
     for (size_t i = 0; i < plan->steps.size() && rc == TC_OK; ++i) {
-        const Step& s = plan->steps[i];
-        int err;
-        if (s.kind == STEP_FUSED)
-            err = tc::launch_fused(s.cfg, plan->prods_dev, s.first, s.count, s.rows, s.cols, A_dev, B_dev, C_dev, W, alpha, beta, stream);
-        else
-            err = tc::launch_lincomb(plan->prods_dev, s.first, s.rows, s.cols, s.lanes_along_rows, A_dev, B_dev, C_dev, W, s.src_role, beta,
-                                     stream);
-        if (err || tc::dev_event_record(ev[i + 1], stream)) rc = TC_ERR_HIP;
+        if (run_step(plan, plan->steps[i], alpha, A_dev, B_dev, beta, C_dev, W, stream) || tc::dev_event_record(ev[i + 1], stream)) rc = TC_ERR_HIP;
     }
     if (rc == TC_OK && tc::dev_event_sync(ev.back())) rc = TC_ERR_HIP;
     for (size_t i = 0; i < plan->steps.size() && rc == TC_OK; ++i) {
@@ -1016,6 +1094,24 @@ int tc_plan_schedule(const tc_plan_t* plan, int index, tc_product_t* out) {
     if (!plan || !out) return TC_ERR_NULL;
     if (index < 0 || index >= (int)plan->sched.size()) return TC_ERR_RANGE;
     *out = plan->sched[index];
+    return TC_OK;
+}
+
+int tc_plan_launch(const tc_plan_t* plan, int index, tc_launch_info_t* out) {
+    if (!plan || !out) return TC_ERR_NULL;
+    if (index < 0 || index >= (int)plan->steps.size()) return TC_ERR_RANGE;
+    std::memset(out, 0, sizeof *out);
+    const Step& s = plan->steps[index];
+    out->kind = s.kind == STEP_FUSED ? 0 : 1;
+    out->rows = s.rows, out->cols = s.cols;
+    if (s.kind == STEP_FUSED) {
+        const FusedShape f = fused_shape(plan, s);
+        out->n_products = s.count;
+        out->max_terms = f.terms;
+        out->depth = f.kb;
+        out->tiles = f.tiles;
+        out->tail_tiles = s.tail_tiles, out->tail_chunks = s.tail_chunks, out->tail_kc = s.tail_kc;
+    }
     return TC_OK;
 }
 

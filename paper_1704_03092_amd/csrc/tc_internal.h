@@ -70,9 +70,13 @@ int dev_event_destroy(void* e);
 // scatter + block scatter vectors for `nvec` bundles described in device array `descs`
 int launch_planner(const BundleDesc* descs_dev, int nvec, int64_t max_total, int bs_block, int64_t* store_dev, void* stream);
 
-// products [first, first + count) of the device schedule, all with the same extents, in one launch
+// products [first, first + count) of the device schedule, all with the same extents, in one launch.
+// tail_tiles > 0: the last tail_tiles tiles of the launch are cut along the contracted bundle into tail_chunks chunks
+// of tail_kc entries (a multiple of 64), computed by one workgroup each into W + partial_off (tail_tiles * tail_chunks
+// dense 128 x 128 tiles), and a second kernel adds the chunks and updates the destinations.
 int launch_fused(const FusedConfig& cfg, const Product* prods_dev, int first, int count, int64_t mb, int64_t nb,
-                 const double* A, const double* B, double* C, double* W, double alpha, double beta, void* stream);
+                 const double* A, const double* B, double* C, double* W, double alpha, double beta, int tail_tiles, int tail_chunks,
+                 int64_t tail_kc, int64_t partial_off, void* stream);
 
 // element-wise: v = sum_t coefA_t * srcA_t;  for each destination d: dst_d = coefC_d * v + f_d * dst_d
 // (Product::B is ignored; extents mb x nb).  lanes_along_rows picks the coalesced direction.

@@ -29,6 +29,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def _plan(A, B, C, level=0, variant="abc", **kw):
+    kw.setdefault("tail_split", -1)  # the schedules below are those of the paper; the tail split has tests of its own
     return tc.tc_plan(A, B, C, level, variant, host_only=True, **kw)
 
 
@@ -295,3 +296,99 @@ def test_split_k_schedule():
     big = _plan(*_gemm_desc(8192, 8192, 8192), split_k=-1)
     assert tc.tc_plan_info(big)["n_products"] == 1
     tc.tc_destroy(big)
+
+
+def _launch_cost(L, mp, tail):
+    """Modelled time of one multiplying launch without its destination updates (oracle.model.granular_time)."""
+    from oracle import model as M
+
+    launch = {"kind": "mul", "products": [{"tiles": L["tiles"], "kb": L["depth"], "terms": L["max_terms"], "c_elems": 0}]}
+    if tail:
+        launch["tail"] = tail
+    return M.granular_time([launch], mp)["total"]
+
+
+@pytest.mark.parametrize("shape,level,variant", [((36864, 2304, 36864), 1, "abc"), ((36864, 2304, 36864), 1, "hybrid"),
+                                                  ((10001, 10001, 10001), 1, "abc"), ((9216, 96, 4096), 0, "abc"),
+                                                  ((13824, 13824, 9216), 2, "hybrid"), ((16384, 16384, 16384), 1, "abc"),
+                                                  ((256, 256, 256), 0, "abc"), ((3000, 2000, 700), 1, "ab")])
+def test_tail_split_is_the_argmin_of_the_model(shape, level, variant):
+    """Every launch: the tail is what is left after whole rounds of the units; the chunk count is the one with the
+    smallest modelled time among 1 (no split) and the admissible 2..16 (chunks of a multiple of 64, at least 256,
+    entries; at most 1024 chunks), evaluated by the oracle's model; the prediction of the whole plan and the
+    workspace follow."""
+    import math
+
+    from oracle import model as M
+
+    d = tc.tc_model_defaults()
+    mp = M.MachineParams(peak_flops=d["peak_flops"], rho_a=d["rho_a"], bandwidth=d["bandwidth"], rho_b=d["rho_b"], t_launch=d["t_launch"],
+                         t_tile=d["t_tile"], units=d["units"])
+    plain = _plan(*_gemm_desc(*shape), level=level, variant=variant)
+    plan = _plan(*_gemm_desc(*shape), level=level, variant=variant, tail_split=0)
+    L0, L1 = tc.tc_plan_launches(plain), tc.tc_plan_launches(plan)
+    assert len(L0) == len(L1)
+    extra_t = extra_l = extra_a = 0.0
+    most = 0
+    for a, b in zip(L0, L1):
+        assert {k: v for k, v in a.items() if not k.startswith("tail")} == {k: v for k, v in b.items() if not k.startswith("tail")}
+        assert a["tail_tiles"] == 0
+        if b["kind"] == 1:
+            assert b["tail_tiles"] == 0
+            continue
+        r = b["tiles"] % mp.units
+        options = {None: _launch_cost(b, mp, None)}
+        if r:
+            for want in range(2, 17):
+                kc = -(-(-(-b["depth"] // want)) // 64) * 64
+                chunks = -(-b["depth"] // kc)
+                if kc < 256 or chunks < 2 or r * chunks > 1024:
+                    continue
+                options[(r, chunks, kc)] = _launch_cost(b, mp, {"tiles": r, "chunks": chunks, "kc": kc})
+        best = min(options.values())
+        got = (b["tail_tiles"], b["tail_chunks"], b["tail_kc"]) if b["tail_tiles"] else None
+        assert got in options and options[got] == best, (b, options)
+        if got:
+            assert (b["tail_chunks"] - 1) * b["tail_kc"] < b["depth"] <= b["tail_chunks"] * b["tail_kc"]
+            most = max(most, r * b["tail_chunks"])
+            extra_l += mp.t_launch
+            extra_t += 2.0 * r * b["tail_chunks"] * 128 * 128 * 8 / (mp.rho_b * mp.bandwidth)
+            extra_a += options[got] - options[None] - mp.t_launch - 2.0 * r * b["tail_chunks"] * 128 * 128 * 8 / (mp.rho_b * mp.bandwidth)
+    t0, t1 = tc.tc_plan_predict(plain), tc.tc_plan_predict(plan)
+    assert t1["launch"] == pytest.approx(t0["launch"] + extra_l, rel=1e-12)
+    assert t1["temporaries"] == pytest.approx(t0["temporaries"] + extra_t, rel=1e-12, abs=1e-18)
+    assert t1["arith"] == pytest.approx(t0["arith"] + extra_a, rel=1e-9)
+    assert t1["c_update"] == t0["c_update"] and t1["total"] <= t0["total"]
+    assert tc.tc_plan_workspace_bytes(plan) == tc.tc_plan_workspace_bytes(plain) + most * 128 * 128 * 8
+    tc.tc_destroy(plain)
+    tc.tc_destroy(plan)
+
+
+def test_tail_split_shapes():
+    # the ladder contraction: 1296 tiles per product = 5 rounds of 256 units and 16 tiles, which 16 chunks each fill a round
+    plan = _plan(*_gemm_desc(36864, 2304, 36864), level=1, variant="hybrid", tail_split=0)
+    fused = [L for L in tc.tc_plan_launches(plan) if L["kind"] == 0]
+    assert len(fused) == 7 and all(L["tiles"] == 1296 and L["tail_tiles"] == 16 and L["tail_chunks"] == 16 for L in fused)
+    tc.tc_destroy(plan)
+    # whole rounds: nothing to split, no workspace
+    plan = _plan(*_gemm_desc(16384, 16384, 16384), tail_split=0)
+    assert tc.tc_plan_launches(plan)[0]["tail_tiles"] == 0 and tc.tc_plan_workspace_bytes(plan) == 0
+    tc.tc_destroy(plan)
+    # with the automatic tail split, split_k = -1 leaves the job to it
+    plan = _plan(*_gemm_desc(9216, 96, 4096), split_k=-1, tail_split=0)
+    info = tc.tc_plan_info(plan)
+    assert info["n_products"] == 1 and info["n_launches"] == 1 and tc.tc_plan_launches(plan)[0]["tail_tiles"] == 72
+    tc.tc_destroy(plan)
+    with pytest.raises(tc.TcError) as e:
+        _plan(*_gemm_desc(64, 64, 64), tail_split=17)
+    assert e.value.status == -10
+    # forced: chunks of a multiple of 64 entries
+    plan = _plan(*_gemm_desc(300, 200, 500), tail_split=3)
+    L = tc.tc_plan_launches(plan)[0]
+    assert (L["tiles"], L["tail_tiles"], L["tail_chunks"], L["tail_kc"]) == (6, 6, 3, 192)
+    assert tc.tc_plan_workspace_bytes(plan) == 18 * 128 * 128 * 8
+    tc.tc_destroy(plan)
+    plan = _plan(*_gemm_desc(300, 200, 100), tail_split=4)  # 128-entry chunks would leave a single one: chunks of 64
+    L = tc.tc_plan_launches(plan)[0]
+    assert (L["tail_tiles"], L["tail_chunks"], L["tail_kc"]) == (6, 2, 64)
+    tc.tc_destroy(plan)

@@ -184,6 +184,59 @@ def test_split_k(gpu):
     assert oracle.error_metric(logical(C, got_flat), ref.view(), oracle.tensor_norm(A), oracle.tensor_norm(B)) <= TOL[0]
 
 
+@pytest.mark.parametrize("idxA,idxB,idxC", [("ik", "kj", "ij"), ("ki", "jk", "ji"), ("ki", "kj", "ij"), ("ik", "jk", "ji")])
+def test_tail_split_every_mode(gpu, idxA, idxB, idxC):
+    """Forced tail split: every tile of these launches is a tail tile (fewer tiles than compute units), cut into 2, 3
+    or 5 chunks along the contracted bundle; the chunks are added by the second kernel.  Gather directions and the
+    destination's contiguous direction in all combinations, ragged tiles, Strassen padding, every variant; small
+    integers must agree bit for bit (the chunk sums are exact there)."""
+    import paper_1704_03092_amd as tc
+
+    for (m, n, k), pad, kind in (((672, 608, 1408), 0, "uniform"), ((645, 583, 1111), 1, "smallint")):
+        lengths = {"i": m, "j": n, "k": k}
+        tens = []
+        for tid, idx in enumerate((idxA, idxB, idxC)):
+            lens = [lengths[c] for c in idx]
+            tens.append(workloads.make_tensor(idx, lengths, 31 + tid, tid, kind, strides_for_order(lens, list(range(len(idx))), pad=pad)))
+        A, B, C = tens
+        for (level, variant), chunks in zip(MODES, (2, 3, 5, 2, 3, 5, 2, 3, 5)):
+            _check(gpu, A, B, C, 1.5, 0.5, level, variant, exact=(kind == "smallint"), tail_split=chunks)
+    # the plan really splits: every tile, in as many chunks as asked for
+    st = __import__("torch").cuda.current_stream()
+    plan = tc.tc_plan(A, B, C, 1, "abc", st, tail_split=3)
+    fused = [L for L in tc.tc_plan_launches(plan) if L["kind"] == 0]
+    assert fused and all(L["tail_tiles"] == L["tiles"] and L["tail_chunks"] == 3 for L in fused)
+    tc.tc_destroy(plan)
+
+
+def test_tail_split_whole_and_split_tiles_together(gpu):
+    """More tiles than compute units: whole tiles and chunks of tail tiles in one launch (300 = 256 + 44 tiles at
+    level 0; the Strassen products have 80 tiles each), the automatic choice next to forced ones, general strides,
+    beta = 0 on a NaN-filled C."""
+    c = workloads.Contraction("g", "ij", "ik", "kj", {"i": 2500, "j": 1850, "k": 900}, seed=21)
+    A, B, C = c.tensors()
+    for level, variant, chunks in ((0, "abc", 2), (0, "abc", 4), (0, "abc", 0), (1, "abc", 3), (1, "hybrid", 2), (2, "abc", 2), (1, "ab", 0)):
+        _check(gpu, A, B, C, -1.0, 2.0, level, variant, tail_split=chunks)
+    Ai, Bi, Ci = c.tensors(kind="smallint")
+    _check(gpu, Ai, Bi, Ci, 2.0, -1.0, 0, "abc", exact=True, tail_split=3)
+    C.data[:] = np.nan
+    run_gpu, logical = gpu
+    got_flat, _ = run_gpu(A, B, C, 1.5, 0.0, 0, "abc", tail_split=3)
+    ref = from_dense("ij", np.zeros((2500, 1850)))
+    oracle.contract_matrix(A, B, ref, 1.5, 0.0)
+    assert oracle.error_metric(logical(C, got_flat), ref.view(), oracle.tensor_norm(A), oracle.tensor_norm(B)) <= TOL[0]
+    cfg = workloads.scaled(workloads.configs()["cfg4a"], {"a": 40, "b": 21, "c": 38, "d": 37, "e": 19})  # m = 1520, n = 21, k = 703
+    A, B, C = cfg.tensors()
+    for chunks in (2, 4, 11):
+        _check(gpu, A, B, C, 1.0, 1.0, 0, "abc", tail_split=chunks)
+    rng = random.Random(99)
+    for trial in range(12):
+        kind = "smallint" if trial % 2 else "uniform"
+        A, B, C = _random_midsize_case(rng, kind)
+        level, variant = MODES[trial % len(MODES)]
+        _check(gpu, A, B, C, rng.choice([1.0, -2.0]), rng.choice([0.0, 1.0, 3.0]), level, variant, exact=bool(trial % 2), tail_split=rng.choice([2, 3, 7]))
+
+
 def test_contract_timed_matches_contract(gpu):
     """tc_contract_timed enqueues the same launches: identical bits, and it counts the launches per kind."""
     import torch
