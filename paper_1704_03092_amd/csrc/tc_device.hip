@@ -18,55 +18,109 @@ namespace {
 // ---------------------------------------------------------------------------------------------------------
 // element-wise linear combination on matrix views
 // ---------------------------------------------------------------------------------------------------------
-template <bool ROWS_FAST>
+// A workgroup covers 256 * LC_FPT entries of the fast direction (LC_FPT per thread, 256 apart) and slow_per_block of
+// the slow one, in chunks of LC_SLOW.  The scatter entries of a chunk's slow direction are staged in LDS first (they
+// are the same for every thread), and every thread issues the loads of a batch of elements together before it
+// stores.  Measured on 8192 x 8192 blocks: with the entries fetched from global memory inside the loop, one slow entry
+// at a time, every entry pays the latency of its fetch, its loads and its store in turn (3.4 TB/s); many slow entries
+// in flight per workgroup open as many DRAM pages at once and cost bandwidth again, hence few slow entries and
+// several fast ones per thread.
+constexpr int LC_SLOW = 2, LC_FPT = 2;  // measured best of {1, 2, 4, 8, 16} x {1, 2, 4}: 5.8 TB/s
+
+// NS, ND: upper bounds (1, 2 or 4) of the numbers of sources and destinations; they size the register arrays.
+template <bool ROWS_FAST, int NS, int ND>
 __global__ __launch_bounds__(256) void lincomb_kernel(const Product* __restrict__ prods, int index, const double* __restrict__ srcU,
                                                       double* __restrict__ Cu, double* __restrict__ W, double beta, int slow_per_block) {
+    constexpr int CAP = 48 / ((NS + ND) * LC_FPT);  // slow entries per batch: at most 48 elements in registers
+    constexpr int LC_BATCH = CAP >= LC_SLOW ? LC_SLOW : (CAP >= 4 ? 4 : (CAP >= 2 ? 2 : 1));
+    static_assert(LC_SLOW % LC_BATCH == 0, "batches tile the chunk");
+    __shared__ int64_t s_off[2][kMaxTerms][LC_SLOW];  // [0]: sources, [1]: destinations
     const Product& P = prods[index];
-    // a block covers 256 entries of the fast direction and slow_per_block of the slow one
-    const int64_t fast = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t slow0 = (int64_t)blockIdx.y * slow_per_block;
+    const int tid = threadIdx.x;
+    const int64_t fast0 = (int64_t)blockIdx.x * (256 * LC_FPT) + tid;
     const int64_t nfast = ROWS_FAST ? P.mb : P.nb, nslow = ROWS_FAST ? P.nb : P.mb;
-    if (fast >= nfast) return;
+    const int64_t slow0 = (int64_t)blockIdx.y * slow_per_block;
+    const int64_t slow_end = slow0 + slow_per_block < nslow ? slow0 + slow_per_block : nslow;
     const double* src = (P.A.space == 0 ? srcU : W) + P.A.base_off;
     double* dst = (P.C.space == 0 ? Cu : W) + P.C.base_off;
     const int nS = P.A.nterms, nD = P.C.nterms;
-    int64_t sfix[kMaxTerms], dfix[kMaxTerms];
+    int64_t sfix[LC_FPT][NS], dfix[LC_FPT][ND];  // kSentinel: the entry does not exist
+    double cs[NS], gd[ND], fd[ND];
 #pragma unroll
-    for (int t = 0; t < kMaxTerms; ++t) {
-        sfix[t] = dfix[t] = kSentinel;
-        if (t < nS) {
-            const int64_t g = (ROWS_FAST ? P.A.roff[t] : P.A.coff[t]) + fast;
-            const int64_t len = ROWS_FAST ? P.A.rs_len : P.A.cs_len;
-            if (g < len) sfix[t] = (ROWS_FAST ? P.A.rs : P.A.cs)[g];
-        }
-        if (t < nD) {
-            const int64_t g = (ROWS_FAST ? P.C.roff[t] : P.C.coff[t]) + fast;
-            const int64_t len = ROWS_FAST ? P.C.rs_len : P.C.cs_len;
-            if (g < len) dfix[t] = (ROWS_FAST ? P.C.rs : P.C.cs)[g];
+    for (int t = 0; t < NS; ++t) {
+        cs[t] = t < nS ? P.A.coef[t] : 0.0;
+#pragma unroll
+        for (int i = 0; i < LC_FPT; ++i) {
+            sfix[i][t] = kSentinel;
+            const int64_t fast = fast0 + 256 * i;
+            if (t < nS && fast < nfast) {
+                const int64_t g = (ROWS_FAST ? P.A.roff[t] : P.A.coff[t]) + fast;
+                if (g < (ROWS_FAST ? P.A.rs_len : P.A.cs_len)) sfix[i][t] = (ROWS_FAST ? P.A.rs : P.A.cs)[g];
+            }
         }
     }
-    for (int e = 0; e < slow_per_block; ++e) {
-        const int64_t sl = slow0 + e;
-        if (sl >= nslow) break;
-        double v = 0.0;
 #pragma unroll
-        for (int t = 0; t < kMaxTerms; ++t) {
-            if (t >= nS) break;
-            const int64_t g = (ROWS_FAST ? P.A.coff[t] : P.A.roff[t]) + sl;
-            const int64_t len = ROWS_FAST ? P.A.cs_len : P.A.rs_len;
-            if (g < len && sfix[t] >= 0) v = __builtin_fma(P.A.coef[t], src[sfix[t] + (ROWS_FAST ? P.A.cs : P.A.rs)[g]], v);
-        }
+    for (int t = 0; t < ND; ++t) {
+        gd[t] = t < nD ? P.C.coef[t] : 0.0;
+        fd[t] = (t >= nD || P.overwrite) ? 0.0 : (((P.first_mask >> t) & 1u) ? beta : 1.0);
 #pragma unroll
-        for (int d = 0; d < kMaxTerms; ++d) {
-            if (d >= nD) break;
-            const int64_t g = (ROWS_FAST ? P.C.coff[d] : P.C.roff[d]) + sl;
-            const int64_t len = ROWS_FAST ? P.C.cs_len : P.C.rs_len;
-            if (g < len && dfix[d] >= 0) {
-                const int64_t off = dfix[d] + (ROWS_FAST ? P.C.cs : P.C.rs)[g];
-                const double f = P.overwrite ? 0.0 : (((P.first_mask >> d) & 1u) ? beta : 1.0);
-                const double gv = P.C.coef[d] * v;
-                dst[off] = (f == 0.0) ? gv : __builtin_fma(f, dst[off], gv);
+        for (int i = 0; i < LC_FPT; ++i) {
+            dfix[i][t] = kSentinel;
+            const int64_t fast = fast0 + 256 * i;
+            if (t < nD && fast < nfast) {
+                const int64_t g = (ROWS_FAST ? P.C.roff[t] : P.C.coff[t]) + fast;
+                if (g < (ROWS_FAST ? P.C.rs_len : P.C.cs_len)) dfix[i][t] = (ROWS_FAST ? P.C.rs : P.C.cs)[g];
             }
+        }
+    }
+    for (int64_t base = slow0; base < slow_end; base += LC_SLOW) {
+        __syncthreads();  // the previous chunk's entries have been used
+        if (tid < 2 * kMaxTerms * LC_SLOW) {
+            const int which = tid / (kMaxTerms * LC_SLOW), t = (tid / LC_SLOW) % kMaxTerms, e = tid % LC_SLOW;
+            const Operand& op = which ? P.C : P.A;
+            int64_t val = kSentinel;
+            if (base + e < slow_end && t < op.nterms) {
+                const int64_t g = (ROWS_FAST ? op.coff[t] : op.roff[t]) + base + e;
+                if (g < (ROWS_FAST ? op.cs_len : op.rs_len)) val = (ROWS_FAST ? op.cs : op.rs)[g];
+            }
+            s_off[which][t][e] = val;
+        }
+        __syncthreads();
+#pragma unroll 1
+        for (int e0 = 0; e0 < LC_SLOW; e0 += LC_BATCH) {
+            double x[LC_BATCH][LC_FPT][NS], cur[LC_BATCH][LC_FPT][ND];
+#pragma unroll
+            for (int b = 0; b < LC_BATCH; ++b)
+#pragma unroll
+                for (int i = 0; i < LC_FPT; ++i) {
+#pragma unroll
+                    for (int t = 0; t < NS; ++t) {
+                        x[b][i][t] = 0.0;
+                        const int64_t a = sfix[i][t] + s_off[0][t][e0 + b];  // negative if either entry does not exist
+                        if (a >= 0) x[b][i][t] = src[a];
+                    }
+#pragma unroll
+                    for (int t = 0; t < ND; ++t) {
+                        cur[b][i][t] = 0.0;
+                        const int64_t o = dfix[i][t] + s_off[1][t][e0 + b];
+                        if (o >= 0 && fd[t] != 0.0) cur[b][i][t] = dst[o];
+                    }
+                }
+#pragma unroll
+            for (int b = 0; b < LC_BATCH; ++b)
+#pragma unroll
+                for (int i = 0; i < LC_FPT; ++i) {
+                    double v = 0.0;
+#pragma unroll
+                    for (int t = 0; t < NS; ++t)
+                        if (t < nS) v = __builtin_fma(cs[t], x[b][i][t], v);  // (an absent element counts as zero)
+#pragma unroll
+                    for (int d = 0; d < ND; ++d) {
+                        const int64_t o = dfix[i][d] + s_off[1][d][e0 + b];
+                        const double gv = gd[d] * v;
+                        if (o >= 0) dst[o] = (fd[d] == 0.0) ? gv : __builtin_fma(fd[d], cur[b][i][d], gv);
+                    }
+                }
         }
     }
 }
@@ -176,20 +230,45 @@ int launch_fused(const FusedConfig& cfg, const Product* prods_dev, int first, in
     return (int)hipGetLastError();
 }
 
-int launch_lincomb(const Product* prods_dev, int index, int64_t mb, int64_t nb, int lanes_along_rows, const double* A, const double* B,
-                   double* C, double* W, int src_role, double beta, void* stream) {
+namespace {
+template <bool ROWS_FAST>
+void launch_lincomb_sized(int ns, int nd, dim3 grid, hipStream_t st, const Product* prods_dev, int index, const double* src, double* C, double* W,
+                          double beta, int per) {
+#define TC_LC(NS, ND)                                                                                                               \
+    hipLaunchKernelGGL((lincomb_kernel<ROWS_FAST, NS, ND>), grid, dim3(256), 0, st, prods_dev, index, src, C, W, beta, per); \
+    return
+    switch (ns * 8 + nd) {
+        case 1 * 8 + 1: TC_LC(1, 1);
+        case 1 * 8 + 2: TC_LC(1, 2);
+        case 1 * 8 + 4: TC_LC(1, 4);
+        case 2 * 8 + 1: TC_LC(2, 1);
+        case 2 * 8 + 2: TC_LC(2, 2);
+        case 2 * 8 + 4: TC_LC(2, 4);
+        case 4 * 8 + 1: TC_LC(4, 1);
+        case 4 * 8 + 2: TC_LC(4, 2);
+        default: TC_LC(4, 4);
+    }
+#undef TC_LC
+}
+}  // namespace
+
+int launch_lincomb(const Product* prods_dev, int index, int n_src, int n_dst, int64_t mb, int64_t nb, int lanes_along_rows, const double* A,
+                   const double* B, double* C, double* W, int src_role, double beta, void* stream) {
     hipStream_t st = (hipStream_t)stream;
     const double* src = src_role == 0 ? A : B;
     const int64_t nfast = lanes_along_rows ? mb : nb, nslow = lanes_along_rows ? nb : mb;
     if (nfast <= 0 || nslow <= 0) return 0;
-    int64_t per = 16;
+    if (n_src < 0 || n_src > kMaxTerms || n_dst < 0 || n_dst > kMaxTerms) return (int)hipErrorInvalidValue;
+    int64_t per = LC_SLOW;
     while ((nslow + per - 1) / per > 65535) per *= 2;
-    const int64_t gx = (nfast + 255) / 256, gy = (nslow + per - 1) / per;
+    const int64_t gx = (nfast + 256 * LC_FPT - 1) / (256 * LC_FPT), gy = (nslow + per - 1) / per;
     if (gx > 0x7fffffff || per > (1 << 30)) return (int)hipErrorInvalidValue;
+    const int ns = n_src <= 1 ? 1 : n_src <= 2 ? 2 : 4, nd = n_dst <= 1 ? 1 : n_dst <= 2 ? 2 : 4;  // register-array sizes
+    const dim3 grid((unsigned)gx, (unsigned)gy);
     if (lanes_along_rows)
-        hipLaunchKernelGGL(lincomb_kernel<true>, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, st, prods_dev, index, src, C, W, beta, (int)per);
+        launch_lincomb_sized<true>(ns, nd, grid, st, prods_dev, index, src, C, W, beta, (int)per);
     else
-        hipLaunchKernelGGL(lincomb_kernel<false>, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, st, prods_dev, index, src, C, W, beta, (int)per);
+        launch_lincomb_sized<false>(ns, nd, grid, st, prods_dev, index, src, C, W, beta, (int)per);
     return (int)hipGetLastError();
 }
 

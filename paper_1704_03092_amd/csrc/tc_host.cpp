@@ -798,7 +798,8 @@ FusedShape fused_shape(const tc_plan_t* p, const Step& s) {
 }
 
 // Modelled time of a fused launch except its destination updates: whole tiles in whole waves of `units` tiles, the
-// chunks of the tail tiles in whole waves of their own depth, the chunks written and read back, the second launch.
+// chunks of the tail tiles in whole waves of their own depth, the chunks written and read back, the second launch
+// (measured on small problems: about twice the cost of an ordinary launch).
 struct TailCost {
     double arith, temporaries, launch;
     double total() const { return arith + temporaries + launch; }
@@ -813,7 +814,7 @@ TailCost fused_cost(const tc_model_params_t& mp, const FusedShape& f, int64_t ta
     if (tail_tiles > 0) {
         c.arith += (double)((tail_tiles * chunks + mp.units - 1) / mp.units) * wave(kc);
         c.temporaries = 2.0 * (double)(tail_tiles * chunks) * 128.0 * 128.0 * 8.0 / (mp.rho_b * mp.bandwidth);
-        c.launch += mp.t_launch;
+        c.launch += 2.0 * mp.t_launch;  // the second launch, and the first one draining before it can start
     }
     return c;
 }
@@ -996,7 +997,9 @@ int run_step(const tc_plan_t* plan, const Step& s, double alpha, const double* A
     if (s.kind == STEP_FUSED)
         return tc::launch_fused(s.cfg, plan->prods_dev, s.first, s.count, s.rows, s.cols, A_dev, B_dev, C_dev, W, alpha, beta, s.tail_tiles,
                                 s.tail_chunks, s.tail_kc, plan->wsPart, stream);
-    return tc::launch_lincomb(plan->prods_dev, s.first, s.rows, s.cols, s.lanes_along_rows, A_dev, B_dev, C_dev, W, s.src_role, beta, stream);
+    const Product& q = plan->prods[s.first];
+    return tc::launch_lincomb(plan->prods_dev, s.first, q.A.nterms, q.C.nterms, s.rows, s.cols, s.lanes_along_rows, A_dev, B_dev, C_dev, W, s.src_role,
+                              beta, stream);
 }
 }  // namespace
 

@@ -79,8 +79,9 @@ int launch_fused(const FusedConfig& cfg, const Product* prods_dev, int first, in
                  int64_t tail_kc, int64_t partial_off, void* stream);
 
 // element-wise: v = sum_t coefA_t * srcA_t;  for each destination d: dst_d = coefC_d * v + f_d * dst_d
-// (Product::B is ignored; extents mb x nb).  lanes_along_rows picks the coalesced direction.
-int launch_lincomb(const Product* prods_dev, int index, int64_t mb, int64_t nb, int lanes_along_rows, const double* A,
+// (Product::B is ignored; extents mb x nb).  lanes_along_rows picks the coalesced direction.  n_src, n_dst: the
+// product's numbers of sources and destinations (they select the kernel instantiation).
+int launch_lincomb(const Product* prods_dev, int index, int n_src, int n_dst, int64_t mb, int64_t nb, int lanes_along_rows, const double* A,
                    const double* B, double* C, double* W, int src_role, double beta, void* stream);
 
 }  // namespace tc
