@@ -497,14 +497,23 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     typedef State<AMODE, BMODE, CF, VA, VB> St;
     constexpr int KT = CF::KT, NTA = CF::NTA, NTB = CF::NTB, D = CF::D;
 
-    // ---- which tile: spread consecutive logical ids over one XCD (block b runs on XCD b % 8) ----
+    // ---- which tile ----
     const int bid = blockIdx.x;
     const bool part = bid >= main_count;  // a chunk of a tail tile
     int lid;
     int64_t kbeg = 0;
     if (!part) {
-        const int q8 = main_count >> 3, r8 = main_count & 7, xcd = bid & 7;
-        lid = xcd * q8 + (xcd < r8 ? xcd : r8) + (bid >> 3);
+        // Block b runs on XCD b % 8.  Each round of 256 blocks hands every XCD 32 consecutive logical ids (tiles that
+        // share panels of A and B in that XCD's L2), so the tiles of the ragged last rows, which run the slower
+        // checked loops, are spread over all XCDs; ids are walked from the last to the first, so that those tiles
+        // are not the ones everything else waits for at the end.
+        const int whole_rounds = main_count & ~255;
+        int v = bid;
+        if (bid < whole_rounds) {
+            const int q = bid >> 3;
+            v = ((q >> 5) * 8 + (bid & 7)) * 32 + (q & 31);
+        }
+        lid = main_count - 1 - v;
     } else {
         const int u = bid - main_count;
         lid = main_count + u % tail_tiles;
@@ -545,33 +554,70 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     }
 
     // ---- tile-fixed gather tables; how much of the tile and of the k range is free of zero padding ----
+    // A tile at the ragged edge still runs the unchecked loops if every row (column) that some destination keeps is
+    // real in every term of A (B): the other rows are then gathered from the tile's first row instead (any readable
+    // address will do, the epilogue drops them).  With pair-wise gathers along the rows a term's last odd row counts
+    // as missing, since its pair would reach past the block.
     int64_t klimit = kb;         // k entries that are real in every term of both operands
-    bool tile_full = true;       // every row and column of the tile is real in every term
+    int minA = TM, minB = TN;    // rows / columns of the tile that are real (and pair-complete) in every term
+    int maxCr = 0, maxCc = 0;    // rows / columns that some destination keeps
+    int effA[NTA], effB[NTB];
+    auto clip = [](int64_t v, int hi) { return (int)(v < 0 ? 0 : (v > hi ? hi : v)); };
 #pragma unroll
-    for (int t = 0; t < NTA; ++t)
+    for (int t = 0; t < NTA; ++t) {
+        effA[t] = 0;
         if (t < nA) {
             klimit = min64(klimit, acs_len - P.A.coff[t]);
-            tile_full = tile_full && (i0 + TM <= min64(P.mb, P.A.rs_len - P.A.roff[t]));
+            effA[t] = clip(min64(P.mb, P.A.rs_len - P.A.roff[t]) - i0, TM);
+            if (AMODE == 0 && VA) effA[t] &= ~1;
+            minA = effA[t] < minA ? effA[t] : minA;
         }
+    }
 #pragma unroll
-    for (int t = 0; t < NTB; ++t)
+    for (int t = 0; t < NTB; ++t) {
+        effB[t] = 0;
         if (t < nB) {
             klimit = min64(klimit, brs_len - P.B.roff[t]);
-            tile_full = tile_full && (j0 + TN <= min64(P.nb, P.B.cs_len - P.B.coff[t]));
+            effB[t] = clip(min64(P.nb, P.B.cs_len - P.B.coff[t]) - j0, TN);
+            if (BMODE == 0 && VB) effB[t] &= ~1;
+            minB = effB[t] < minB ? effB[t] : minB;
         }
+    }
+    for (int d = 0; d < P.C.nterms; ++d) {
+        const int r = clip(min64(P.mb, P.C.rs_len - P.C.roff[d]) - i0, TM), c = clip(min64(P.nb, P.C.cs_len - P.C.coff[d]) - j0, TN);
+        maxCr = r > maxCr ? r : maxCr;
+        maxCc = c > maxCc ? c : maxCc;
+    }
+    const bool whole = minA == TM && minB == TN;  // nothing missing at all
+    const bool rows_ok = minA == TM || (minA >= 1 && minA >= maxCr), cols_ok = minB == TN || (minB >= 1 && minB >= maxCc);
+    const bool tile_full = rows_ok && cols_ok;
     st.kfull = tile_full ? (int)(klimit / KT) : 0;  // k-steps [0, kfull) need no checks
     for (int e = tid; e < NTA * TM; e += NTHREADS) {
         const int t = e / TM, x = e % TM;
-        const int64_t gi = i0 + x;
         int64_t val = kSentinel;
-        if (t < nA && gi < P.mb && P.A.roff[t] + gi < P.A.rs_len) val = (int64_t)Abase + 8 * as_global(P.A.rs)[P.A.roff[t] + gi];
+        int eff = 0;
+#pragma unroll
+        for (int u = 0; u < NTA; ++u) eff = (t == u) ? effA[u] : eff;
+        if (t < nA) {
+            if (tile_full && x >= eff)
+                val = (int64_t)Abase + 8 * as_global(P.A.rs)[P.A.roff[t] + i0];
+            else if (i0 + x < P.mb && P.A.roff[t] + i0 + x < P.A.rs_len)
+                val = (int64_t)Abase + 8 * as_global(P.A.rs)[P.A.roff[t] + i0 + x];
+        }
         S.a_fix[t][x] = val;
     }
     for (int e = tid; e < NTB * TN; e += NTHREADS) {
         const int t = e / TN, x = e % TN;
-        const int64_t gj = j0 + x;
         int64_t val = kSentinel;
-        if (t < nB && gj < P.nb && P.B.coff[t] + gj < P.B.cs_len) val = (int64_t)Bbase + 8 * as_global(P.B.cs)[P.B.coff[t] + gj];
+        int eff = 0;
+#pragma unroll
+        for (int u = 0; u < NTB; ++u) eff = (t == u) ? effB[u] : eff;
+        if (t < nB) {
+            if (tile_full && x >= eff)
+                val = (int64_t)Bbase + 8 * as_global(P.B.cs)[P.B.coff[t] + j0];
+            else if (j0 + x < P.nb && P.B.coff[t] + j0 + x < P.B.cs_len)
+                val = (int64_t)Bbase + 8 * as_global(P.B.cs)[P.B.coff[t] + j0 + x];
+        }
         S.b_fix[t][x] = val;
     }
     // Threads 0..KT*NTA-1 fetch the column scatter entries of A for a k-step (one per term and k), threads
@@ -661,6 +707,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     if constexpr (VA && VB && CF::EXACT) {
         affine = P.A.rs_stride >= 0 && P.A.cs_stride >= 0 && P.B.rs_stride >= 0 && P.B.cs_stride >= 0 && P.A.rs_stride < kStrideLimit &&
                  P.A.cs_stride < kStrideLimit && P.B.rs_stride < kStrideLimit && P.B.cs_stride < kStrideLimit;
+        affine = affine && whole;  // (computed addresses of missing rows would leave the operand)
         if (affine) {
             const int wu = __builtin_amdgcn_readfirstlane(wave);
             // A: free bundle = rows, contracted = columns; B: free bundle = columns, contracted = rows
