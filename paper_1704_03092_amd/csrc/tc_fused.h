@@ -620,6 +620,30 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         }
         S.b_fix[t][x] = val;
     }
+    // Scatter entries of the destinations (used by the epilogue; fetched here so that their latency is hidden).
+    int64_t(*c_rs)[TM] = S.c_rs;
+    int64_t(*c_cs)[TN] = S.c_cs;
+    // A chunk of a tail tile has one destination: its dense slot of the partial buffer, contiguous along the
+    // direction c_mode makes the lanes run, written as is (no alpha, no previous contents).
+    const int nC = part ? 1 : P.C.nterms;
+    for (int e = tid; e < MAXC * TM; e += NTHREADS) {
+        const int d = e / TM, x = e % TM;
+        const int64_t gi = i0 + x, gj = j0 + x;
+        int64_t val = kSentinel;
+        if (part) {
+            if (d == 0) val = c_mode == 0 ? x : TN * x;
+        } else if (d < nC && gi < P.mb && P.C.roff[d] + gi < P.C.rs_len) {
+            val = as_global(P.C.rs)[P.C.roff[d] + gi];
+        }
+        c_rs[d][x] = val;
+        val = kSentinel;
+        if (part) {
+            if (d == 0) val = c_mode == 0 ? TM * x : x;
+        } else if (d < nC && gj < P.nb && P.C.coff[d] + gj < P.C.cs_len) {
+            val = as_global(P.C.cs)[P.C.coff[d] + gj];
+        }
+        c_cs[d][x] = val;
+    }
     // Threads 0..KT*NTA-1 fetch the column scatter entries of A for a k-step (one per term and k), threads
     // 256..256+KT*NTB-1 the row scatter entries of B, D + 1 k-steps ahead of the tile that uses them.
     static_assert(KT * NTA <= 256 && KT * NTB <= 256, "one owner thread per table entry");
@@ -738,35 +762,41 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     constexpr int NPASS = (sizeof(S.a) + sizeof(S.b) >= (size_t)TN * OPITCH * sizeof(double)) ? 1 : 2;
     constexpr int CP = TN / NPASS;  // tile columns staged per pass
     static_assert(sizeof(S.a) + sizeof(S.b) >= (size_t)CP * OPITCH * sizeof(double), "output staging does not fit");
-    int64_t(*c_rs)[TM] = S.c_rs;
-    int64_t(*c_cs)[TN] = S.c_cs;
     double* otile = &S.a[0][0];  // [CP columns][OPITCH], rows fastest
-    // A chunk of a tail tile has one destination: its dense slot of the partial buffer, contiguous along the
-    // direction c_mode makes the lanes run, written as is (no alpha, no previous contents).
-    const int nC = part ? 1 : P.C.nterms;
-    for (int e = tid; e < MAXC * TM; e += NTHREADS) {
-        const int d = e / TM, x = e % TM;
-        const int64_t gi = i0 + x, gj = j0 + x;
-        int64_t val = kSentinel;
-        if (part) {
-            if (d == 0) val = c_mode == 0 ? x : TN * x;
-        } else if (d < nC && gi < P.mb && P.C.roff[d] + gi < P.C.rs_len) {
-            val = as_global(P.C.rs)[P.C.roff[d] + gi];
-        }
-        c_rs[d][x] = val;
-        val = kSentinel;
-        if (part) {
-            if (d == 0) val = c_mode == 0 ? TM * x : x;
-        } else if (d < nC && gj < P.nb && P.C.coff[d] + gj < P.C.cs_len) {
-            val = as_global(P.C.cs)[P.C.coff[d] + gj];
-        }
-        c_cs[d][x] = val;
-    }
     double* Cbase = part ? partial + (int64_t)(bid - main_count) * (TM * TN) : (P.C.space == 0 ? Cu : W) + P.C.base_off;
     if (part) alpha = 1.0;
     const int dj = lane & 3, dblk = (lane >> 2) & 3, di = lane >> 4;
+    constexpr int BATCH = CP / 4;  // elements per thread, destination and pass: all their loads are issued together
+    constexpr int RS = NTHREADS / CP;
+    static_assert(BATCH == TM / RS, "both thread mappings cover the pass");
+    // c_mode 0, lanes along the rows: thread = (row r, column group cg), columns cg + 4 b.
+    // c_mode 1, lanes along the columns: thread = (column c, row group rg), rows rg + RS b.
+    const int e_r = tid & 127, e_cg = tid >> 7, e_c = tid % CP, e_rg = tid / CP;
+    auto offset = [&](int d, int pass, int b) -> int64_t {
+        return c_mode == 0 ? c_rs[d][e_r] + c_cs[d][pass * CP + e_cg + 4 * b] : c_rs[d][e_rg + RS * b] + c_cs[d][pass * CP + e_c];
+    };
+    auto factor = [&](int d) -> double { return (part || P.overwrite) ? 0.0 : (((P.first_mask >> d) & 1u) ? beta : 1.0); };
+    // current contents of destination d (where the update needs them)
+    auto fetch = [&](int d, int pass, double (&cur)[BATCH]) {
+        const bool need = factor(d) != 0.0;
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) {
+            const int64_t off = offset(d, pass, b);
+            cur[b] = (need && off >= 0) ? Cbase[off] : 0.0;
+        }
+    };
+    auto update = [&](int d, int pass, const double (&cur)[BATCH]) {
+        const double g = part ? 1.0 : P.C.coef[d], f = factor(d);
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) {
+            const int64_t off = offset(d, pass, b);
+            const double v = g * (c_mode == 0 ? otile[(e_cg + 4 * b) * OPITCH + e_r] : otile[e_c * OPITCH + e_rg + RS * b]);
+            if (off >= 0) Cbase[off] = (f == 0.0) ? v : __builtin_fma(f, cur[b], v);
+        }
+    };
 #pragma unroll 1
     for (int pass = 0; pass < NPASS; ++pass) {
+        double cur[BATCH];
         if (pass > 0) __syncthreads();  // the previous pass has been read out
         if (wn / (4 / NPASS) == pass) {
             const int cw = (wn % (4 / NPASS)) * 32;
@@ -780,48 +810,11 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
                             alpha * st.acc[x][y][s];
         }
         __syncthreads();
-        for (int d = 0; d < nC; ++d) {
-            const double g = part ? 1.0 : P.C.coef[d];
-            const double f = (part || P.overwrite) ? 0.0 : (((P.first_mask >> d) & 1u) ? beta : 1.0);
-            constexpr int BATCH = CP / 4;  // elements per thread, destination and pass: all their loads are issued together
-            static_assert(BATCH == TM / (NTHREADS / CP), "both thread mappings cover the pass");
-            if (c_mode == 0) {
-                // lanes along the rows: thread = (row r, column group cg), columns cg + 4 j
-                const int r = tid & 127, cg = tid >> 7;
-                const int64_t rsd = c_rs[d][r];
-                for (int j0b = 0; j0b < CP / 4; j0b += BATCH) {
-                    int64_t off[BATCH];
-                    double cur[BATCH];
 #pragma unroll
-                    for (int b = 0; b < BATCH; ++b) {
-                        off[b] = rsd + c_cs[d][pass * CP + cg + 4 * (j0b + b)];
-                        cur[b] = (f != 0.0 && off[b] >= 0) ? Cbase[off[b]] : 0.0;
-                    }
-#pragma unroll
-                    for (int b = 0; b < BATCH; ++b) {
-                        const double v = g * otile[(cg + 4 * (j0b + b)) * OPITCH + r];
-                        if (off[b] >= 0) Cbase[off[b]] = (f == 0.0) ? v : __builtin_fma(f, cur[b], v);
-                    }
-                }
-            } else {
-                // lanes along the columns: thread = (column c, row group rg), rows rg + RS j
-                constexpr int RS = NTHREADS / CP;
-                const int c = tid % CP, rg = tid / CP;
-                const int64_t csd = c_cs[d][pass * CP + c];
-                for (int j0b = 0; j0b < TM / RS; j0b += BATCH) {
-                    int64_t off[BATCH];
-                    double cur[BATCH];
-#pragma unroll
-                    for (int b = 0; b < BATCH; ++b) {
-                        off[b] = c_rs[d][rg + RS * (j0b + b)] + csd;
-                        cur[b] = (f != 0.0 && off[b] >= 0) ? Cbase[off[b]] : 0.0;
-                    }
-#pragma unroll
-                    for (int b = 0; b < BATCH; ++b) {
-                        const double v = g * otile[c * OPITCH + rg + RS * (j0b + b)];
-                        if (off[b] >= 0) Cbase[off[b]] = (f == 0.0) ? v : __builtin_fma(f, cur[b], v);
-                    }
-                }
+        for (int d = 0; d < MAXC; ++d) {
+            if (d < nC) {
+                fetch(d, pass, cur);  // (fetching ahead, during the transposition, costs registers and measured slower)
+                update(d, pass, cur);
             }
         }
     }
