@@ -158,6 +158,7 @@ struct Affine {
     uint32_t voff;    // per lane: byte offset of its element pair inside the wave's patch
     int64_t u0[NT];   // per term: byte address of the wave's patch for load 0 of k-step 0
     int64_t dE, dS;   // bytes from one load to the next, from one k-step to the next
+    int last;         // last k-step that exists: gathers issued ahead of the end read that one again
 };
 
 template <int MODE, int NT, int KT>
@@ -166,7 +167,7 @@ __device__ __forceinline__ void issue_affine(double (&ld)[NT][TM * KT / NTHREADS
     typedef const __attribute__((address_space(1))) char* gbyte_t;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        const int64_t ub = a.u0[t] + (int64_t)target * a.dS;
+        const int64_t ub = a.u0[t] + (int64_t)(target < a.last ? target : a.last) * a.dS;
 #pragma unroll
         for (int e = 0; e < M::N; ++e) {
             const double2_t v = *(gdbl2_t)((gbyte_t)(ub + e * a.dE) + a.voff);
@@ -180,9 +181,10 @@ __device__ __forceinline__ void issue_affine(double (&ld)[NT][TM * KT / NTHREADS
 // offx / offk: first free / contracted entry of each term; tile0: first free entry of the tile; w: wave index.
 template <int MODE, int NT, int KT>
 __device__ __forceinline__ void setup_affine(Affine<NT>& a, const double* base, int64_t sx, int64_t sk, const int64_t* offx, const int64_t* offk,
-                                             int64_t tile0, int lane, int w) {
+                                             int64_t tile0, int lane, int w, int last) {
     typedef Map<MODE, KT, true> M;
     constexpr int KB = KT / 16;
+    a.last = last;
     int64_t wx, wk;
     if (MODE == 0) {
         a.voff = (uint32_t)(8 * (2 * lane) * sx);
@@ -284,6 +286,7 @@ struct State {
     int tid, nA, nB, nk, kfull;
     bool unitA, unitB;         // the first coefficient is +1
     bool early;                // first of the two waves of its SIMD
+    bool all_fast;             // no k-step needs checks: gathers issued ahead of the end re-read entries that exist
     double coefA[NTA], coefB[NTB];
     const double *safeA, *safeB;
     // scatter entries of later k-steps
@@ -427,7 +430,8 @@ struct State {
         read_frags<CUR, 0>(af[0], bf[0]);
         groups<CUR, 0, ROLE, FAST, UNIT, AFF>(af, bf, step);
 
-        ent_dst[ESLOT ? ent_stride : 0] = have ? raw_entry * 8 : kSentinel;  // every thread stores: no branch around the wait
+        // every thread stores: no branch around the wait.  (Past the end raw_entry is the thread's first entry.)
+        ent_dst[ESLOT ? ent_stride : 0] = (have || all_fast) ? raw_entry * 8 : kSentinel;
         __syncthreads();
     }
 
@@ -592,6 +596,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     const bool rows_ok = minA == TM || (minA >= 1 && minA >= maxCr), cols_ok = minB == TN || (minB >= 1 && minB >= maxCc);
     const bool tile_full = rows_ok && cols_ok;
     st.kfull = tile_full ? (int)(klimit / KT) : 0;  // k-steps [0, kfull) need no checks
+    // No padding anywhere in the tile: the unchecked loop runs to the end.  The gathers it issues for the D k-steps
+    // past the end are never used; their table entries (and computed addresses) repeat ones that exist.
+    st.all_fast = CF::EXACT && st.kfull == st.nk;
     for (int e = tid; e < NTA * TM; e += NTHREADS) {
         const int t = e / TM, x = e % TM;
         int64_t val = kSentinel;
@@ -708,7 +715,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     if constexpr (D == 2) {
         st.template issue<1, 1, false>(1);
         __syncthreads();  // table slot 0 has been read by every thread
-        st.ent_dst[0] = (2 * KT < st.ent_limit) ? 8 * st.ent_ptr[2 * KT] : kSentinel;
+        st.ent_dst[0] = (2 * KT < st.ent_limit || st.all_fast) ? 8 * st.ent_ptr[2 * KT < st.ent_limit ? 2 * KT : 0] : kSentinel;
     }
     st.template stage<0, 0, false, false>();
 #pragma unroll
@@ -725,6 +732,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     // (sums whose terms are counted at run time only occur for blocks a few tiles wide: they take the general loop)
     int nfast = CF::EXACT ? st.kfull - D : 0;
     nfast = nfast < 2 ? 0 : (nfast & ~1);
+    if (st.all_fast) nfast = st.nk;
     // table-free gather for products whose operands are both plain strided matrices (and gathered pair-wise)
     constexpr int64_t kStrideLimit = (int64_t)1 << 20;  // keeps the per-lane byte offset within 32 bits
     bool affine = false;
@@ -735,8 +743,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         if (affine) {
             const int wu = __builtin_amdgcn_readfirstlane(wave);
             // A: free bundle = rows, contracted = columns; B: free bundle = columns, contracted = rows
-            setup_affine<AMODE, NTA, KT>(st.afa, Abase + kbeg * P.A.cs_stride, P.A.rs_stride, P.A.cs_stride, P.A.roff, P.A.coff, i0, lane, wu);
-            setup_affine<BMODE, NTB, KT>(st.afb, Bbase + kbeg * P.B.rs_stride, P.B.cs_stride, P.B.rs_stride, P.B.coff, P.B.roff, j0, lane, wu);
+            setup_affine<AMODE, NTA, KT>(st.afa, Abase + kbeg * P.A.cs_stride, P.A.rs_stride, P.A.cs_stride, P.A.roff, P.A.coff, i0, lane, wu, st.nk - 1);
+            setup_affine<BMODE, NTB, KT>(st.afb, Bbase + kbeg * P.B.rs_stride, P.B.cs_stride, P.B.rs_stride, P.B.coff, P.B.roff, j0, lane, wu, st.nk - 1);
         }
     }
     if (nfast > 0) {
