@@ -161,18 +161,37 @@ struct Affine {
     int last;         // last k-step that exists: gathers issued ahead of the end read that one again
 };
 
-template <int MODE, int NT, int KT>
+// BUF: the loads are buffer loads, whose descriptor base (scalar registers), scalar offset and per-lane offset are
+// added by the address unit, where a global load needs a 64-bit vector add per load.  Measured at 16384^3: the
+// two-term families gain 1 % from buffer loads; the (1,1) family with two k-steps in flight loses 2 % (its issue
+// points were tuned with the adds between the loads) and the four-term families lose 6 % (four descriptors per
+// operand spill scalar registers), so those keep global loads.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+template <int MODE, int NT, int KT, bool BUF>
 __device__ __forceinline__ void issue_affine(double (&ld)[NT][TM * KT / NTHREADS], const Affine<NT>& a, int target) {
     typedef Map<MODE, KT, true> M;
     typedef const __attribute__((address_space(1))) char* gbyte_t;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int64_t ub = a.u0[t] + (int64_t)(target < a.last ? target : a.last) * a.dS;
+        if constexpr (BUF) {
+            // raw buffer over the address space from ub on: no stride, no range limit that matters
+            const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)ub, 0, -1, 0x00020000);
 #pragma unroll
-        for (int e = 0; e < M::N; ++e) {
-            const double2_t v = *(gdbl2_t)((gbyte_t)(ub + e * a.dE) + a.voff);
-            ld[t][2 * e] = v.x;
-            ld[t][2 * e + 1] = v.y;
+            for (int e = 0; e < M::N; ++e) {
+                const double2_t v =
+                    __builtin_bit_cast(double2_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)a.voff, (int)(e * a.dE), 0));
+                ld[t][2 * e] = v.x;
+                ld[t][2 * e + 1] = v.y;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < M::N; ++e) {
+                const double2_t v = *(gdbl2_t)((gbyte_t)(ub + e * a.dE) + a.voff);
+                ld[t][2 * e] = v.x;
+                ld[t][2 * e + 1] = v.y;
+            }
         }
     }
 }
@@ -310,8 +329,9 @@ struct State {
     template <int SET, int SLOT, bool FAST, bool AFF = false>
     __device__ __forceinline__ void issue(int target) {
         if constexpr (FAST && AFF) {
-            issue_affine<AMODE, NTA, KT>(la[SET], afa, target);
-            issue_affine<BMODE, NTB, KT>(lb[SET], afb, target);
+            constexpr bool BUF = D == 1 && NTA <= 2 && NTB <= 2;  // (four descriptors per operand would spill scalar registers)
+            issue_affine<AMODE, NTA, KT, BUF>(la[SET], afa, target);
+            issue_affine<BMODE, NTB, KT, BUF>(lb[SET], afb, target);
             return;
         }
         if (!FAST) issued_fast[SET] = target < kfull;
@@ -423,7 +443,9 @@ struct State {
         constexpr int ESLOT = (D == 2) ? (CUR ^ 1) : CUR;
         const int kn = (step + D + 1) * KT;
         const bool have = kn < ent_limit;
-        const int64_t raw_entry = ent_ptr[have ? kn : 0];  // unconditional load: ent_ptr always points at readable memory
+        int64_t raw_entry = 0;
+        constexpr bool NOENT = AFF && KT == 32;  // (measured: the four-term families lose 2 % without the fetch in their loop)
+        if constexpr (!NOENT) raw_entry = ent_ptr[have ? kn : 0];  // unconditional load: ent_ptr always points at readable memory
 
         between_groups<CUR, 0, ROLE, FAST, UNIT, AFF>(step);
         double af[2][4], bf[2][8];
@@ -431,7 +453,8 @@ struct State {
         groups<CUR, 0, ROLE, FAST, UNIT, AFF>(af, bf, step);
 
         // every thread stores: no branch around the wait.  (Past the end raw_entry is the thread's first entry.)
-        ent_dst[ESLOT ? ent_stride : 0] = (have || all_fast) ? raw_entry * 8 : kSentinel;
+        // The table-free loop runs to the tile's last k-step and needs no entries at all.
+        if constexpr (!NOENT) ent_dst[ESLOT ? ent_stride : 0] = (have || all_fast) ? raw_entry * 8 : kSentinel;
         __syncthreads();
     }
 
@@ -734,12 +757,14 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     nfast = nfast < 2 ? 0 : (nfast & ~1);
     if (st.all_fast) nfast = st.nk;
     // table-free gather for products whose operands are both plain strided matrices (and gathered pair-wise)
-    constexpr int64_t kStrideLimit = (int64_t)1 << 20;  // keeps the per-lane byte offset within 32 bits
+    constexpr int64_t kStrideLimit = (int64_t)1 << 20;  // keeps the per-lane and per-load byte offsets within 31 bits
     bool affine = false;
     if constexpr (VA && VB && CF::EXACT) {
         affine = P.A.rs_stride >= 0 && P.A.cs_stride >= 0 && P.B.rs_stride >= 0 && P.B.cs_stride >= 0 && P.A.rs_stride < kStrideLimit &&
                  P.A.cs_stride < kStrideLimit && P.B.rs_stride < kStrideLimit && P.B.cs_stride < kStrideLimit;
-        affine = affine && whole;  // (computed addresses of missing rows would leave the operand)
+        // (computed addresses of missing rows would leave the operand; a tile with padded k-steps needs the tables
+        // for them, and the table-free loop does not keep them up to date)
+        affine = affine && whole && st.all_fast;
         if (affine) {
             const int wu = __builtin_amdgcn_readfirstlane(wave);
             // A: free bundle = rows, contracted = columns; B: free bundle = columns, contracted = rows
