@@ -165,7 +165,9 @@ struct Affine {
 // added by the address unit, where a global load needs a 64-bit vector add per load.  Measured at 16384^3: the
 // two-term families gain 1 % from buffer loads; the (1,1) family with two k-steps in flight loses 2 % (its issue
 // points were tuned with the adds between the loads) and the four-term families lose 6 % (four descriptors per
-// operand spill scalar registers), so those keep global loads.
+// operand spill scalar registers), so those keep global loads.  (Global loads in their scalar-base form, which
+// also needs no vector add, measured 2 % slower for the (1,1) family as well: back-to-back loads without the adds
+// between them delay the matrix-core instructions of the partner wave more.)
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 template <int MODE, int NT, int KT, bool BUF>
