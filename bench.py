@@ -26,13 +26,13 @@ if ROOT not in sys.path:
 FP64_MFMA_PEAK_TFLOPS = 78.6  # MI355X published dense FP64 matrix peak
 
 
-def profiled_traffic(N, level, variant):
+def profiled_traffic(wname, level, variant):
     """HBM bytes per fused-kernel launch (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy kernel) from the committed
     counter summary of this exact workload; None if there is none.  The counters need the profiler, so they are
     collected in separate runs of this script under rocprofv3 --pmc and written down in profiles/."""
     import re
 
-    path = os.path.join(ROOT, "profiles", f"fused_kernel_cfg2_{N}_level{level}_{variant}.md")
+    path = os.path.join(ROOT, "profiles", f"fused_kernel_{wname}_level{level}_{variant}.md")
     try:
         m = re.search(r"^hbm_traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(path).read(), re.M)
     except OSError:
@@ -46,6 +46,7 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--size", type=int, default=16384, help="m = n = k of the square contraction")
+    ap.add_argument("--workload", default="", help="another benchmark configuration instead of the square one: cfg1, cfg3, cfg4a, cfg4b, cfg5")
     ap.add_argument("--level", type=int, default=1)
     ap.add_argument("--variant", default="hybrid")
     ap.add_argument("--modes", default="0abc,1abc,1ab,1naive,1hybrid,2abc,2ab,2naive,2hybrid", help="other modes to time (level+variant)")
@@ -66,7 +67,14 @@ def main():
     tc.load_library()  # no fallback: fails if the HIP library is missing
     torch.cuda.set_device(0)
     N = args.size
-    cfg = workloads.gemm(N)
+    if args.workload:
+        cfg = workloads.configs()[args.workload]
+        wname = args.workload
+        wtext = f"{cfg.name} contraction {cfg.idxC}-{cfg.idxA}-{cfg.idxB}, lengths {cfg.lengths}, {cfg.kind}, alpha={cfg.alpha:g} beta={cfg.beta:g}, generalized column-major"
+    else:
+        cfg = workloads.gemm(N)
+        wname = f"cfg2_{N}"
+        wtext = f"cfg2 square contraction ij-ik-kj, m=n=k={N}, uniform[-1,1), alpha=1 beta=1, column-major"
     m, n, k = cfg.mnk()
     flops = 2.0 * m * n * k
     A, B, C = cfg.tensors()
@@ -143,16 +151,20 @@ def main():
     dC.copy_(dC0)
     one_step(args.level, args.variant)
     torch.cuda.synchronize()
-    got = dC.view(n, m).t()[torch.from_numpy(rows).to("cuda")].cpu().numpy()  # column-major storage: element (i, j) at i + j * m
-    ref = oracle.contract_rows(A, B, C, rows, cfg.alpha, cfg.beta, orders=(["i"], ["j"], ["k"]))
-    normA_rows = oracle.fro(A.view()[rows, :])
-    parity = oracle.error_metric(got, ref, normA_rows, oracle.fro(B.data))
+    orders = (list(info["I"]), list(info["J"]), list(info["P"]))  # the matrix view the plan chose
+    view = oracle.matrix_view(A, B, C, orders=orders)
+    drows = torch.from_numpy(view["rsC"][rows]).to("cuda")
+    dcols = torch.from_numpy(view["csC"]).to("cuda")
+    got = dC[drows[:, None] + dcols[None, :]].cpu().numpy()
+    ref = oracle.contract_rows(A, B, C, rows, cfg.alpha, cfg.beta, view=view)
+    normA_rows = oracle.fro(A.data[view["rsA"][rows][:, None] + view["csA"][None, :]])
+    parity = oracle.error_metric(got, ref, normA_rows, oracle.tensor_norm(B))
 
     # ---- roofline of the dominant kernel (fused gather + MFMA + update): executed flops / its own launch durations ----
     executed = flops * (7.0 / 8.0) ** info["level"]
     achieved = executed / (kern["fused_ms"] * 1e-3) * 1e-12
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / FP64_MFMA_PEAK_TFLOPS, 4), "traffic": profiled_traffic(N, info["level"], "abc" if info["level"] == 0 else args.variant),
+                "frac": round(achieved / FP64_MFMA_PEAK_TFLOPS, 4), "traffic": profiled_traffic(wname, info["level"], "abc" if info["level"] == 0 else args.variant),
                 "kernel": "fused_kernel", "launches_per_contract": kern["fused_launches"],
                 "flops_per_launch": executed / kern["fused_launches"], "avg_launch_ms": round(kern["fused_ms"] / kern["fused_launches"], 4),
                 "other_kernels_ms_per_contract": round(kern["elementwise_ms"], 3)}
@@ -183,7 +195,7 @@ def main():
         "metric": "effective fp64 GFLOPS (2mnk/t)", "value": round(value, 1), "unit": "GFLOPS", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(wall_ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
-        "config": {"workload": f"cfg2 square contraction ij-ik-kj, m=n=k={N}, uniform[-1,1), alpha=1 beta=1, column-major",
+        "config": {"workload": wtext,
                    "level": info["level"], "variant": args.variant, "step": "tc_plan + tc_contract + tc_destroy",
                    "contract_ms": round(ev_ms, 3), "frac_fp64_mfma_peak_effective": round(value * 1e-3 / FP64_MFMA_PEAK_TFLOPS, 4),
                    "parity_sampled_rows": float(f"{parity:.3e}"), "parity_rows": int(len(rows)), "modes": modes},

@@ -222,10 +222,10 @@ int launch_fused(const FusedConfig& cfg, const Product* prods_dev, int first, in
     if (err || tail_tiles == 0) return err;
     const int main_count = (int)((int64_t)count * tm * tn - tail_tiles);
     if (cfg.c_mode == 0)
-        hipLaunchKernelGGL(fused::tail_fixup_kernel<true>, dim3((unsigned)tail_tiles), dim3(fused::NTHREADS), 0, st, prods_dev, first, tm, tn,
+        hipLaunchKernelGGL(fused::tail_fixup_kernel<true>, dim3((unsigned)tail_tiles, fused::FIX_SLICES), dim3(fused::NTHREADS), 0, st, prods_dev, first, tm, tn,
                            main_count, tail_tiles, tail_chunks, tail.partial, C, W, alpha, beta);
     else
-        hipLaunchKernelGGL(fused::tail_fixup_kernel<false>, dim3((unsigned)tail_tiles), dim3(fused::NTHREADS), 0, st, prods_dev, first, tm, tn,
+        hipLaunchKernelGGL(fused::tail_fixup_kernel<false>, dim3((unsigned)tail_tiles, fused::FIX_SLICES), dim3(fused::NTHREADS), 0, st, prods_dev, first, tm, tn,
                            main_count, tail_tiles, tail_chunks, tail.partial, C, W, alpha, beta);
     return (int)hipGetLastError();
 }

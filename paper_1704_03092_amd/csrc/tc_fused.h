@@ -911,8 +911,15 @@ int launch_family(int a_mode, int b_mode, int vec, int c_mode, const Product* pr
     }
 
 // Sum of the chunks of every tail tile, in chunk order, added to the destinations exactly as the fused kernel's
-// epilogue does for a whole tile (Sec. 4.2).  One workgroup per tail tile.  LANES_ROWS: lanes run along the tile's
-// rows (the partial tiles were written with c_mode 0, rows contiguous); otherwise along its columns.
+// epilogue does for a whole tile (Sec. 4.2).  Grid: (tail tile, slice of FIX_SLOW entries of the slow direction); a
+// thread owns FIX_PER elements and issues the loads of all their chunks together before it adds them (one workgroup
+// per tile with one element at a time took 0.25 ms for 16 tiles of 16 chunks).  LANES_ROWS: lanes run along the
+// tile's rows (the partial tiles were written with c_mode 0, rows contiguous); otherwise along its columns.
+constexpr int FIX_PER = 2;                                // elements per thread
+constexpr int FIX_SLOW = FIX_PER * (NTHREADS / TM);       // slow entries per workgroup
+constexpr int FIX_SLICES = TM / FIX_SLOW;                 // workgroups per tail tile
+constexpr int FIX_MAXCHUNKS = 16;                         // chunks whose loads are in flight together
+
 template <bool LANES_ROWS>
 __global__ __launch_bounds__(NTHREADS) void tail_fixup_kernel(const Product* __restrict__ prods, int first, int tiles_m, int tiles_n,
                                                               int main_count, int tail_tiles, int chunks, const double* __restrict__ partial,
@@ -923,9 +930,9 @@ __global__ __launch_bounds__(NTHREADS) void tail_fixup_kernel(const Product* __r
     const int64_t i0 = (int64_t)tile.tm * TM, j0 = (int64_t)tile.tn * TN;
     double* Cbase = (P.C.space == 0 ? Cu : W) + P.C.base_off;
     const int nC = P.C.nterms;
-    const int fast = tid & 127, sg = tid >> 7;  // position along the lanes' direction; the other direction: sg + 4 j
+    const int fast = tid & (TM - 1), sg = tid / TM;  // position along the lanes' direction; the other: slice + sg + 4 j
     const int64_t gfast = (LANES_ROWS ? i0 : j0) + fast;
-    const int64_t lim_fast = LANES_ROWS ? P.mb : P.nb;
+    const int64_t lim_fast = LANES_ROWS ? P.mb : P.nb, lim_slow = LANES_ROWS ? P.nb : P.mb;
     int64_t fix[MAXC];
 #pragma unroll
     for (int d = 0; d < MAXC; ++d) {
@@ -935,21 +942,39 @@ __global__ __launch_bounds__(NTHREADS) void tail_fixup_kernel(const Product* __r
             if (g < (LANES_ROWS ? P.C.rs_len : P.C.cs_len)) fix[d] = as_global(LANES_ROWS ? P.C.rs : P.C.cs)[g];
         }
     }
-    const int64_t lim_slow = LANES_ROWS ? P.nb : P.mb;
-    for (int j = 0; j < TM / 4; ++j) {
-        const int slow = sg + 4 * j;
-        const int64_t gslow = (LANES_ROWS ? j0 : i0) + slow;
+    const int64_t stride_c = (int64_t)tail_tiles * (TM * TN);  // from one chunk of a tile to the next
+    double v[FIX_PER];
+    int slow[FIX_PER];
+#pragma unroll
+    for (int j = 0; j < FIX_PER; ++j) {
+        slow[j] = blockIdx.y * FIX_SLOW + sg + (NTHREADS / TM) * j;
+        v[j] = 0.0;
+    }
+    for (int c0 = 0; c0 < chunks; c0 += FIX_MAXCHUNKS) {
+        double x[FIX_PER][FIX_MAXCHUNKS];
+#pragma unroll
+        for (int j = 0; j < FIX_PER; ++j) {
+            const double* src = partial + (int64_t)t * (TM * TN) + slow[j] * TM + fast + c0 * stride_c;
+#pragma unroll
+            for (int c = 0; c < FIX_MAXCHUNKS; ++c) x[j][c] = (c0 + c < chunks) ? src[c * stride_c] : 0.0;
+        }
+#pragma unroll
+        for (int j = 0; j < FIX_PER; ++j)
+#pragma unroll
+            for (int c = 0; c < FIX_MAXCHUNKS; ++c)
+                if (c0 + c < chunks) v[j] = (c0 + c == 0) ? x[j][c] : v[j] + x[j][c];  // chunk order, whatever the batch size
+    }
+#pragma unroll
+    for (int j = 0; j < FIX_PER; ++j) {
+        const int64_t gslow = (LANES_ROWS ? j0 : i0) + slow[j];
         if (gslow >= lim_slow) continue;
-        const double* src = partial + (int64_t)t * (TM * TN) + slow * 128 + fast;
-        double v = src[0];
-        for (int c = 1; c < chunks; ++c) v += src[(int64_t)c * tail_tiles * (TM * TN)];
-        v *= alpha;
+        const double av = alpha * v[j];
         for (int d = 0; d < nC; ++d) {
             const int64_t g = (LANES_ROWS ? P.C.coff[d] : P.C.roff[d]) + gslow;
             if (fix[d] < 0 || g >= (LANES_ROWS ? P.C.cs_len : P.C.rs_len)) continue;
             const int64_t off = fix[d] + as_global(LANES_ROWS ? P.C.cs : P.C.rs)[g];
             const double f = P.overwrite ? 0.0 : (((P.first_mask >> d) & 1u) ? beta : 1.0);
-            const double gv = P.C.coef[d] * v;
+            const double gv = P.C.coef[d] * av;
             Cbase[off] = (f == 0.0) ? gv : __builtin_fma(f, Cbase[off], gv);
         }
     }
