@@ -161,7 +161,7 @@ typedef struct {
  * temporaries = the T_m^{+} terms (element-wise passes of the AB and Naive variants), launch = launches * t_launch.
  * Reading A and B is taken as hidden behind the matrix cores.  A launch that splits its tail counts its whole tiles in
  * whole waves of full depth plus the chunks in whole waves of chunk depth (arith), the chunks written and read back
- * (temporaries) and three more launches' worth of time (the second kernel, and the first one draining before it). */
+ * (temporaries) and one more launch. */
 typedef struct {
     double total, arith, c_update, temporaries, launch;
 } tc_model_time_t;

@@ -123,7 +123,7 @@ def granular_time(launches: Sequence[dict], p: MachineParams) -> Dict[str, float
     contracted bundle into s chunks of kc entries, computed by one unit each and stored; a further launch reads them
     back and adds them.  The whole tiles then count in whole waves of depth kb, the r * s chunks in whole waves of
     depth kc, the chunks written and read back are a T_m^{+} term (2 * r * s * tile_m * tile_n elements), and the
-    second launch, which starts only when the first has drained, costs 3 * t_launch.
+    second launch costs t_launch.
     """
     tau_b = 8.0 / (p.rho_b * p.bandwidth)
     out = {"arith": 0.0, "c_update": 0.0, "temporaries": 0.0, "launch": 0.0}
@@ -147,7 +147,7 @@ def granular_time(launches: Sequence[dict], p: MachineParams) -> Dict[str, float
                 pieces = tail["tiles"] * tail["chunks"]
                 out["arith"] += math.ceil(pieces / p.units) * wave(tail["kc"])
                 out["temporaries"] += 2.0 * pieces * p.tile_m * p.tile_n * tau_b
-                out["launch"] += 3.0 * p.t_launch
+                out["launch"] += p.t_launch
             out["c_update"] += sum(q["c_elems"] for q in L["products"]) * tau_b
         else:
             out["temporaries"] += L["elems"] * tau_b

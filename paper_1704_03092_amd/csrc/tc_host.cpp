@@ -799,8 +799,7 @@ FusedShape fused_shape(const tc_plan_t* p, const Step& s) {
 }
 
 // Modelled time of a fused launch except its destination updates: whole tiles in whole waves of `units` tiles, the
-// chunks of the tail tiles in whole waves of their own depth, the chunks written and read back, the second launch
-// (measured on small problems: about three times the cost of an ordinary launch).
+// chunks of the tail tiles in whole waves of their own depth, the chunks written and read back, the second launch.
 struct TailCost {
     double arith, temporaries, launch;
     double total() const { return arith + temporaries + launch; }
@@ -815,14 +814,14 @@ TailCost fused_cost(const tc_model_params_t& mp, const FusedShape& f, int64_t ta
     if (tail_tiles > 0) {
         c.arith += (double)((tail_tiles * chunks + mp.units - 1) / mp.units) * wave(kc);
         c.temporaries = 2.0 * (double)(tail_tiles * chunks) * 128.0 * 128.0 * 8.0 / (mp.rho_b * mp.bandwidth);
-        c.launch += 3.0 * mp.t_launch;  // the second launch, and the first one draining before it can start
+        c.launch += mp.t_launch;  // the second launch
     }
     return c;
 }
 
-// The tail of a launch: the tiles beyond the last full round of the compute units.  Cut into 2..16 chunks of at
-// least 256 contracted entries (a multiple of 64) if the model says that this is faster than running them whole.
-// forced >= 2: that many chunks (of at least 64 entries) whatever the model says.
+// The tail of a launch: the tiles beyond the last full round of the compute units.  Cut into 2..16 chunks of a
+// multiple of 64 contracted entries if the model says that this is faster than running them whole.
+// forced >= 2: that many chunks whatever the model says.
 void choose_tail(const tc_plan_t* p, Step& s, const tc_model_params_t& mp, int forced) {
     s.tail_tiles = s.tail_chunks = 0;
     s.tail_kc = 0;
@@ -832,7 +831,6 @@ void choose_tail(const tc_plan_t* p, Step& s, const tc_model_params_t& mp, int f
     double best = fused_cost(mp, f, 0, 0, 0).total();
     for (int64_t want = forced ? forced : 2; want <= (forced ? forced : 16); ++want) {
         const int64_t kc = round_up((f.kb + want - 1) / want, 64);
-        if (!forced && kc < 256) break;
         const int64_t chunks = (f.kb + kc - 1) / kc;
         if (chunks < 2 || r * chunks > 1024) continue;
         const double t = fused_cost(mp, f, r, chunks, kc).total();

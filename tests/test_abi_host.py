@@ -314,8 +314,8 @@ def _launch_cost(L, mp, tail):
                                                   ((256, 256, 256), 0, "abc"), ((3000, 2000, 700), 1, "ab")])
 def test_tail_split_is_the_argmin_of_the_model(shape, level, variant):
     """Every launch: the tail is what is left after whole rounds of the units; the chunk count is the one with the
-    smallest modelled time among 1 (no split) and the admissible 2..16 (chunks of a multiple of 64, at least 256,
-    entries; at most 1024 chunks), evaluated by the oracle's model; the prediction of the whole plan and the
+    smallest modelled time among 1 (no split) and the admissible 2..16 (chunks of a multiple of 64 entries; at most
+    1024 chunks), evaluated by the oracle's model; the prediction of the whole plan and the
     workspace follow."""
     import math
 
@@ -342,7 +342,7 @@ def test_tail_split_is_the_argmin_of_the_model(shape, level, variant):
             for want in range(2, 17):
                 kc = -(-(-(-b["depth"] // want)) // 64) * 64
                 chunks = -(-b["depth"] // kc)
-                if kc < 256 or chunks < 2 or r * chunks > 1024:
+                if chunks < 2 or r * chunks > 1024:
                     continue
                 options[(r, chunks, kc)] = _launch_cost(b, mp, {"tiles": r, "chunks": chunks, "kc": kc})
         best = min(options.values())
@@ -351,9 +351,9 @@ def test_tail_split_is_the_argmin_of_the_model(shape, level, variant):
         if got:
             assert (b["tail_chunks"] - 1) * b["tail_kc"] < b["depth"] <= b["tail_chunks"] * b["tail_kc"]
             most = max(most, r * b["tail_chunks"])
-            extra_l += 3.0 * mp.t_launch
+            extra_l += mp.t_launch
             extra_t += 2.0 * r * b["tail_chunks"] * 128 * 128 * 8 / (mp.rho_b * mp.bandwidth)
-            extra_a += options[got] - options[None] - 3.0 * mp.t_launch - 2.0 * r * b["tail_chunks"] * 128 * 128 * 8 / (mp.rho_b * mp.bandwidth)
+            extra_a += options[got] - options[None] - mp.t_launch - 2.0 * r * b["tail_chunks"] * 128 * 128 * 8 / (mp.rho_b * mp.bandwidth)
     t0, t1 = tc.tc_plan_predict(plain), tc.tc_plan_predict(plan)
     assert t1["launch"] == pytest.approx(t0["launch"] + extra_l, rel=1e-12)
     assert t1["temporaries"] == pytest.approx(t0["temporaries"] + extra_t, rel=1e-12, abs=1e-18)
