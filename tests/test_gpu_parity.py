@@ -237,6 +237,44 @@ def test_tail_split_whole_and_split_tiles_together(gpu):
         _check(gpu, A, B, C, rng.choice([1.0, -2.0]), rng.choice([0.0, 1.0, 3.0]), level, variant, exact=bool(trial % 2), tail_split=rng.choice([2, 3, 7]))
 
 
+def test_column_stride_beyond_the_table_free_limit(gpu):
+    """Plain matrices whose column stride is 2^20 + 8 elements: the table-free gather (strides below 2^20 only) must
+    step aside for the gather through the scatter tables; full tiles, several k-steps, every family at level 1."""
+    ld = (1 << 20) + 8
+    m, n, k = 256, 160, 128
+    A = workloads.make_tensor("ik", {"i": m, "k": k}, 5, 0, "smallint", (1, ld))
+    B = workloads.make_tensor("kj", {"k": k, "j": n}, 5, 1, "smallint", (1, k))
+    C = workloads.make_tensor("ij", {"i": m, "j": n}, 5, 2, "smallint", (1, m))
+    for level, variant in ((0, "abc"), (1, "abc"), (1, "hybrid")):
+        _check(gpu, A, B, C, 1.0, 1.0, level, variant, exact=True)
+
+
+def test_results_are_reproducible(gpu):
+    """No floating-point atomics anywhere: the same plan gives the same bits on every call, also with the tail of a
+    launch cut into chunks and with the contracted bundle split."""
+    import torch
+
+    import paper_1704_03092_amd as tc
+    from gpu_util import to_dev
+
+    c = workloads.Contraction("g", "ij", "ik", "kj", {"i": 2500, "j": 1850, "k": 900}, seed=33)
+    A, B, C = c.tensors()
+    st = torch.cuda.current_stream()
+    dA, dB = to_dev(A), to_dev(B)
+    for level, variant, kw in ((0, "abc", {"tail_split": 4}), (1, "abc", {}), (1, "hybrid", {"tail_split": 3}), (2, "ab", {}), (0, "abc", {"split_k": 3})):
+        plan = tc.tc_plan(A, B, C, level, variant, st, **kw)
+        ws = torch.empty(max(tc.tc_plan_workspace_bytes(plan) // 8, 1), dtype=torch.float64, device="cuda")
+        outs = []
+        for _ in range(3):
+            dC = to_dev(C)
+            ws.fill_(float("nan"))
+            tc.tc_contract(plan, 1.25, dA, dB, 0.5, dC, ws, st)
+            torch.cuda.synchronize()
+            outs.append(dC)
+        tc.tc_destroy(plan)
+        assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2]), (level, variant, kw)
+
+
 def test_contract_timed_matches_contract(gpu):
     """tc_contract_timed enqueues the same launches: identical bits, and it counts the launches per kind."""
     import torch
