@@ -624,6 +624,32 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     // No padding anywhere in the tile: the unchecked loop runs to the end.  The gathers it issues for the D k-steps
     // past the end are never used; their table entries (and computed addresses) repeat ones that exist.
     st.all_fast = CF::EXACT && st.kfull == st.nk;
+    // table-free gather for products whose operands are both plain strided matrices (and gathered pair-wise)
+    constexpr int64_t kStrideLimit = (int64_t)1 << 20;  // keeps the per-lane and per-load byte offsets within 31 bits
+    bool affine = false;
+    if constexpr (VA && VB && CF::EXACT) {
+        affine = P.A.rs_stride >= 0 && P.A.cs_stride >= 0 && P.B.rs_stride >= 0 && P.B.cs_stride >= 0 && P.A.rs_stride < kStrideLimit &&
+                 P.A.cs_stride < kStrideLimit && P.B.rs_stride < kStrideLimit && P.B.cs_stride < kStrideLimit;
+        // (computed addresses of missing rows would leave the operand; a tile with padded k-steps needs the tables
+        // for them, and the table-free loop does not keep them up to date)
+        affine = affine && whole && st.all_fast;
+        if (affine) {
+            const int wu = __builtin_amdgcn_readfirstlane(tid >> 6);
+            // A: free bundle = rows, contracted = columns; B: free bundle = columns, contracted = rows
+            setup_affine<AMODE, NTA, KT>(st.afa, Abase + kbeg * P.A.cs_stride, P.A.rs_stride, P.A.cs_stride, P.A.roff, P.A.coff, i0, tid & 63, wu, st.nk - 1);
+            setup_affine<BMODE, NTB, KT>(st.afb, Bbase + kbeg * P.B.rs_stride, P.B.cs_stride, P.B.rs_stride, P.B.coff, P.B.roff, j0, tid & 63, wu, st.nk - 1);
+        }
+    }
+    // Such a tile needs no table for its gathers: the first D k-steps are issued here, before the tables are
+    // fetched, so that the two latencies overlap.
+    if constexpr (VA && VB && CF::EXACT) {
+        if (affine) {
+            st.template issue<0, 0, true, true>(0);
+            if constexpr (D == 2) st.template issue<1, 1, true, true>(1);
+#pragma unroll
+            for (int d = 0; d < D; ++d) st.issued_fast[d] = true;
+        }
+    }
     for (int e = tid; e < NTA * TM; e += NTHREADS) {
         const int t = e / TM, x = e % TM;
         int64_t val = kSentinel;
@@ -736,9 +762,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
 
     // ---- prologue: k-step 0 into LDS buffer 0; with two steps in flight also the gather of k-step 1 and the
     //      scatter entries of k-step 2 ----
-    st.template issue<0, 0, false>(0);
+    if (!affine) st.template issue<0, 0, false>(0);
     if constexpr (D == 2) {
-        st.template issue<1, 1, false>(1);
+        if (!affine) st.template issue<1, 1, false>(1);
         __syncthreads();  // table slot 0 has been read by every thread
         st.ent_dst[0] = (2 * KT < st.ent_limit || st.all_fast) ? 8 * st.ent_ptr[2 * KT < st.ent_limit ? 2 * KT : 0] : kSentinel;
     }
@@ -758,22 +784,6 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     int nfast = CF::EXACT ? st.kfull - D : 0;
     nfast = nfast < 2 ? 0 : (nfast & ~1);
     if (st.all_fast) nfast = st.nk;
-    // table-free gather for products whose operands are both plain strided matrices (and gathered pair-wise)
-    constexpr int64_t kStrideLimit = (int64_t)1 << 20;  // keeps the per-lane and per-load byte offsets within 31 bits
-    bool affine = false;
-    if constexpr (VA && VB && CF::EXACT) {
-        affine = P.A.rs_stride >= 0 && P.A.cs_stride >= 0 && P.B.rs_stride >= 0 && P.B.cs_stride >= 0 && P.A.rs_stride < kStrideLimit &&
-                 P.A.cs_stride < kStrideLimit && P.B.rs_stride < kStrideLimit && P.B.cs_stride < kStrideLimit;
-        // (computed addresses of missing rows would leave the operand; a tile with padded k-steps needs the tables
-        // for them, and the table-free loop does not keep them up to date)
-        affine = affine && whole && st.all_fast;
-        if (affine) {
-            const int wu = __builtin_amdgcn_readfirstlane(wave);
-            // A: free bundle = rows, contracted = columns; B: free bundle = columns, contracted = rows
-            setup_affine<AMODE, NTA, KT>(st.afa, Abase + kbeg * P.A.cs_stride, P.A.rs_stride, P.A.cs_stride, P.A.roff, P.A.coff, i0, lane, wu, st.nk - 1);
-            setup_affine<BMODE, NTB, KT>(st.afb, Bbase + kbeg * P.B.rs_stride, P.B.cs_stride, P.B.rs_stride, P.B.coff, P.B.roff, j0, lane, wu, st.nk - 1);
-        }
-    }
     if (nfast > 0) {
         const bool role0 = __builtin_amdgcn_readfirstlane(wm) == 0;
         if (CF::EXACT && st.unitA && st.unitB) {  // a loop of its own: no multiply (or no arithmetic at all) per element
