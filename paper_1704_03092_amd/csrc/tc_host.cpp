@@ -768,7 +768,7 @@ void copy_labels(char* out, const std::vector<Dim>& b) {
 }
 
 // ---- performance model (Sec. 5) on the plan's schedule ----
-// Defaults fitted to the measured grid of paper_1704_03092_amd/sweep.py on one MI355X (RMS error of log time 5 %).
+// Defaults fitted to the measured grid of paper_1704_03092_amd/sweep.py on one MI355X (RMS error of log time 6 %).
 extern const tc_model_params_t kDefaultModel = {
     78.6e12,               // published FP64 matrix peak
     {0.90, 0.80, 0.66},    // fused kernel with 1 / 2 / 4-term operand sums
