@@ -11,8 +11,8 @@
  * with the labels of each tensor listed in any order and every dimension carrying its own stride
  * (Sec. 2.3 "General stride layouts").  The library views the contraction as a matrix product over the
  * bundles, addressed through scatter vectors and block scatter vectors (Sec. 2.3 "Block Scatter Matrix
- * View"), splits that matrix view 2x2 (4x4) for Strassen (Sec. 3, eq. (straprim1); the seven products of
- * Sec. 2.2, eq. (allops)), forms the operand sums while staging tiles into LDS (Sec. 4.1) and adds each
+ * View"), splits that matrix view 2x2 (4x4) for Strassen (Sec. 3, the display of the general
+ * primitive; the seven products M_0..M_6 displayed in Sec. 2.2), forms the operand sums while staging tiles into LDS (Sec. 4.1) and adds each
  * product to several blocks of C from registers (Sec. 4.2).  Variants (Sec. 4.1): ABC keeps no temporary,
  * AB stores each product M densely and then accumulates it into C, Naive also stores the operand sums.
  *
@@ -57,7 +57,10 @@ typedef enum {
     TC_ERR_NDIM = -2,      /* ndim < 0 or > TC_MAX_NDIM */
     TC_ERR_LABEL = -3,     /* label repeated inside a tensor, or not in exactly two tensors */
     TC_ERR_LENGTH = -4,    /* negative length, or one label with two different lengths */
-    TC_ERR_STRIDE = -5,    /* negative stride, zero stride on a dimension longer than 1, or C's elements may overlap */
+    TC_ERR_STRIDE = -5,    /* negative stride, zero stride on a dimension longer than 1, or two elements of C share a
+                            * location.  (Sec. 2.3 "General stride layouts" allows any strides in the naturals.  Layouts
+                            * of C whose dimensions nest, with or without padding, are always accepted; layouts that
+                            * interleave dimensions are checked exactly up to 2^22 elements and refused beyond that.) */
     TC_ERR_LEVEL = -6,     /* level not in {0, 1, 2} and not TC_LEVEL_AUTO */
     TC_ERR_VARIANT = -7,   /* unknown variant */
     TC_ERR_WORKSPACE = -8, /* workspace is NULL although tc_plan_workspace_bytes() > 0 */
@@ -168,36 +171,30 @@ typedef struct {
 
 /* Build a plan: classify labels into bundles (Sec. 2.3), choose the order inside each bundle, compute the
  * scatter and block scatter vectors on the device (planner kernel, enqueued on `stream`, a hipStream_t or NULL),
- * and schedule the 1 / 7 / 49 products of level 0 / 1 / 2 (Sec. 2.2 eq. (allops), Sec. 3 eq. (straprim1)).
+ * and schedule the 1 / 7 / 49 products of level 0 / 1 / 2 (Sec. 2.2, the display of the seven products M_0..M_6; Sec. 3, the display of the general primitive).
  * On failure *plan_out is set to NULL.  Synchronises `stream` before returning. */
 int tc_plan(tc_plan_t **plan_out, const tc_tensor_desc_t *A, const tc_tensor_desc_t *B, const tc_tensor_desc_t *C,
             int level, int variant, void *stream);
 int tc_plan_ex(tc_plan_t **plan_out, const tc_tensor_desc_t *A, const tc_tensor_desc_t *B, const tc_tensor_desc_t *C,
                int level, int variant, const tc_options_t *opts, void *stream);
 
-/* Bytes of device workspace tc_contract() needs: the temporaries of the variant (none for ABC and for level 0 without
- * split_k; AB: one block of C; Naive: plus one block of A and of B; HYBRID: one first-level block of A and of B) plus,
- * where a launch splits its tail (tc_options_t.tail_split), 128 KiB per chunk of a tail tile (at most 128 MiB). */
+/* Bytes of device workspace tc_contract() needs.  Sec. 4.1 names the temporaries of each variant: ABC keeps none; AB
+ * stores every product M as a dense matrix before it is accumulated into C (one block of C here: the products run one
+ * after the other); Naive also stores the operand sums (plus one block of A and one of B); HYBRID: one first-level
+ * block of A and of B.  Level 0 needs none unless split_k is used.  Where a launch splits its tail
+ * (tc_options_t.tail_split) add 128 KiB per chunk of a tail tile (at most 128 MiB). */
 size_t tc_plan_workspace_bytes(const tc_plan_t *plan);
 
-/* C := alpha * A * B + beta * C.  A_dev, B_dev, C_dev, workspace_dev are device pointers owned by the caller;
+/* C := alpha * A * B + beta * C: the tensor contraction as defined in Sec. 2.3 ("Tensor Contraction": the sum over the
+ * contracted bundle P for every multi-index of I and J, each element located by the general stride layout), evaluated
+ * on the matrix view by the plan's schedule: per product the general primitive of Sec. 3 (operand sums formed while
+ * tiles are staged, Sec. 4.1; the product added to each of its blocks of C, or stored as M, Sec. 4.2 and 4.1).
+ * A_dev, B_dev, C_dev, workspace_dev are device pointers owned by the caller;
  * C must not overlap A, B or the workspace.  With beta == 0, C is written without being read.
  * A bundle of length zero: empty I or J makes the call a no-op; empty P gives C := beta * C.
  * Work is enqueued on `stream` in order; the call returns without waiting for it. */
 int tc_contract(const tc_plan_t *plan, double alpha, const double *A_dev, const double *B_dev, double beta,
                 double *C_dev, void *workspace_dev, void *stream);
-
-/* Time spent per kind of kernel in one tc_contract() (tc_contract_timed). */
-typedef struct {
-    double fused_ms;        /* the gather + multiply + update kernel (Sec. 4.1, 4.2) */
-    double elementwise_ms;  /* temporaries of the AB / Naive / HYBRID variants, split_k sums, C := beta C */
-    int fused_launches, elementwise_launches;
-} tc_launch_times_t;
-
-/* Same work as tc_contract(), with a HIP event recorded on `stream` after every launch; waits for the last one
- * and reports the time per kind of kernel.  For benchmarks and tools: it creates and destroys events and blocks. */
-int tc_contract_timed(const tc_plan_t *plan, double alpha, const double *A_dev, const double *B_dev, double beta,
-                      double *C_dev, void *workspace_dev, void *stream, tc_launch_times_t *out);
 
 /* Release the plan and its device tables.  NULL is accepted. */
 int tc_destroy(tc_plan_t *plan);
@@ -219,6 +216,23 @@ int tc_plan_launch(const tc_plan_t *plan, int index, tc_launch_info_t *out);
  * 6..11 the block scatter vectors rbs_A, cbs_A, rbs_B, cbs_B, rbs_C, cbs_C (Sec. 2.3).  Returns the number of entries
  * (also when host_out is NULL), or a negative status; copies at most `capacity` entries.  Synchronous. */
 int64_t tc_plan_vector(const tc_plan_t *plan, int which, int64_t *host_out, int64_t capacity);
+
+/* ------------------------------------------------------------------------------------------------------------------
+ * Tools for benchmarks (not for production call paths: the call below creates and destroys HIP events and blocks the
+ * host until the work is done).
+ * ------------------------------------------------------------------------------------------------------------------ */
+
+/* Time spent per kind of kernel in one tc_contract() (tc_contract_timed). */
+typedef struct {
+    double fused_ms;        /* the gather + multiply + update kernel (Sec. 4.1, 4.2) */
+    double elementwise_ms;  /* temporaries of the AB / Naive / HYBRID variants, split_k sums, C := beta C */
+    int fused_launches, elementwise_launches;
+} tc_launch_times_t;
+
+/* Same work as tc_contract(), with a HIP event recorded on `stream` after every launch; waits for the last one
+ * and reports the time per kind of kernel.  For benchmarks and tools: it creates and destroys events and blocks. */
+int tc_contract_timed(const tc_plan_t *plan, double alpha, const double *A_dev, const double *B_dev, double beta,
+                      double *C_dev, void *workspace_dev, void *stream, tc_launch_times_t *out);
 
 #ifdef __cplusplus
 }

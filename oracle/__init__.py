@@ -8,12 +8,12 @@ What is here, and the passage of the paper each part follows:
 
 * ``classify`` / ``scatter_vector`` / ``block_scatter`` / ``matrix_view`` -- index
   bundles I, J, P and the (block) scatter vectors of the matrix view
-  (Sec. 2.3, "Tensor Contraction" and "Block Scatter Matrix View", eq. (scatmat)).
+  (Sec. 2.3, "Tensor Contraction" and "Block Scatter Matrix View", the scatter-matrix location formula).
 * ``contract_literal`` -- the definition of tensor contraction, loop nest in C
   (Sec. 2.3, displayed definition; locations by the general stride layout).
 * ``contract_matrix`` / ``contract_rows`` -- the same sum on the matrix view, tiled
   and OpenMP-parallel in C; used at sizes the literal loop nest cannot reach.
-* ``STRASSEN_U/V/W`` and ``strassen_tables`` -- the seven products of eq. (allops)
+* ``STRASSEN_U/V/W`` and ``strassen_tables`` -- the seven products M_0..M_6 displayed in Sec. 2.2
   as coefficient triples, and their L-level extension read as the Kronecker
   product of the one-level triples (Sec. 3 says only that the scheme "can be
   extended to multiple levels"; the 2-level operation counts 49/95/95/144 in the
@@ -22,7 +22,7 @@ What is here, and the passage of the paper each part follows:
   (the Naive formulation of Sec. 4.1), recursion depth L, classical product at the
   leaves, dynamic peeling for odd sizes (Sec. 3, last paragraph).
 * ``strassen_flat`` -- the same result from the flattened 7^L-product schedule of
-  the general primitive, eq. (straprim1); rows/columns beyond the matrix are
+  the general primitive displayed in Sec. 3; rows/columns beyond the matrix are
   treated as zeros (the zero-padding option of Sec. 3, last paragraph).
 * ``error_metric`` -- ||C - C_ref||_F / (||A||_F ||B||_F).
 * ``freivalds`` -- randomized estimate of ||C - C_ref||_F over the whole of C.
@@ -74,8 +74,6 @@ def _load():
         lib.orc_contract_rows.argtypes = [vp] * 10 + [i64, i64, i64, dbl, dbl, vp]
         lib.orc_matvec.restype = ci
         lib.orc_matvec.argtypes = [vp, vp, vp, i64, i64, vp, vp]
-        lib.orc_matvec_t.restype = ci
-        lib.orc_matvec_t.argtypes = [vp, vp, vp, i64, i64, vp, vp]
         lib.orc_num_threads.restype = ci
         lib.orc_num_threads.argtypes = []
         _lib = lib
@@ -355,13 +353,13 @@ def tensor_norm(T) -> float:
     return fro(T.view())
 
 
-def _matvec(T, rs, cs, x, transpose=False) -> np.ndarray:
+def _matvec(T, rs, cs, x) -> np.ndarray:
+    """y = M x for the matrix view M[i, j] = T[rs[i] + cs[j]]."""
     lib = _load()
     x = np.ascontiguousarray(x, dtype=np.float64)
     m, n = len(rs), len(cs)
-    y = np.zeros(n if transpose else m, dtype=np.float64)
-    f = lib.orc_matvec_t if transpose else lib.orc_matvec
-    f(T.data.ctypes.data, _ptr(rs), _ptr(cs), m, n, x.ctypes.data, y.ctypes.data)
+    y = np.zeros(m, dtype=np.float64)
+    lib.orc_matvec(T.data.ctypes.data, _ptr(rs), _ptr(cs), m, n, x.ctypes.data, y.ctypes.data)
     return y
 
 

@@ -14,10 +14,10 @@
  *   orc_block_scatter     block scatter vector: the common stride of each block of
  *                         blk consecutive scatter entries, 0 if irregular (same section).
  *   orc_contract_rows     the same sum as orc_contract_literal written on the matrix
- *                         view (LOC = rscat_i + cscat_j, eq. (scatmat)); rows may be a
- *                         subset.  Cache-tiled and OpenMP-parallel; every C element is
+ *                         view (LOC = rscat_i + cscat_j, the scatter-matrix location
+ *                         formula of Sec. 2.3); rows may be a subset.  Cache-tiled and OpenMP-parallel; every C element is
  *                         still one thread's running sum over p = 0..k-1 in order.
- *   orc_matvec / _t       y = M x and y = M^T x on a matrix view (for the Freivalds check).
+ *   orc_matvec            y = M x on a matrix view (for the Freivalds check).
  *
  * Pins: tests/test_oracle_*.py (numpy einsum / matmul, brute force, the paper's
  * worked layout example, invariants).
@@ -272,20 +272,6 @@ int orc_matvec(const double *T, const int64_t *rs, const int64_t *cs, int64_t m,
             for (int64_t i = i0; i < i1; ++i)
                 y[i] += col[rs[i]] * xj;
         }
-    }
-    return ORC_OK;
-}
-
-/* y[j] = sum_i T[rs[i] + cs[j]] * x[i] */
-int orc_matvec_t(const double *T, const int64_t *rs, const int64_t *cs, int64_t m, int64_t n, const double *x, double *y)
-{
-#pragma omp parallel for schedule(static)
-    for (int64_t j = 0; j < n; ++j) {
-        double s = 0.0;
-        const double *col = T + cs[j];
-        for (int64_t i = 0; i < m; ++i)
-            s += col[rs[i]] * x[i];
-        y[j] = s;
     }
     return ORC_OK;
 }

@@ -1,4 +1,4 @@
-// The fused kernel of libstrassen_tc (gfx950 / CDNA4 only): the general primitive of Sec. 3, eq. (straprim1),
+// The fused kernel of libstrassen_tc (gfx950 / CDNA4 only): the general primitive displayed at the start of Sec. 3,
 // generalised to <= 4 signed blocks per operand and <= 4 signed destinations.  It gathers blocks of A and B through
 // the scatter vectors, adds them in registers, stages the sums in LDS (Sec. 4.1 "packing"), multiplies tiles on the
 // FP64 matrix cores and adds the tile to every destination block of C from registers (Sec. 4.2).  Level 0 is the same
@@ -19,6 +19,8 @@
 // operands whose consecutive entry pairs are contiguous are gathered two elements per load.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 
 #include "tc_internal.h"
 
@@ -46,24 +48,51 @@ constexpr int OPITCH = 130;  // row pitch of the output tile staged in LDS by th
 // their sum is stored to LDS during k-step s + 1, long after they have landed.  Two register sets fit only for
 // single-term operands (two sets of the (1,2) family already spill); the others keep D = 1 and, while both sums have
 // at most two terms, a k-step deep enough (KT = 32) to cover most of the latency.  Four-term sums: KT = 16.
+// Build-time switches of the schedule (measurement aid; the defaults are the measured optima).
+#ifndef TC_ONE_SET_AHEAD
+#define TC_ONE_SET_AHEAD 0
+#endif
+#ifndef TC_XE
+#define TC_XE 2
+#endif
+#ifndef TC_XL
+#define TC_XL 6
+#endif
+#ifndef TC_PIN1
+#define TC_PIN1 1
+#endif
+
 template <int NTA_, int NTB_, bool EXACT_>
 struct Cfg {
     static constexpr int NTA = NTA_, NTB = NTB_;
     static constexpr bool EXACT = EXACT_;
-    static constexpr int D = (EXACT && NTA == 1 && NTB == 1) ? 2 : 1;
     static constexpr int KT = (EXACT && NTA <= 2 && NTB <= 2) ? 32 : 16;
+    static constexpr bool SINGLE = EXACT && NTA == 1 && NTB == 1;
+    // D = how many k-steps ahead of the multiplying step a gather is issued; SETS = register sets for gathers in
+    // flight.  Single-term operands: D = 2 with two sets (issued during step s, stored to LDS during step s + 1).
+    // Sums of several terms have registers for one set only.  Their set is stored to LDS in the middle of a step and
+    // re-issued at once for the step after the next (D = 2, SETS = 1): the gathered data has one whole k-step to
+    // arrive and the store to LDS happens while the SIMD's other wave multiplies, where issuing at the start of a
+    // step and storing at its end (D = 1) leaves both waves of a SIMD waiting and storing at the same time.
+    static constexpr int D = SINGLE ? 2 : ((TC_ONE_SET_AHEAD && EXACT) ? 2 : 1);
+    static constexpr int SETS = SINGLE ? 2 : 1;
     static constexpr int NE = TM * KT / NTHREADS;  // elements of each operand tile (and term) a thread gathers per k-step
     static constexpr int NQ = KT / 4;              // matrix-core instruction groups per k-step
     static constexpr int TILE = KT * PITCH;
     // Schedule inside a k-step, in instruction groups completed (measured optima).  The two waves of a SIMD do their
     // loads and LDS stores at different times so that one of them always has MFMAs to issue: the first wave issues
     // its gather before group 0, its partner after ISSUE_LATE groups, when the first burst of loads has drained from
-    // the CU's address pipeline.  With D = 2 the second wave stores right before it issues and the first wave
-    // three quarters into the step; with D = 1 both store after the last group.
-    static constexpr int ISSUE_LATE = (D == 2) ? 5 : (NQ == 8 ? 4 : 3);
-    static constexpr int STAGE_EARLY = (D == 2) ? 6 : NQ;
-    static constexpr int STAGE_LATE = (D == 2) ? 4 : NQ;
-    static_assert(D == 1 || NQ == 8, "the D = 2 schedule is written for 8 groups");
+    // the CU's address pipeline.  With two sets the second wave stores right before it issues and the first wave
+    // three quarters into the step; with D = 1 both store after the last group.  One set, two steps ahead: the
+    // first wave stores and re-issues after X_EARLY groups, its partner after X_LATE.
+    static constexpr int ISSUE_LATE = (SETS == 2) ? 5 : (NQ == 8 ? 4 : 3);
+    static constexpr int STAGE_EARLY = (SETS == 2) ? 6 : NQ;
+    static constexpr int STAGE_LATE = (SETS == 2) ? 4 : NQ;
+    static constexpr int X_EARLY = (NQ == 8) ? TC_XE : TC_XE / 2;
+    static constexpr int X_LATE = (NQ == 8) ? TC_XL : TC_XL / 2;
+    static constexpr bool PIN = SETS == 1 && (D == 1 || TC_PIN1);
+    static_assert(SETS == 1 || NQ == 8, "the two-set schedule is written for 8 groups");
+    static_assert(X_EARLY >= 0 && X_LATE <= NQ, "store points lie inside the step");
 };
 
 // Scatter vectors are reached through pointers stored in the product descriptors; telling the compiler that they
@@ -300,7 +329,7 @@ __device__ __forceinline__ int64_t min64(int64_t a, int64_t b) { return a < b ? 
 
 template <int AMODE, int BMODE, class CF, bool VA, bool VB>
 struct State {
-    static constexpr int KT = CF::KT, NE = CF::NE, NQ = CF::NQ, TILE = CF::TILE, D = CF::D, NTA = CF::NTA, NTB = CF::NTB;
+    static constexpr int KT = CF::KT, NE = CF::NE, NQ = CF::NQ, TILE = CF::TILE, D = CF::D, SETS = CF::SETS, NTA = CF::NTA, NTB = CF::NTB;
     static_assert(NTA * NE <= 32 && NTB * NE <= 32, "padding masks are 32 bits");
     Smem<CF>* S;
     const Product* P;
@@ -320,9 +349,9 @@ struct State {
     const double* fa;
     const double* fb[4];
     double acc[4][2][4];
-    double la[D][NTA][NE], lb[D][NTB][NE];  // register sets of the gathers in flight
-    unsigned pa[D], pb[D];
-    bool issued_fast[D];       // the loads of a set were issued without padding checks
+    double la[SETS][NTA][NE], lb[SETS][NTB][NE];  // register sets of the gathers in flight
+    unsigned pa[SETS], pb[SETS];
+    bool issued_fast[SETS];    // the loads of a set were issued without padding checks
     Affine<NTA> afa;           // table-free gather (valid when the product qualifies)
     Affine<NTB> afb;
 
@@ -331,7 +360,7 @@ struct State {
     template <int SET, int SLOT, bool FAST, bool AFF = false>
     __device__ __forceinline__ void issue(int target) {
         if constexpr (FAST && AFF) {
-            constexpr bool BUF = D == 1 && NTA <= 2 && NTB <= 2;  // (four descriptors per operand would spill scalar registers)
+            constexpr bool BUF = SETS == 1 && NTA <= 2 && NTB <= 2;  // (four descriptors per operand would spill scalar registers)
             issue_affine<AMODE, NTA, KT, BUF>(la[SET], afa, target);
             issue_affine<BMODE, NTB, KT, BUF>(lb[SET], afb, target);
             return;
@@ -386,40 +415,61 @@ struct State {
                     acc[x][y][s] = __builtin_amdgcn_mfma_f64_4x4x4f64(af[x], bf[y * 4 + s], acc[x][y][s], 0, 0, 0);
     }
 
-    // With one k-step in flight the compiler must not move the waits for gathered data up into the MFMA groups;
-    // with two in flight the data has long arrived and free scheduling measured faster.
+    // With one register set the compiler must not move the waits for gathered data up into the MFMA groups;
+    // with two sets the data has long arrived and free scheduling measured faster.
     __device__ static __forceinline__ void pin() {
-        if constexpr (D == 1) __builtin_amdgcn_sched_barrier(0);
+        if constexpr (CF::PIN) __builtin_amdgcn_sched_barrier(0);
     }
 
     // What a wave does besides MFMAs once DONE instruction groups of k-step `step` (LDS buffer CUR) are complete.
-    // D = 2: the loads of step + 2 go to register set CUR (its previous contents, k-step `step`, were stored one
-    //        step ago), and set CUR ^ 1 (k-step step + 1, issued one step ago) is stored to LDS buffer CUR ^ 1.
+    // D = 2, two sets: the loads of step + 2 go to register set CUR (its previous contents, k-step `step`, were
+    //        stored one step ago), and set CUR ^ 1 (k-step step + 1, issued one step ago) is stored to LDS buffer CUR ^ 1.
+    // D = 2, one set: the set (k-step step + 1, issued one step ago) is stored to LDS buffer CUR ^ 1 and the loads of
+    //        step + 2 are issued into it right away.
     // D = 1: the loads of step + 1 are issued and, after the last group, stored.
     // ROLE: 0 = first wave of the SIMD, 1 = second, 2 = decided at run time (member `early`).
     template <int CUR, int DONE, int ROLE, bool FAST, bool UNIT, bool AFF>
     __device__ __forceinline__ void between_groups(int step) {
         constexpr int NXT = CUR ^ 1;
-        constexpr int ISET = (D == 2) ? CUR : 0, SSET = (D == 2) ? NXT : 0, ISLOT = (D == 2) ? CUR : NXT;
-        if constexpr (ROLE != 1 && DONE == CF::STAGE_EARLY) {
-            pin();
-            if (ROLE == 0 || early) stage<SSET, NXT, FAST, UNIT>();
-            pin();
-        }
-        if constexpr (ROLE != 0 && DONE == CF::STAGE_LATE) {
-            pin();
-            if (ROLE == 1 || !early) stage<SSET, NXT, FAST, UNIT>();
-            pin();
-        }
-        if constexpr (ROLE != 1 && DONE == 0) {
-            pin();
-            if (ROLE == 0 || early) issue<ISET, ISLOT, FAST, AFF>(step + D);
-            pin();
-        }
-        if constexpr (ROLE != 0 && DONE == CF::ISSUE_LATE) {
-            pin();
-            if (ROLE == 1 || !early) issue<ISET, ISLOT, FAST, AFF>(step + D);
-            pin();
+        if constexpr (D == 2 && SETS == 1) {
+            if constexpr (ROLE != 1 && DONE == CF::X_EARLY) {
+                pin();
+                if (ROLE == 0 || early) {
+                    stage<0, NXT, FAST, UNIT>();
+                    issue<0, CUR, FAST, AFF>(step + 2);
+                }
+                pin();
+            }
+            if constexpr (ROLE != 0 && DONE == CF::X_LATE) {
+                pin();
+                if (ROLE == 1 || !early) {
+                    stage<0, NXT, FAST, UNIT>();
+                    issue<0, CUR, FAST, AFF>(step + 2);
+                }
+                pin();
+            }
+        } else {
+            constexpr int ISET = (D == 2) ? CUR : 0, SSET = (D == 2) ? NXT : 0, ISLOT = (D == 2) ? CUR : NXT;
+            if constexpr (ROLE != 1 && DONE == CF::STAGE_EARLY) {
+                pin();
+                if (ROLE == 0 || early) stage<SSET, NXT, FAST, UNIT>();
+                pin();
+            }
+            if constexpr (ROLE != 0 && DONE == CF::STAGE_LATE) {
+                pin();
+                if (ROLE == 1 || !early) stage<SSET, NXT, FAST, UNIT>();
+                pin();
+            }
+            if constexpr (ROLE != 1 && DONE == 0) {
+                pin();
+                if (ROLE == 0 || early) issue<ISET, ISLOT, FAST, AFF>(step + D);
+                pin();
+            }
+            if constexpr (ROLE != 0 && DONE == CF::ISSUE_LATE) {
+                pin();
+                if (ROLE == 1 || !early) issue<ISET, ISLOT, FAST, AFF>(step + D);
+                pin();
+            }
         }
     }
 
@@ -431,7 +481,7 @@ struct State {
             if constexpr (Q + 1 < NQ) read_frags<CUR, Q + 1>(af[(Q + 1) & 1], bf[(Q + 1) & 1]);
             // D = 2: a wave in the first half of its k-step outranks its SIMD partner in the second half, which
             // keeps the two from drifting far apart (measured +1.5 %; with D = 1 it costs 2 %)
-            if constexpr (D == 2 && (Q * 2) % NQ == 0) __builtin_amdgcn_s_setprio(1 - (Q * 2) / NQ);
+            if constexpr (SETS == 2 && (Q * 2) % NQ == 0) __builtin_amdgcn_s_setprio(1 - (Q * 2) / NQ);
             multiply(af[Q & 1], bf[Q & 1]);
             between_groups<CUR, Q + 1, ROLE, FAST, UNIT, AFF>(step);
             groups<CUR, Q + 1, ROLE, FAST, UNIT, AFF>(af, bf, step);
@@ -524,7 +574,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     Smem<CF>& S = *reinterpret_cast<Smem<CF>*>(smem_raw);
     const int tid = threadIdx.x;
     typedef State<AMODE, BMODE, CF, VA, VB> St;
-    constexpr int KT = CF::KT, NTA = CF::NTA, NTB = CF::NTB, D = CF::D;
+    constexpr int KT = CF::KT, NTA = CF::NTA, NTB = CF::NTB, D = CF::D, SETS = CF::SETS;
 
     // ---- which tile ----
     const int bid = blockIdx.x;
@@ -577,7 +627,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     st.safeA = Abase;
     st.safeB = Bbase;
 #pragma unroll
-    for (int d = 0; d < D; ++d) {
+    for (int d = 0; d < SETS; ++d) {
         st.pa[d] = st.pb[d] = 0;
         st.issued_fast[d] = false;
     }
@@ -640,14 +690,14 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
             setup_affine<BMODE, NTB, KT>(st.afb, Bbase + kbeg * P.B.rs_stride, P.B.cs_stride, P.B.rs_stride, P.B.coff, P.B.roff, j0, tid & 63, wu, st.nk - 1);
         }
     }
-    // Such a tile needs no table for its gathers: the first D k-steps are issued here, before the tables are
-    // fetched, so that the two latencies overlap.
+    // Such a tile needs no table for its gathers: its first k-steps (one per register set) are issued here, before
+    // the tables are fetched, so that the two latencies overlap.
     if constexpr (VA && VB && CF::EXACT) {
         if (affine) {
             st.template issue<0, 0, true, true>(0);
-            if constexpr (D == 2) st.template issue<1, 1, true, true>(1);
+            if constexpr (SETS == 2) st.template issue<1, 1, true, true>(1);
 #pragma unroll
-            for (int d = 0; d < D; ++d) st.issued_fast[d] = true;
+            for (int d = 0; d < SETS; ++d) st.issued_fast[d] = true;
         }
     }
     for (int e = tid; e < NTA * TM; e += NTHREADS) {
@@ -760,15 +810,27 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         }
     }
 
-    // ---- prologue: k-step 0 into LDS buffer 0; with two steps in flight also the gather of k-step 1 and the
-    //      scatter entries of k-step 2 ----
+    // ---- prologue: k-step 0 into LDS buffer 0; with D = 2 also the gather of k-step 1 (into the second register
+    //      set, or into the only one once k-step 0 has left it) and the scatter entries of k-step 2 ----
     if (!affine) st.template issue<0, 0, false>(0);
-    if constexpr (D == 2) {
+    if constexpr (D == 2 && SETS == 2) {
         if (!affine) st.template issue<1, 1, false>(1);
         __syncthreads();  // table slot 0 has been read by every thread
         st.ent_dst[0] = (2 * KT < st.ent_limit || st.all_fast) ? 8 * st.ent_ptr[2 * KT < st.ent_limit ? 2 * KT : 0] : kSentinel;
     }
     st.template stage<0, 0, false, false>();
+    if constexpr (D == 2 && SETS == 1) {
+        bool done = false;
+        if constexpr (VA && VB && CF::EXACT) {
+            if (affine) {
+                st.template issue<0, 1, true, true>(1);
+                done = true;
+            }
+        }
+        if (!done) st.template issue<0, 1, false>(1);
+        __syncthreads();  // table slot 0 has been read by every thread
+        st.ent_dst[0] = (2 * KT < st.ent_limit || st.all_fast) ? 8 * st.ent_ptr[2 * KT < st.ent_limit ? 2 * KT : 0] : kSentinel;
+    }
 #pragma unroll
     for (int x = 0; x < 4; ++x)
 #pragma unroll
@@ -797,7 +859,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
             else
                 st.template run_fast<1, false>(nfast, affine);
         }
-        if constexpr (D == 2) st.issued_fast[1] = true;  // the gather of k-step nfast + 1 is in flight
+        if constexpr (D == 2) st.issued_fast[SETS - 1] = true;  // the gather of k-step nfast + 1 is in flight (issued unchecked)
     }
     st.run_checked(nfast);
 
@@ -875,14 +937,20 @@ struct TailSplit {
 template <int AMODE, int BMODE, class CF, bool VA, bool VB>
 int launch_one(const Product* prods, int first, int count, int tiles_m, int tiles_n, const double* A, const double* B, double* C,
                double* W, double alpha, double beta, int c_mode, const TailSplit& tail, hipStream_t stream) {
-    static bool configured = false;
     static_assert(sizeof(Smem<CF>) <= 160 * 1024, "LDS budget of one CU");
     const size_t smem = sizeof(Smem<CF>);
     auto kern = fused_kernel<AMODE, BMODE, CF, VA, VB>;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    // The kernel's dynamic LDS size must be raised once per device and instantiation; callers may launch from several
+    // host threads and on several devices, so the record of what has been done is an atomic bit per device.
+    static std::atomic<uint64_t> configured{0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    const uint64_t bit = (dev >= 0 && dev < 64) ? (uint64_t)1 << dev : 0;
+    if (!bit || !(configured.load(std::memory_order_acquire) & bit)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return (int)e;
-        configured = true;
+        configured.fetch_or(bit, std::memory_order_release);
     }
     const int64_t total = (int64_t)count * tiles_m * tiles_n;
     if (total <= 0 || tail.tiles < 0 || tail.tiles > total) return (int)hipErrorInvalidValue;

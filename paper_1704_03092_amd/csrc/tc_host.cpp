@@ -16,7 +16,7 @@ using tc::BundleDesc;
 using tc::Operand;
 using tc::Product;
 
-// The seven products of one-level Strassen (Sec. 2.2, eq. (allops)); quadrants numbered X0 X1 / X2 X3.
+// The seven products of one-level Strassen (Sec. 2.2, the display of M_0..M_6); quadrants numbered X0 X1 / X2 X3.
 // Row r:  M_r = (sum_q kU[r][q] A_q) (sum_q kV[r][q] B_q);   C_q += kW[r][q] M_r.
 const int kU[7][4] = {{1, 0, 0, 1}, {0, 0, 1, 1}, {1, 0, 0, 0}, {0, 0, 0, 1}, {1, 1, 0, 0}, {-1, 0, 1, 0}, {0, 1, 0, -1}};
 const int kV[7][4] = {{1, 0, 0, 1}, {1, 0, 0, 0}, {0, 1, 0, -1}, {-1, 0, 1, 0}, {0, 0, 0, 1}, {1, 1, 0, 0}, {0, 0, 1, 1}};
@@ -94,19 +94,39 @@ int find(const tc_tensor_desc_t* T, char c) {
     return -1;
 }
 
-// Sufficient condition for the elements of C to be pairwise distinct: sorted by stride, every dimension
-// steps over the whole extent of the ones before it.
+// Are the elements of T pairwise distinct (no two multi-indices share a location)?  First a sufficient condition
+// that costs nothing: sorted by stride, every dimension steps over the whole extent of the ones before it (all
+// layouts that nest, with or without padding).  Layouts that interleave dimensions can still be free of overlap
+// (lengths (2, 3) with strides (3, 2): locations 0, 3, 2, 5, 4, 7); those are decided exactly by listing and sorting
+// the locations, for tensors of up to kExactDistinctLimit elements.  Larger interleaved layouts are refused.
+constexpr int64_t kExactDistinctLimit = (int64_t)1 << 22;
+
 bool distinct_elements(const tc_tensor_desc_t* T) {
     std::vector<std::pair<int64_t, int64_t>> d;  // (stride, len)
     for (int i = 0; i < T->ndim; ++i)
         if (T->len[i] > 1) d.push_back({T->stride[i], T->len[i]});
     std::sort(d.begin(), d.end());
     int64_t extent = 1;  // 1 + largest offset so far
+    bool nested = true;
     for (auto& p : d) {
-        if (p.first < extent) return false;
+        if (p.first < extent) nested = false;
         extent += (p.second - 1) * p.first;
     }
-    return true;
+    if (nested) return true;
+    int64_t total = 1;
+    for (auto& p : d) {
+        if (total > kExactDistinctLimit / p.second) return false;
+        total *= p.second;
+    }
+    std::vector<int64_t> loc(1, 0);
+    loc.reserve((size_t)total);
+    for (auto& p : d) {
+        const size_t have = loc.size();
+        for (int64_t i = 1; i < p.second; ++i)
+            for (size_t e = 0; e < have; ++e) loc.push_back(loc[e] + i * p.first);
+    }
+    std::sort(loc.begin(), loc.end());
+    return std::adjacent_find(loc.begin(), loc.end()) == loc.end();
 }
 
 int64_t min_stride(const std::vector<Dim>& bundle, int which) {

@@ -68,6 +68,27 @@ def test_error_paths():
     assert "host-only" in tc.tc_strerror(-10)
 
 
+def test_interleaved_layouts_of_C_are_decided_exactly():
+    """C's elements must be pairwise distinct.  Nested layouts pass a cheap sufficient test; interleaved ones are listed
+    and sorted: lengths (2, 3) with strides (3, 2) give the locations 0, 3, 2, 5, 4, 7 (legal), strides (2, 1) give
+    0, 2, 1, 3, 2, 4 (location 2 twice)."""
+    A, B = ("ik", (2, 5), (1, 2)), ("kj", (5, 3), (1, 5))
+    tc.tc_destroy(_plan(A, B, ("ij", (2, 3), (3, 2))))
+    with pytest.raises(tc.TcError) as e:
+        _plan(A, B, ("ij", (2, 3), (2, 1)))
+    assert e.value.status == -5
+    # three dimensions, interleaved and legal: offsets i + 2 j with j < 2 cover 0..3, the last dimension steps over them
+    tc.tc_destroy(_plan(("ik", (2, 5), (1, 2)), ("kjl", (5, 2, 3), (1, 5, 10)), ("ijl", (2, 2, 3), (1, 2, 4))))
+    # an interleaved layout too large to list is refused, a nested one of the same size is not
+    big = 1 << 23  # rows at odd locations 3 + 2 j, columns at even ones: legal, but 2^24 elements are not listed
+    A, B = ("ik", (2, 2), (1, 2)), ("kj", (2, big), (1, 2))
+    tc.tc_destroy(_plan(A, B, ("ij", (2, big), (1, 2))))
+    tc.tc_destroy(_plan(A, ("kj", (2, 1 << 20), (1, 2)), ("ij", (2, 1 << 20), (3, 2))))
+    with pytest.raises(tc.TcError) as e:
+        _plan(A, B, ("ij", (2, big), (3, 2)))
+    assert e.value.status == -5
+
+
 def test_plan_info_bundles_and_modes():
     # the paper's example contraction C_abc += A_dca * B_db, generalized column-major
     L = dict(a=4, b=8, c=2, d=8)

@@ -58,7 +58,7 @@ def test_paper_layout_example():
 
 
 def test_scatter_vector_is_the_stride_layout():
-    """rscat_i + cscat_j equals the general-stride location of the element (eq. (scatmat) vs. LOC_gsten)."""
+    """rscat_i + cscat_j equals the general-stride location of the element (the scatter-matrix location formula against the general-stride one, Sec. 2.3)."""
     rng = random.Random(5)
     for _ in range(30):
         nd = rng.randint(1, 5)
@@ -178,7 +178,7 @@ def test_tiled_matrix_form_equals_literal_bit_for_bit():
         oracle.contract_literal(A, B, C, 1.25, 0.75)
         oracle.contract_matrix(A, B, C2, 1.25, 0.75, orders=(I, J, P))
         assert np.array_equal(C.data, C2.data)
-    # a case larger than the tile sizes in every direction (tiles: 8 x 8 micro, 64 cols, 256 rows, 1024 deep)
+    # a case larger than the tile sizes in every direction (tiles: 4 x 8 register tile, 64 columns, 256 rows, 1024 deep)
     L = {"i": 300, "j": 70, "k": 1100}
     A = workloads.make_tensor("ik", L, 9, 0)
     B = workloads.make_tensor("kj", L, 9, 1)

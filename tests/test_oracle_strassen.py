@@ -68,7 +68,7 @@ def test_two_level_tables_satisfy_brent_equations():
 
 
 def test_seven_products_written_out():
-    """eq. (allops) typed out product by product on random quadrants reproduces the blocked product."""
+    """The seven products of Sec. 2.2 typed out product by product on random quadrants reproduces the blocked product."""
     rng = np.random.default_rng(0)
     A = [rng.integers(-3, 4, (3, 4)).astype(float) for _ in range(4)]
     B = [rng.integers(-3, 4, (4, 5)).astype(float) for _ in range(4)]
