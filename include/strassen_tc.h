@@ -66,7 +66,8 @@ typedef enum {
     TC_ERR_WORKSPACE = -8, /* workspace is NULL although tc_plan_workspace_bytes() > 0 */
     TC_ERR_HIP = -9,       /* a HIP runtime call failed (no device, out of memory, launch failure) */
     TC_ERR_STATE = -10,    /* plan was created host-only and cannot run, or option value out of range */
-    TC_ERR_RANGE = -11     /* output buffer too small / index out of range in an inspection call */
+    TC_ERR_RANGE = -11,    /* output buffer too small / index out of range in an inspection call */
+    TC_ERR_CAPACITY = -12  /* tc_contract_static: the plan's workspace exceeds TC_STATIC_WORKSPACE_BYTES */
 } tc_status_t;
 
 #define TC_MAX_NDIM 16
@@ -195,6 +196,19 @@ size_t tc_plan_workspace_bytes(const tc_plan_t *plan);
  * Work is enqueued on `stream` in order; the call returns without waiting for it. */
 int tc_contract(const tc_plan_t *plan, double alpha, const double *A_dev, const double *B_dev, double beta,
                 double *C_dev, void *workspace_dev, void *stream);
+
+/* tc_contract() for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The workspace is a buffer of TC_STATIC_WORKSPACE_BYTES that
+ * the library holds in the memory of every GPU it runs on, from the time its code is loaded there until the process
+ * ends; the call itself allocates and frees nothing.  Same kernels, same launch order and same results (bit for bit)
+ * as tc_contract() with a workspace of tc_plan_workspace_bytes().  Returns TC_ERR_CAPACITY, and enqueues nothing, if
+ * the plan needs more than TC_STATIC_WORKSPACE_BYTES (then use tc_contract()).  All calls on one GPU share that
+ * GPU's buffer: two calls that overlap in time on one GPU (different streams or threads) race; calls in stream order
+ * are safe.  The buffer keeps the previous call's contents, which is harmless: every kernel writes the part of the
+ * workspace it later reads.  The plan must have been created with the same GPU current. */
+#define TC_STATIC_WORKSPACE_BYTES ((size_t)32 << 20)
+int tc_contract_static(const tc_plan_t *plan, double alpha, const double *A_dev, const double *B_dev, double beta,
+                       double *C_dev, void *stream);
 
 /* Release the plan and its device tables.  NULL is accepted. */
 int tc_destroy(tc_plan_t *plan);

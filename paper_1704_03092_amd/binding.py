@@ -131,6 +131,8 @@ def load_library():
         lib.tc_plan_workspace_bytes.argtypes = [vp]
         lib.tc_contract.restype = ci
         lib.tc_contract.argtypes = [vp, dbl, vp, vp, dbl, vp, vp, vp]
+        lib.tc_contract_static.restype = ci
+        lib.tc_contract_static.argtypes = [vp, dbl, vp, vp, dbl, vp, vp]
         lib.tc_contract_timed.restype = ci
         lib.tc_contract_timed.argtypes = [vp, dbl, vp, vp, dbl, vp, vp, vp, ctypes.POINTER(tc_launch_times_t)]
         lib.tc_destroy.restype = ci
@@ -226,6 +228,16 @@ def tc_contract(plan: Plan, alpha: float, A, B, beta: float, C, workspace=None, 
     rc = load_library().tc_contract(plan.handle, float(alpha), _ptr(A), _ptr(B), float(beta), _ptr(C), _ptr(workspace), _stream(stream))
     if rc != 0:
         raise TcError(rc, "tc_contract")
+
+
+TC_STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def tc_contract_static(plan: Plan, alpha: float, A, B, beta: float, C, stream=None) -> None:
+    """tc_contract with the library's static per-GPU workspace (no allocation; plans up to TC_STATIC_WORKSPACE_BYTES)."""
+    rc = load_library().tc_contract_static(plan.handle, float(alpha), _ptr(A), _ptr(B), float(beta), _ptr(C), _stream(stream))
+    if rc != 0:
+        raise TcError(rc, "tc_contract_static")
 
 
 def tc_contract_timed(plan: Plan, alpha: float, A, B, beta: float, C, workspace=None, stream=None) -> dict:

@@ -8,8 +8,18 @@
 //  launchers         thin host wrappers the planner code in tc_host.cpp calls
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "tc_fused.h"
 #include "tc_internal.h"
+
+// ---------------------------------------------------------------------------------------------------------
+// workspace for callers that cannot allocate (tc_contract_static)
+// ---------------------------------------------------------------------------------------------------------
+// One array per GPU, held from the moment the library's code object is loaded on that GPU until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress: the device address differs per GPU and is
+// looked up once per device, with that device current; kernels, copies and fills only ever see the looked-up pointer.
+static __device__ __align__(256) unsigned char scratch[tc::kStaticWorkspaceBytes];
 
 namespace tc {
 
@@ -160,6 +170,31 @@ __global__ __launch_bounds__(256) void block_scatter_kernel(const BundleDesc* __
 }
 
 }  // namespace
+
+// ---- static workspace: device address per GPU ----
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+int dev_static_workspace(void** ptr) {
+    *ptr = nullptr;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(::scratch));
+        if (e != hipSuccess) return (int)e;
+        if (!p) return (int)hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return 0;
+}
 
 int dev_malloc(void** p, size_t bytes) { return (int)hipMalloc(p, bytes); }
 int dev_free(void* p) { return (int)hipFree(p); }

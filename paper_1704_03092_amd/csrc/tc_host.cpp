@@ -47,6 +47,8 @@ enum { V_RSA = 0, V_CSA, V_RSB, V_CSB, V_RSC, V_CSC, V_RSM, V_CSM, V_RSTA, V_CST
 
 int64_t round_up(int64_t x, int64_t q) { return (x + q - 1) / q * q; }
 
+static_assert(TC_STATIC_WORKSPACE_BYTES == tc::kStaticWorkspaceBytes, "the public limit is the size of the device array");
+
 }  // namespace
 
 struct tc_plan {
@@ -413,6 +415,9 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     }
 
     if (!p->host_only) {
+        // look up this GPU's static workspace now, so that tc_contract_static finds the address ready
+        void* static_ws = nullptr;
+        if (tc::dev_static_workspace(&static_ws)) return TC_ERR_HIP;
         if (tc::dev_malloc((void**)&p->store_dev, sizeof(int64_t) * (size_t)std::max<int64_t>(p->store_entries, 1))) return TC_ERR_HIP;
         if (tc::dev_malloc((void**)&p->bundles_dev, sizeof(BundleDesc) * V_COUNT)) return TC_ERR_HIP;
         if (tc::dev_upload(p->bundles_dev, p->bundles.data(), sizeof(BundleDesc) * V_COUNT, stream)) return TC_ERR_HIP;
@@ -1035,6 +1040,16 @@ int tc_contract(const tc_plan_t* plan, double alpha, const double* A_dev, const 
     return TC_OK;
 }
 
+int tc_contract_static(const tc_plan_t* plan, double alpha, const double* A_dev, const double* B_dev, double beta, double* C_dev,
+                       void* stream) {
+    if (!plan) return TC_ERR_NULL;
+    if (plan->host_only) return TC_ERR_STATE;
+    if (plan->workspace_bytes > tc::kStaticWorkspaceBytes) return TC_ERR_CAPACITY;
+    void* ws = nullptr;
+    if (plan->workspace_bytes > 0 && tc::dev_static_workspace(&ws)) return TC_ERR_HIP;
+    return tc_contract(plan, alpha, A_dev, B_dev, beta, C_dev, ws, stream);
+}
+
 int tc_contract_timed(const tc_plan_t* plan, double alpha, const double* A_dev, const double* B_dev, double beta, double* C_dev,
                       void* workspace_dev, void* stream, tc_launch_times_t* out) {
     if (!plan || !out) return TC_ERR_NULL;
@@ -1089,6 +1104,7 @@ const char* tc_strerror(int status) {
         case TC_ERR_HIP: return "HIP runtime call failed";
         case TC_ERR_STATE: return "plan cannot run (host-only) or option out of range";
         case TC_ERR_RANGE: return "index or capacity out of range";
+        case TC_ERR_CAPACITY: return "the plan needs more workspace than the static buffer holds (TC_STATIC_WORKSPACE_BYTES)";
         default: return "unknown status";
     }
 }

@@ -11,7 +11,7 @@ constexpr int kMaxTerms = 4;  // 2^L blocks per operand at L = 2
 // cannot overflow (-2^62 - 2^62 = -2^63).
 constexpr int64_t kSentinel = INT64_MIN / 2;
 
-// One side of the general primitive M = alpha (X + dY)(V + eW); C += g0 M; D += g1 M  (Sec. 3, eq. (straprim1)),
+// One side of the general primitive M = alpha (X + dY)(V + eW); C += g0 M; D += g1 M  (Sec. 3, first display),
 // extended to up to four signed blocks: a linear combination of blocks of one matrix view.
 struct Operand {
     const int64_t* rs;  // row scatter vector of the whole matrix view (device memory)
@@ -55,7 +55,13 @@ struct FusedConfig {
     int c_mode;           // 0: the destination is contiguous along its rows (free bundle I), 1: along its columns
 };
 
+// Size of the per-GPU array that stands in for the caller's workspace in tc_contract_static
+// (= TC_STATIC_WORKSPACE_BYTES of the public header).
+constexpr size_t kStaticWorkspaceBytes = (size_t)32 << 20;
+
 // ---- device entry points (tc_device.hip); each returns a hipError_t cast to int ----
+// Device address of the current GPU's static workspace array (looked up on the first call per device, then cached).
+int dev_static_workspace(void** ptr);
 int dev_malloc(void** p, size_t bytes);
 int dev_free(void* p);
 int dev_upload(void* dst, const void* src, size_t bytes, void* stream);
