@@ -5,13 +5,15 @@ Workload: the square fp64 GEMM-shaped contraction C[i,j] += A[i,k] * B[k,j] with
 single-GPU case of the second benchmark configuration), seeded uniform[-1,1) data, generalized column-major.
 A step is one pass of the whole hot path on inputs resident in HBM: tc_plan (bundle classification, scatter and
 block scatter vectors, Strassen schedule), tc_contract (operand sums, gather, FP64 matrix-core tiles,
-multi-destination update) and tc_destroy, for the headline mode: one-level Strassen in the HYBRID variant, the
-fastest one-level schedule on this GPU (first-level operand sums stored, the seven products in the same kernel as the
-classical mode, each added to its blocks of C from registers).  The other modes (classical, ABC, AB, Naive, two-level)
+multi-destination update) and tc_destroy, for the headline mode: one-level Strassen in the ABC variant of the paper
+(operand sums formed while tiles are staged, every product added to its blocks of C from registers, no temporaries).
+The other modes (classical, AB, Naive, two-level, and the HYBRID variant that stores the first-level operand sums)
 are timed the same way and listed under config.modes.
 
 Prints ONE JSON line: effective GFLOPS = 2 m n k / t (classical flop count for every mode), the roofline figure of
-the dominant kernel, and the CPU oracle timed on a bounded row panel of the same workload.
+the fused kernel (all launches of the headline mode together, and per kernel family = number of blocks in the operand
+sums of A and B), the same against the measured MFMA-only ceiling, and the CPU oracle timed on a bounded row panel of
+the same workload.
 """
 import argparse
 import json
@@ -24,6 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 FP64_MFMA_PEAK_TFLOPS = 78.6  # MI355X published dense FP64 matrix peak
+HBM_PEAK_TBS = 8.0            # MI355X published HBM3E bandwidth
 
 
 def profiled_traffic(wname, level, variant):
@@ -48,7 +51,7 @@ def main():
     ap.add_argument("--size", type=int, default=16384, help="m = n = k of the square contraction")
     ap.add_argument("--workload", default="", help="another benchmark configuration instead of the square one: cfg1, cfg3, cfg4a, cfg4b, cfg5")
     ap.add_argument("--level", type=int, default=1)
-    ap.add_argument("--variant", default="hybrid")
+    ap.add_argument("--variant", default="abc")
     ap.add_argument("--modes", default="0abc,1abc,1ab,1naive,1hybrid,2abc,2ab,2naive,2hybrid", help="other modes to time (level+variant)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
@@ -122,11 +125,23 @@ def main():
             e1.record(st)
         torch.cuda.synchronize()
         ev_ms = sum(e0.elapsed_time(e1) for e0, e1 in evs) / steps
-        # time of the dominant kernel alone: an event after every launch (tc_contract_timed), averaged over the same steps
-        timed = [tc.tc_contract_timed(plan, cfg.alpha, dA, dB, cfg.beta, dC, ws, st) for _ in range(steps)]
+        # time of every launch alone: an event after every launch (tc_contract_launch_times), averaged over the same steps
+        launches = tc.tc_plan_launches(plan)
+        per = [0.0] * len(launches)
+        for _ in range(steps):
+            for i, ms in enumerate(tc.tc_contract_launch_times(plan, cfg.alpha, dA, dB, cfg.beta, dC, ws, st)):
+                per[i] += ms / steps
         tc.tc_destroy(plan)
-        kern = {"fused_ms": sum(t["fused_ms"] for t in timed) / steps, "elementwise_ms": sum(t["elementwise_ms"] for t in timed) / steps,
-                "fused_launches": timed[0]["fused_launches"], "elementwise_launches": timed[0]["elementwise_launches"]}
+        fused = [(L, ms) for L, ms in zip(launches, per) if L["kind"] == 0]
+        fam = {}
+        for L, ms in fused:
+            f = fam.setdefault(f"{L['terms_a']}x{L['terms_b']}", {"launches": 0, "ms": 0.0, "flops": 0.0})
+            f["launches"] += 1
+            f["ms"] += ms
+            f["flops"] += 2.0 * L["n_products"] * L["rows"] * L["cols"] * L["depth"]
+        kern = {"fused_ms": sum(ms for _, ms in fused), "elementwise_ms": sum(ms for L, ms in zip(launches, per) if L["kind"] != 0),
+                "fused_launches": len(fused), "elementwise_launches": len(launches) - len(fused), "families": fam,
+                "fused_flops": sum(f["flops"] for f in fam.values())}
         return wall_ms, ev_ms, info, kern
 
     if args.calib_copy:  # reads 2^26 doubles and writes 2^26 doubles, nothing else
@@ -160,22 +175,42 @@ def main():
     normA_rows = oracle.fro(A.data[view["rsA"][rows][:, None] + view["csA"][None, :]])
     parity = oracle.error_metric(got, ref, normA_rows, oracle.tensor_norm(B))
 
-    # ---- roofline of the dominant kernel (fused gather + MFMA + update): executed flops / its own launch durations ----
-    executed = flops * (7.0 / 8.0) ** info["level"]
+    # ---- roofline of the fused kernel (gather + operand sums + MFMA + update): executed flops / its own launch durations ----
+    # (block extents are rounded up to multiples of 16, so the executed flops are what the launches really multiply)
+    mfma_only = tc.tc_bench_mfma_peak(0, st)  # what the matrix cores sustain with nothing else going on, same instruction
+    executed = kern["fused_flops"]
     achieved = executed / (kern["fused_ms"] * 1e-3) * 1e-12
-    roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / FP64_MFMA_PEAK_TFLOPS, 4), "traffic": profiled_traffic(wname, info["level"], "abc" if info["level"] == 0 else args.variant),
-                "kernel": "fused_kernel", "launches_per_contract": kern["fused_launches"],
-                "flops_per_launch": executed / kern["fused_launches"], "avg_launch_ms": round(kern["fused_ms"] / kern["fused_launches"], 4),
-                "other_kernels_ms_per_contract": round(kern["elementwise_ms"], 3)}
+    nC = 2.0 if cfg.beta != 0.0 else 1.0
+    compulsory_bytes = 8.0 * (m * k + k * n + nC * m * n)  # every element of A and B read once, C read (beta != 0) and written
+    hbm_tbs = compulsory_bytes / (ev_ms * 1e-3) * 1e-12
+    mfma_frac, hbm_frac = achieved / FP64_MFMA_PEAK_TFLOPS, hbm_tbs / HBM_PEAK_TBS
+    families = {name: {"launches": f["launches"], "avg_launch_ms": round(f["ms"] / f["launches"], 4),
+                       "achieved": round(f["flops"] / (f["ms"] * 1e-3) * 1e-12, 2),
+                       "frac": round(f["flops"] / (f["ms"] * 1e-3) * 1e-12 / FP64_MFMA_PEAK_TFLOPS, 4)} for name, f in sorted(kern["families"].items())}
+    if mfma_frac >= hbm_frac:
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(mfma_frac, 4)}
+    else:
+        roofline = {"bound": "hbm", "achieved": round(hbm_tbs * 1e3, 1), "peak": HBM_PEAK_TBS * 1e3, "unit": "GB/s", "frac": round(hbm_frac, 4)}
+    roofline.update({"traffic": profiled_traffic(wname, info["level"], "abc" if info["level"] == 0 else args.variant),
+                     "kernel": "fused_kernel", "launches_per_contract": kern["fused_launches"],
+                     "flops_per_launch": executed / max(kern["fused_launches"], 1),
+                     "avg_launch_ms": round(kern["fused_ms"] / max(kern["fused_launches"], 1), 4),
+                     "other_kernels_ms_per_contract": round(kern["elementwise_ms"], 3),
+                     "families": families,
+                     "mfma_tflops": round(achieved, 2), "mfma_frac": round(mfma_frac, 4),
+                     "measured_mfma_only_tflops": round(mfma_only, 2), "frac_measured_mfma_peak": round(achieved / mfma_only, 4),
+                     "compulsory_hbm_gbs": round(hbm_tbs * 1e3, 1), "hbm_frac": round(hbm_frac, 4)})
 
     # ---- the other modes ----
     modes = {}
     for md in [x for x in args.modes.split(",") if x]:
         lv, var = int(md[0]), md[1:]
-        w, e, inf, _ = time_mode(lv, var, max(2, args.steps // 2 + 1), 1)
+        w, e, inf, kn = time_mode(lv, var, max(2, args.steps // 2 + 1), 1)
         modes[md] = {"ms_per_step": round(w, 3), "contract_ms": round(e, 3), "eff_gflops": round(flops / w * 1e-6, 1),
-                     "frac_peak_eff": round(flops / w * 1e-9 / FP64_MFMA_PEAK_TFLOPS, 4), "launches": inf["n_launches"]}
+                     "frac_peak_eff": round(flops / w * 1e-9 / FP64_MFMA_PEAK_TFLOPS, 4), "launches": inf["n_launches"],
+                     # executed TFLOP/s of the fused kernel per family (blocks in the sums of A x B) and the other kernels' time
+                     "fused_tflops_by_family": {name: round(f["flops"] / (f["ms"] * 1e-3) * 1e-12, 2) for name, f in sorted(kn["families"].items())},
+                     "elementwise_ms": round(kn["elementwise_ms"], 3)}
 
     # ---- CPU oracle on a bounded row panel of the same workload ----
     cpu = None
@@ -198,7 +233,9 @@ def main():
         "config": {"workload": wtext,
                    "level": info["level"], "variant": args.variant, "step": "tc_plan + tc_contract + tc_destroy",
                    "contract_ms": round(ev_ms, 3), "frac_fp64_mfma_peak_effective": round(value * 1e-3 / FP64_MFMA_PEAK_TFLOPS, 4),
-                   "parity_sampled_rows": float(f"{parity:.3e}"), "parity_rows": int(len(rows)), "modes": modes},
+                   "parity_sampled_rows": float(f"{parity:.3e}"), "parity_rows": int(len(rows)),
+                   "speedup_vs_classical": round(value / modes["0abc"]["eff_gflops"], 4) if "0abc" in modes else None,
+                   "modes": modes},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(out))

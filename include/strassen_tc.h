@@ -153,7 +153,9 @@ typedef struct {
     int max_terms;        /* fused: largest number of blocks in an operand sum of the launch */
     int tail_tiles;       /* fused: tiles cut into chunks (0: none); a split launch is followed by the kernel that adds the chunks */
     int tail_chunks;      /* chunks per tail tile */
-    int reserved[3];
+    int terms_a, terms_b; /* fused: the kernel family of the launch = blocks in the operand sum of A and of B (1, 2 or 4 each;
+                           * 0, 0: the family that counts up to four terms at run time) */
+    int reserved[1];
     int64_t rows, cols;   /* extents of one product (fused) or of the pass (element-wise) */
     int64_t depth;        /* fused: contracted extent of one product */
     int64_t tiles;        /* fused: 128 x 128 tiles of the launch */
@@ -243,10 +245,22 @@ typedef struct {
     int fused_launches, elementwise_launches;
 } tc_launch_times_t;
 
-/* Same work as tc_contract(), with a HIP event recorded on `stream` after every launch; waits for the last one
- * and reports the time per kind of kernel.  For benchmarks and tools: it creates and destroys events and blocks. */
+/* Same work as tc_contract(), with a HIP event recorded on `stream` after every launch; waits for the last one and
+ * writes the duration of launch i (the index tc_plan_launch() uses; a fused launch that splits its tail includes the
+ * kernel that adds the chunks) to ms_out[i], in milliseconds.  Returns the number of launches, or a negative status
+ * (TC_ERR_RANGE if capacity is smaller than the plan's n_launches). */
+int tc_contract_launch_times(const tc_plan_t *plan, double alpha, const double *A_dev, const double *B_dev, double beta,
+                             double *C_dev, void *workspace_dev, void *stream, double *ms_out, int capacity);
+
+/* The same, summed per kind of kernel. */
 int tc_contract_timed(const tc_plan_t *plan, double alpha, const double *A_dev, const double *B_dev, double beta,
                       double *C_dev, void *workspace_dev, void *stream, tc_launch_times_t *out);
+
+/* What the FP64 matrix cores of this GPU sustain when they do nothing else: a kernel of independent MFMA chains, no
+ * memory traffic (instruction 0: v_mfma_f64_4x4x4_4b_f64, the one the library's kernels use; 1: v_mfma_f64_16x16x4_f64).
+ * Writes the achieved TFLOP/s to *tflops_out.  Uses the static workspace of tc_contract_static for its (discarded)
+ * results; blocks until the measurement is done (about 50 ms). */
+int tc_bench_mfma_peak(int instruction, void *stream, double *tflops_out);
 
 #ifdef __cplusplus
 }

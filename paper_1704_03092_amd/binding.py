@@ -75,7 +75,7 @@ class tc_options_t(ctypes.Structure):
 
 class tc_launch_info_t(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int), ("n_products", ctypes.c_int), ("max_terms", ctypes.c_int), ("tail_tiles", ctypes.c_int),
-                ("tail_chunks", ctypes.c_int), ("reserved", ctypes.c_int * 3), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("tail_chunks", ctypes.c_int), ("terms_a", ctypes.c_int), ("terms_b", ctypes.c_int), ("reserved", ctypes.c_int * 1), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
                 ("depth", ctypes.c_int64), ("tiles", ctypes.c_int64), ("tail_kc", ctypes.c_int64)]
 
 
@@ -133,6 +133,10 @@ def load_library():
         lib.tc_contract.argtypes = [vp, dbl, vp, vp, dbl, vp, vp, vp]
         lib.tc_contract_static.restype = ci
         lib.tc_contract_static.argtypes = [vp, dbl, vp, vp, dbl, vp, vp]
+        lib.tc_contract_launch_times.restype = ci
+        lib.tc_contract_launch_times.argtypes = [vp, dbl, vp, vp, dbl, vp, vp, vp, ctypes.POINTER(ctypes.c_double), ci]
+        lib.tc_bench_mfma_peak.restype = ci
+        lib.tc_bench_mfma_peak.argtypes = [ci, vp, ctypes.POINTER(ctypes.c_double)]
         lib.tc_contract_timed.restype = ci
         lib.tc_contract_timed.argtypes = [vp, dbl, vp, vp, dbl, vp, vp, vp, ctypes.POINTER(tc_launch_times_t)]
         lib.tc_destroy.restype = ci
@@ -238,6 +242,26 @@ def tc_contract_static(plan: Plan, alpha: float, A, B, beta: float, C, stream=No
     rc = load_library().tc_contract_static(plan.handle, float(alpha), _ptr(A), _ptr(B), float(beta), _ptr(C), _stream(stream))
     if rc != 0:
         raise TcError(rc, "tc_contract_static")
+
+
+def tc_contract_launch_times(plan: Plan, alpha: float, A, B, beta: float, C, workspace=None, stream=None) -> list:
+    """tc_contract with a HIP event after every launch; blocks; returns the milliseconds of each launch (tc_plan_launches order)."""
+    n = tc_plan_info(plan)["n_launches"]
+    buf = (ctypes.c_double * max(n, 1))()
+    rc = load_library().tc_contract_launch_times(plan.handle, float(alpha), _ptr(A), _ptr(B), float(beta), _ptr(C), _ptr(workspace),
+                                                 _stream(stream), buf, max(n, 1))
+    if rc < 0:
+        raise TcError(rc, "tc_contract_launch_times")
+    return [buf[i] for i in range(rc)]
+
+
+def tc_bench_mfma_peak(instruction: int = 0, stream=None) -> float:
+    """TFLOP/s of an MFMA-only kernel (0: v_mfma_f64_4x4x4_4b_f64, 1: v_mfma_f64_16x16x4_f64)."""
+    out = ctypes.c_double()
+    rc = load_library().tc_bench_mfma_peak(int(instruction), _stream(stream), ctypes.byref(out))
+    if rc != 0:
+        raise TcError(rc, "tc_bench_mfma_peak")
+    return out.value
 
 
 def tc_contract_timed(plan: Plan, alpha: float, A, B, beta: float, C, workspace=None, stream=None) -> dict:

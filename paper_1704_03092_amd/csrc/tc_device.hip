@@ -196,6 +196,76 @@ int dev_static_workspace(void** ptr) {
     return 0;
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// matrix-core ceiling: nothing but dependent-free FP64 MFMA instructions (benchmark tool)
+// ---------------------------------------------------------------------------------------------------------
+namespace {
+typedef double double4_t __attribute__((ext_vector_type(4)));
+constexpr int kPeakBlocks = 2048, kPeakThreads = 512, kPeakChains = 32;
+
+// KIND 0: v_mfma_f64_4x4x4_4b_f64 (512 flops per wave and instruction), KIND 1: v_mfma_f64_16x16x4_f64 (2048).
+// Every wave keeps kPeakChains (KIND 0) or kPeakChains / 4 (KIND 1) independent accumulator chains going.
+template <int KIND>
+__global__ __launch_bounds__(kPeakThreads) void mfma_peak_kernel(double* __restrict__ out, int iters) {
+    const double a = 1.0 + 1e-9 * threadIdx.x, b = 1.0 - 1e-9 * threadIdx.x;
+    double r = 0.0;
+    if constexpr (KIND == 0) {
+        double acc[kPeakChains];
+#pragma unroll
+        for (int j = 0; j < kPeakChains; ++j) acc[j] = j;
+        for (int i = 0; i < iters; ++i) {
+#pragma unroll
+            for (int j = 0; j < kPeakChains; ++j) acc[j] = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, acc[j], 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < kPeakChains; ++j) r += acc[j];
+    } else {
+        double4_t acc[kPeakChains / 4];
+#pragma unroll
+        for (int j = 0; j < kPeakChains / 4; ++j) acc[j] = double4_t{(double)j, 0.0, 0.0, 0.0};
+        for (int i = 0; i < iters; ++i) {
+#pragma unroll
+            for (int j = 0; j < kPeakChains / 4; ++j) acc[j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[j], 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < kPeakChains / 4; ++j) r += acc[j].x + acc[j].y + acc[j].z + acc[j].w;
+    }
+    out[(size_t)blockIdx.x * kPeakThreads + threadIdx.x] = r;
+}
+}  // namespace
+
+int bench_mfma_peak(int kind, int iters, void* stream, double* tflops_out) {
+    static_assert((size_t)kPeakBlocks * kPeakThreads * sizeof(double) <= kStaticWorkspaceBytes, "the results fit the static workspace");
+    void* out = nullptr;
+    int rc = dev_static_workspace(&out);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return (int)hipErrorUnknown;
+    float ms = 0;
+    for (int pass = 0; pass < 2; ++pass) {  // the first pass warms up
+        hipEventRecord(e0, st);
+        if (kind == 0)
+            hipLaunchKernelGGL(mfma_peak_kernel<0>, dim3(kPeakBlocks), dim3(kPeakThreads), 0, st, (double*)out, iters);
+        else
+            hipLaunchKernelGGL(mfma_peak_kernel<1>, dim3(kPeakBlocks), dim3(kPeakThreads), 0, st, (double*)out, iters);
+        hipEventRecord(e1, st);
+        hipError_t e = hipEventSynchronize(e1);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e != hipSuccess) {
+            hipEventDestroy(e0);
+            hipEventDestroy(e1);
+            return (int)e;
+        }
+    }
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    const double per_instr = kind == 0 ? 512.0 : 2048.0, chains = kind == 0 ? kPeakChains : kPeakChains / 4;
+    const double flops = per_instr * chains * (double)iters * (kPeakThreads / 64) * (double)kPeakBlocks;
+    *tflops_out = flops / (ms * 1e-3) * 1e-12;
+    return 0;
+}
+
 int dev_malloc(void** p, size_t bytes) { return (int)hipMalloc(p, bytes); }
 int dev_free(void* p) { return (int)hipFree(p); }
 int dev_upload(void* dst, const void* src, size_t bytes, void* stream) {

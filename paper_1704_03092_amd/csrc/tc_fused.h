@@ -43,23 +43,17 @@ constexpr int OPITCH = 130;  // row pitch of the output tile staged in LDS by th
 // One kernel family per (NTA, NTB) = terms of the operand sums of A and B.
 //   EXACT : every product of the launch has exactly NTA and NTB terms; the term loops are compile-time.
 //   !EXACT: up to NTA / NTB terms, counted at run time (a four-term sum that lost a block to the zero padding).
-// D = k-steps of gather in flight.  Measured under load, a gathered element takes 7000-9000 cycles to arrive, about
-// the matrix-core work of one 32-deep k-step, so with D = 2 the loads of k-step s + 2 are issued during k-step s and
-// their sum is stored to LDS during k-step s + 1, long after they have landed.  Two register sets fit only for
-// single-term operands (two sets of the (1,2) family already spill); the others keep D = 1 and, while both sums have
-// at most two terms, a k-step deep enough (KT = 32) to cover most of the latency.  Four-term sums: KT = 16.
-// Build-time switches of the schedule (measurement aid; the defaults are the measured optima).
-#ifndef TC_ONE_SET_AHEAD
-#define TC_ONE_SET_AHEAD 0
+// The k-step is 32 deep while both sums have at most two terms, 16 deep for four-term sums (registers).  How far
+// ahead the gathers run and how they are turned over is described at Cfg::D / Cfg::ROLL.
+// Build-time switches of the schedule (measurement aids; the defaults are the measured optima).
+#ifndef TC_ROLL
+#define TC_ROLL 1      // 1: the multi-term families gather in a rolling fashion (see Cfg::ROLL); 0: one burst per k-step
 #endif
-#ifndef TC_XE
-#define TC_XE 2
+#ifndef TC_PIN8
+#define TC_PIN8 0      // KT = 32: keep the compiler from moving the parts of a rolling gather across instruction groups
 #endif
-#ifndef TC_XL
-#define TC_XL 6
-#endif
-#ifndef TC_PIN1
-#define TC_PIN1 1
+#ifndef TC_PIN4
+#define TC_PIN4 1      // KT = 16: likewise
 #endif
 
 template <int NTA_, int NTB_, bool EXACT_>
@@ -70,29 +64,34 @@ struct Cfg {
     static constexpr bool SINGLE = EXACT && NTA == 1 && NTB == 1;
     // D = how many k-steps ahead of the multiplying step a gather is issued; SETS = register sets for gathers in
     // flight.  Single-term operands: D = 2 with two sets (issued during step s, stored to LDS during step s + 1).
-    // Sums of several terms have registers for one set only.  Their set is stored to LDS in the middle of a step and
-    // re-issued at once for the step after the next (D = 2, SETS = 1): the gathered data has one whole k-step to
-    // arrive and the store to LDS happens while the SIMD's other wave multiplies, where issuing at the start of a
-    // step and storing at its end (D = 1) leaves both waves of a SIMD waiting and storing at the same time.
-    static constexpr int D = SINGLE ? 2 : ((TC_ONE_SET_AHEAD && EXACT) ? 2 : 1);
+    // Sums of several terms have registers for one set only.  ROLL: that set is turned over piecewise.  The tile of
+    // the next k-step is cut into NQ parts (the first half of the groups takes A's, the second half B's); next to
+    // instruction group g a wave waits for part g of the loads it issued one k-step earlier, adds the terms, stores
+    // the sums to the other LDS buffer and at once re-issues that part's loads for the k-step after the next.
+    // Every load has exactly one k-step to arrive, the waits are for the oldest loads in flight only, and loads and
+    // LDS stores are spread evenly over the step.  (Issuing a whole k-step of a multi-term tile in one burst, 16 to
+    // 32 loads per wave, fills the address queue of the CU: the profiler counts cycles with that queue full for the
+    // multi-term families and none for the single-term one.)  Without ROLL: D = 1, issue at the start (first wave of
+    // a SIMD) or in the middle (second wave) of a step, store after its last group.
+    static constexpr bool ROLL = TC_ROLL && EXACT && !SINGLE;
+    static constexpr int D = (SINGLE || ROLL) ? 2 : 1;
     static constexpr int SETS = SINGLE ? 2 : 1;
     static constexpr int NE = TM * KT / NTHREADS;  // elements of each operand tile (and term) a thread gathers per k-step
     static constexpr int NQ = KT / 4;              // matrix-core instruction groups per k-step
     static constexpr int TILE = KT * PITCH;
-    // Schedule inside a k-step, in instruction groups completed (measured optima).  The two waves of a SIMD do their
-    // loads and LDS stores at different times so that one of them always has MFMAs to issue: the first wave issues
-    // its gather before group 0, its partner after ISSUE_LATE groups, when the first burst of loads has drained from
-    // the CU's address pipeline.  With two sets the second wave stores right before it issues and the first wave
-    // three quarters into the step; with D = 1 both store after the last group.  One set, two steps ahead: the
-    // first wave stores and re-issues after X_EARLY groups, its partner after X_LATE.
+    // Schedule inside a k-step without ROLL, in instruction groups completed (measured optima).  The two waves of a
+    // SIMD do their loads and LDS stores at different times so that one of them always has MFMAs to issue: the
+    // first wave issues its gather before group 0, its partner after ISSUE_LATE groups, when the first burst of
+    // loads has drained from the CU's address pipeline.  With two sets the second wave stores right before it
+    // issues and the first wave three quarters into the step; with D = 1 both store after the last group.
     static constexpr int ISSUE_LATE = (SETS == 2) ? 5 : (NQ == 8 ? 4 : 3);
     static constexpr int STAGE_EARLY = (SETS == 2) ? 6 : NQ;
     static constexpr int STAGE_LATE = (SETS == 2) ? 4 : NQ;
-    static constexpr int X_EARLY = (NQ == 8) ? TC_XE : TC_XE / 2;
-    static constexpr int X_LATE = (NQ == 8) ? TC_XL : TC_XL / 2;
-    static constexpr bool PIN = SETS == 1 && (D == 1 || TC_PIN1);
+    // Measured at 16384^3: the 32-deep rolling families are fastest when the compiler may place the parts freely
+    // (one-level ABC 73.8 against 73.4 TFLOP/s), the 16-deep ones when each part stays next to its group.
+    static constexpr bool PIN = SETS == 1 && (D == 1 || (NQ == 8 ? TC_PIN8 : TC_PIN4));
     static_assert(SETS == 1 || NQ == 8, "the two-set schedule is written for 8 groups");
-    static_assert(X_EARLY >= 0 && X_LATE <= NQ, "store points lie inside the step");
+    static_assert(NE % (NQ / 2) == 0 && (NE / (NQ / 2)) % 2 == 0, "a part of a rolling gather holds whole element pairs");
 };
 
 // Scatter vectors are reached through pointers stored in the product descriptors; telling the compiler that they
@@ -227,6 +226,15 @@ __device__ __forceinline__ void issue_affine(double (&ld)[NT][TM * KT / NTHREADS
     }
 }
 
+// A wave-uniform value, marked as such for the compiler (it then lives in scalar registers and everything derived
+// from it is scalar arithmetic; without the mark a value that crosses a branch can end up in a vector register, and
+// a buffer load whose scalar operand sits there is turned into a loop over the lanes).
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+    const int lo = __builtin_amdgcn_readfirstlane((int)(uint32_t)(uint64_t)v);
+    const int hi = __builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+
 // Per-operand set-up of the table-free gather.  sx / sk: element strides along the free / the contracted bundle;
 // offx / offk: first free / contracted entry of each term; tile0: first free entry of the tile; w: wave index.
 template <int MODE, int NT, int KT>
@@ -247,9 +255,11 @@ __device__ __forceinline__ void setup_affine(Affine<NT>& a, const double* base, 
         wk = 16 * (w % KB);
         a.dE = 8 * M::CX * sx;
     }
-    a.dS = 8 * KT * sk;
+    a.dE = uniform64(a.dE);
+    a.dS = uniform64(8 * KT * sk);
+    a.last = __builtin_amdgcn_readfirstlane(last);
 #pragma unroll
-    for (int t = 0; t < NT; ++t) a.u0[t] = (int64_t)base + 8 * ((offx[t] + tile0 + wx) * sx + (offk[t] + wk) * sk);
+    for (int t = 0; t < NT; ++t) a.u0[t] = uniform64((int64_t)base + 8 * ((offx[t] + tile0 + wx) * sx + (offk[t] + wk) * sk));
 }
 
 // Signed sum of the terms (the operand sum of Sec. 4.1) into the LDS tile.
@@ -325,6 +335,114 @@ __device__ __forceinline__ void stage_checked(const double (&ld)[NT][TM * KT / N
     }
 }
 
+// ---- the same four steps for a part of a tile: loads [E0, E1) of every term (rolling gather, Cfg::ROLL) ----
+template <int MODE, int NT, int KT, bool VEC, int E0, int E1>
+__device__ __forceinline__ void issue_fast_part(double (&ld)[NT][TM * KT / NTHREADS], const Bases& b, int slot_off) {
+    typedef Map<MODE, KT, VEC> M;
+#pragma unroll
+    for (int e = E0; e < E1; ++e) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int64_t addr = (M::CX == 0 ? b.fixv[t] : b.fix[t * 128 + M::CX * e]) + b.step[slot_off + t * KT + M::CK * e];
+            if (VEC) {
+                const double2_t v = *(gdbl2_t)addr;
+                ld[t][2 * e] = v.x;
+                ld[t][2 * e + 1] = v.y;
+            } else {
+                ld[t][e] = *(gdbl_t)addr;
+            }
+        }
+    }
+}
+
+template <int MODE, int NT, int KT, bool BUF, int E0, int E1>
+__device__ __forceinline__ void issue_affine_part(double (&ld)[NT][TM * KT / NTHREADS], const Affine<NT>& a, int target) {
+    typedef const __attribute__((address_space(1))) char* gbyte_t;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int64_t ub = a.u0[t] + (int64_t)(target < a.last ? target : a.last) * a.dS;
+        if constexpr (BUF) {
+            const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)ub, 0, -1, 0x00020000);
+#pragma unroll
+            for (int e = E0; e < E1; ++e) {
+                const double2_t v =
+                    __builtin_bit_cast(double2_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)a.voff, (int)(e * a.dE), 0));
+                ld[t][2 * e] = v.x;
+                ld[t][2 * e + 1] = v.y;
+            }
+        } else {
+#pragma unroll
+            for (int e = E0; e < E1; ++e) {
+                const double2_t v = *(gdbl2_t)((gbyte_t)(ub + e * a.dE) + a.voff);
+                ld[t][2 * e] = v.x;
+                ld[t][2 * e + 1] = v.y;
+            }
+        }
+    }
+}
+
+template <int MODE, int NT, int KT, bool VEC, bool UNIT, int E0, int E1>
+__device__ __forceinline__ void stage_fast_part(const double (&ld)[NT][TM * KT / NTHREADS], double* __restrict__ dst, const double* __restrict__ coef) {
+    typedef Map<MODE, KT, VEC> M;
+#pragma unroll
+    for (int e = E0; e < E1; ++e) {
+        double v[2];
+#pragma unroll
+        for (int h = 0; h < (VEC ? 2 : 1); ++h) {
+            const int i = VEC ? 2 * e + h : e;
+            v[h] = UNIT ? ld[0][i] : coef[0] * ld[0][i];
+#pragma unroll
+            for (int t = 1; t < NT; ++t) v[h] = __builtin_fma(coef[t], ld[t][i], v[h]);
+        }
+        double* p = dst + M::CK * e * PITCH + M::CX * e;
+        if (!VEC) {
+            p[0] = v[0];
+        } else if (MODE == 0) {
+            double2_t vv = {v[0], v[1]};
+            *reinterpret_cast<double2_t*>(p) = vv;
+        } else {
+            p[0] = v[0];
+            p[PITCH] = v[1];
+        }
+    }
+}
+
+template <int MODE, int NT, int KT, int E0, int E1>
+__device__ __forceinline__ void issue_checked_part(double (&ld)[NT][TM * KT / NTHREADS], unsigned& padmask, const double* __restrict__ safe,
+                                                   const int64_t* __restrict__ fixed_tab, const int64_t* __restrict__ step_tab, int tid) {
+    typedef Map<MODE, KT, false> M;
+    constexpr int NE = M::NE;
+    const int k0 = M::k0(tid), x0 = M::x0(tid);
+#pragma unroll
+    for (int e = E0; e < E1; ++e) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int64_t addr = fixed_tab[t * 128 + x0 + M::CX * e] + step_tab[t * KT + k0 + M::CK * e];
+            const unsigned bit = 1u << (t * NE + e);
+            padmask = addr < 0 ? (padmask | bit) : (padmask & ~bit);
+            ld[t][e] = *(gdbl_t)(addr < 0 ? (int64_t)safe : addr);
+        }
+    }
+}
+
+template <int MODE, int NT, int KT, int E0, int E1>
+__device__ __forceinline__ void stage_checked_part(const double (&ld)[NT][TM * KT / NTHREADS], unsigned padmask, double* __restrict__ tile,
+                                                   const double* __restrict__ coef, int tid) {
+    typedef Map<MODE, KT, false> M;
+    constexpr int NE = M::NE;
+    double* dst = tile + M::k0(tid) * PITCH + M::x0(tid);
+#pragma unroll
+    for (int e = E0; e < E1; ++e) {
+        double v = 0.0;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const double x = ((padmask >> (t * NE + e)) & 1u) ? 0.0 : ld[t][e];
+            v = (t == 0) ? coef[0] * x : __builtin_fma(coef[t], x, v);
+        }
+        dst[M::CK * e * PITCH + M::CX * e] = v;
+    }
+}
+
 __device__ __forceinline__ int64_t min64(int64_t a, int64_t b) { return a < b ? a : b; }
 
 template <int AMODE, int BMODE, class CF, bool VA, bool VB>
@@ -388,6 +506,72 @@ struct State {
         }
     }
 
+    // Rolling gather: part G of a k-step's tile.  Parts 0 .. NQ/2 - 1 belong to A, the others to B; part g of an
+    // operand is registers [g * PER, (g + 1) * PER) of every term, whatever mapping loaded them.  Whether a k-step was
+    // (and is) gathered without padding checks follows from its number alone.
+    // roll_stage: part G of k-step `target` (in flight in the set) goes to LDS buffer BUF.
+    template <int BUF, int G, bool FAST, bool UNIT>
+    __device__ __forceinline__ void roll_stage(int target) {
+        constexpr int H = NQ / 2, PER = NE / H;
+        constexpr bool IS_A = G < H;
+        constexpr int g = IS_A ? G : G - H;
+        constexpr int S0 = g * PER, S1 = (g + 1) * PER;  // as scalar loads
+        const bool fast = FAST || target < kfull;
+        if constexpr (IS_A) {
+            constexpr int E0 = VA ? S0 / 2 : S0, E1 = VA ? S1 / 2 : S1;
+            if (fast)
+                stage_fast_part<AMODE, NTA, KT, VA, UNIT, E0, E1>(la[0], ba.stage + BUF * TILE, coefA);
+            else
+                stage_checked_part<AMODE, NTA, KT, S0, S1>(la[0], pa[0], &S->a[BUF][0], coefA, tid);
+        } else {
+            constexpr int E0 = VB ? S0 / 2 : S0, E1 = VB ? S1 / 2 : S1;
+            if (fast)
+                stage_fast_part<BMODE, NTB, KT, VB, UNIT, E0, E1>(lb[0], bb.stage + BUF * TILE, coefB);
+            else
+                stage_checked_part<BMODE, NTB, KT, S0, S1>(lb[0], pb[0], &S->b[BUF][0], coefB, tid);
+        }
+    }
+    // roll_issue: the loads of part G of k-step `target`, with table slot SLOT (= target % 2)
+    template <int SLOT, int G, bool FAST, bool AFF>
+    __device__ __forceinline__ void roll_issue(int target) {
+        constexpr int H = NQ / 2, PER = NE / H;
+        constexpr bool IS_A = G < H;
+        constexpr int g = IS_A ? G : G - H;
+        constexpr int S0 = g * PER, S1 = (g + 1) * PER;
+        constexpr bool BUF = NTA <= 2 && NTB <= 2;  // (four descriptors per operand would spill scalar registers)
+        const bool fast = FAST || target < kfull;
+        if constexpr (IS_A) {
+            constexpr int E0 = VA ? S0 / 2 : S0, E1 = VA ? S1 / 2 : S1;
+            if constexpr (FAST && AFF) {
+                issue_affine_part<AMODE, NTA, KT, BUF, S0 / 2, S1 / 2>(la[0], afa, target);
+            } else {
+                if (fast)
+                    issue_fast_part<AMODE, NTA, KT, VA, E0, E1>(la[0], ba, SLOT * NTA * KT);
+                else
+                    issue_checked_part<AMODE, NTA, KT, S0, S1>(la[0], pa[0], safeA, &S->a_fix[0][0], &S->a_step[SLOT][0][0], tid);
+            }
+        } else {
+            constexpr int E0 = VB ? S0 / 2 : S0, E1 = VB ? S1 / 2 : S1;
+            if constexpr (FAST && AFF) {
+                issue_affine_part<BMODE, NTB, KT, BUF, S0 / 2, S1 / 2>(lb[0], afb, target);
+            } else {
+                if (fast)
+                    issue_fast_part<BMODE, NTB, KT, VB, E0, E1>(lb[0], bb, SLOT * NTB * KT);
+                else
+                    issue_checked_part<BMODE, NTB, KT, S0, S1>(lb[0], pb[0], safeB, &S->b_fix[0][0], &S->b_step[SLOT][0][0], tid);
+            }
+        }
+    }
+    // Every part of k-step `target`, in the order in which the loop turns the parts over (the hardware returns loads
+    // in issue order and the waits count loads, so the loop's first trip must find them in that order).
+    template <int SLOT, bool FAST, bool AFF, int G = 0>
+    __device__ __forceinline__ void roll_issue_all(int target) {
+        if constexpr (G < NQ) {
+            roll_issue<SLOT, G, FAST, AFF>(target);
+            roll_issue_all<SLOT, FAST, AFF, G + 1>(target);
+        }
+    }
+
     template <int CUR, int Q>
     __device__ __forceinline__ void read_frags(double (&af)[4], double (&bf)[8]) {
         constexpr int ROW = 16 * (Q / 4) + (Q % 4);
@@ -424,28 +608,19 @@ struct State {
     // What a wave does besides MFMAs once DONE instruction groups of k-step `step` (LDS buffer CUR) are complete.
     // D = 2, two sets: the loads of step + 2 go to register set CUR (its previous contents, k-step `step`, were
     //        stored one step ago), and set CUR ^ 1 (k-step step + 1, issued one step ago) is stored to LDS buffer CUR ^ 1.
-    // D = 2, one set: the set (k-step step + 1, issued one step ago) is stored to LDS buffer CUR ^ 1 and the loads of
-    //        step + 2 are issued into it right away.
+    // ROLL (D = 2, one set): part G of the set (k-step step + 1, issued one step ago) is stored to LDS buffer CUR ^ 1
+    //        and that part's loads of step + 2 are issued into the same registers right away.
     // D = 1: the loads of step + 1 are issued and, after the last group, stored.
     // ROLE: 0 = first wave of the SIMD, 1 = second, 2 = decided at run time (member `early`).
     template <int CUR, int DONE, int ROLE, bool FAST, bool UNIT, bool AFF>
     __device__ __forceinline__ void between_groups(int step) {
         constexpr int NXT = CUR ^ 1;
-        if constexpr (D == 2 && SETS == 1) {
-            if constexpr (ROLE != 1 && DONE == CF::X_EARLY) {
+        if constexpr (CF::ROLL) {
+            constexpr int G = DONE - 1;  // part g is turned over after instruction group g
+            if constexpr (G >= 0 && G < NQ) {
                 pin();
-                if (ROLE == 0 || early) {
-                    stage<0, NXT, FAST, UNIT>();
-                    issue<0, CUR, FAST, AFF>(step + 2);
-                }
-                pin();
-            }
-            if constexpr (ROLE != 0 && DONE == CF::X_LATE) {
-                pin();
-                if (ROLE == 1 || !early) {
-                    stage<0, NXT, FAST, UNIT>();
-                    issue<0, CUR, FAST, AFF>(step + 2);
-                }
+                roll_stage<NXT, G, FAST, UNIT>(step + 1);
+                roll_issue<CUR, G, FAST, AFF>(step + 2);
                 pin();
             }
         } else {
@@ -515,6 +690,12 @@ struct State {
     // wait counts for the loads in flight are exact.
     template <int ROLE, bool UNIT, bool AFF>
     __device__ __forceinline__ void run_fast(int end) {
+        // A rolling gather enters its loop with k-step 1 in flight, issued here, straight ahead of the loop and in
+        // the loop's own order, so that the loop's load counts are exact from its first trip on.
+        if constexpr (CF::ROLL) {
+            roll_issue_all<1, true, AFF>(1);
+            if constexpr (!(AFF && KT == 32)) __syncthreads();  // table slot 1 has been read by every thread (step 0 refills it)
+        }
         for (int step = 0; step < end; step += 2) {
             step_body<0, ROLE, true, UNIT, AFF>(step);
             step_body<1, ROLE, true, UNIT, AFF>(step + 1);
@@ -533,6 +714,12 @@ struct State {
 
     // k-steps [begin, nk) (both even): padding decided per k-step
     __device__ __forceinline__ void run_checked(int begin) {
+        if constexpr (CF::ROLL) {
+            if (begin == 0) {
+                roll_issue_all<1, false, false>(1);
+                __syncthreads();  // table slot 1 has been read by every thread (step 0 refills it)
+            }
+        }
         for (int step = begin; step < nk; step += 2) {
             step_body<0, 2, false, false, false>(step);
             step_body<1, 2, false, false, false>(step + 1);
@@ -811,7 +998,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     }
 
     // ---- prologue: k-step 0 into LDS buffer 0; with D = 2 also the gather of k-step 1 (into the second register
-    //      set, or into the only one once k-step 0 has left it) and the scatter entries of k-step 2 ----
+    //      set; a rolling gather issues it ahead of its loop) and the scatter entries of k-step 2 ----
     if (!affine) st.template issue<0, 0, false>(0);
     if constexpr (D == 2 && SETS == 2) {
         if (!affine) st.template issue<1, 1, false>(1);
@@ -819,15 +1006,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         st.ent_dst[0] = (2 * KT < st.ent_limit || st.all_fast) ? 8 * st.ent_ptr[2 * KT < st.ent_limit ? 2 * KT : 0] : kSentinel;
     }
     st.template stage<0, 0, false, false>();
-    if constexpr (D == 2 && SETS == 1) {
-        bool done = false;
-        if constexpr (VA && VB && CF::EXACT) {
-            if (affine) {
-                st.template issue<0, 1, true, true>(1);
-                done = true;
-            }
-        }
-        if (!done) st.template issue<0, 1, false>(1);
+    if constexpr (CF::ROLL) {  // (k-step 1 is issued where the loops begin)
         __syncthreads();  // table slot 0 has been read by every thread
         st.ent_dst[0] = (2 * KT < st.ent_limit || st.all_fast) ? 8 * st.ent_ptr[2 * KT < st.ent_limit ? 2 * KT : 0] : kSentinel;
     }
@@ -847,7 +1026,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     nfast = nfast < 2 ? 0 : (nfast & ~1);
     if (st.all_fast) nfast = st.nk;
     if (nfast > 0) {
-        const bool role0 = __builtin_amdgcn_readfirstlane(wm) == 0;
+        const bool role0 = CF::ROLL || __builtin_amdgcn_readfirstlane(wm) == 0;  // (a rolling gather is the same for both waves of a SIMD)
         if (CF::EXACT && st.unitA && st.unitB) {  // a loop of its own: no multiply (or no arithmetic at all) per element
             if (role0)
                 st.template run_fast<0, CF::EXACT>(nfast, affine);

@@ -1050,12 +1050,13 @@ int tc_contract_static(const tc_plan_t* plan, double alpha, const double* A_dev,
     return tc_contract(plan, alpha, A_dev, B_dev, beta, C_dev, ws, stream);
 }
 
-int tc_contract_timed(const tc_plan_t* plan, double alpha, const double* A_dev, const double* B_dev, double beta, double* C_dev,
-                      void* workspace_dev, void* stream, tc_launch_times_t* out) {
-    if (!plan || !out) return TC_ERR_NULL;
+int tc_contract_launch_times(const tc_plan_t* plan, double alpha, const double* A_dev, const double* B_dev, double beta, double* C_dev,
+                             void* workspace_dev, void* stream, double* ms_out, int capacity) {
+    if (!plan) return TC_ERR_NULL;
     if (plan->host_only) return TC_ERR_STATE;
-    std::memset(out, 0, sizeof *out);
-    if (plan->steps.empty()) return TC_OK;
+    const int n = (int)plan->steps.size();
+    if (n == 0) return 0;
+    if (!ms_out || capacity < n) return TC_ERR_RANGE;
     if (!C_dev) return TC_ERR_NULL;
     if (plan->k > 0 && (!A_dev || !B_dev)) return TC_ERR_NULL;
     if (plan->workspace_bytes > 0 && !workspace_dev) return TC_ERR_WORKSPACE;
@@ -1075,14 +1076,34 @@ int tc_contract_timed(const tc_plan_t* plan, double alpha, const double* A_dev, 
             rc = TC_ERR_HIP;
             break;
         }
-        if (plan->steps[i].kind == STEP_FUSED)
-            out->fused_ms += ms, ++out->fused_launches;
-        else
-            out->elementwise_ms += ms, ++out->elementwise_launches;
+        ms_out[i] = ms;
     }
     for (void* e : ev)
         if (e) tc::dev_event_destroy(e);
-    return rc;
+    return rc == TC_OK ? n : rc;
+}
+
+int tc_contract_timed(const tc_plan_t* plan, double alpha, const double* A_dev, const double* B_dev, double beta, double* C_dev,
+                      void* workspace_dev, void* stream, tc_launch_times_t* out) {
+    if (!plan || !out) return TC_ERR_NULL;
+    std::memset(out, 0, sizeof *out);
+    std::vector<double> ms(plan->steps.size() + 1, 0.0);
+    const int n = tc_contract_launch_times(plan, alpha, A_dev, B_dev, beta, C_dev, workspace_dev, stream, ms.data(), (int)ms.size());
+    if (n < 0) return n;
+    for (int i = 0; i < n; ++i) {
+        if (plan->steps[i].kind == STEP_FUSED)
+            out->fused_ms += ms[i], ++out->fused_launches;
+        else
+            out->elementwise_ms += ms[i], ++out->elementwise_launches;
+    }
+    return TC_OK;
+}
+
+int tc_bench_mfma_peak(int instruction, void* stream, double* tflops_out) {
+    if (!tflops_out) return TC_ERR_NULL;
+    if (instruction != 0 && instruction != 1) return TC_ERR_RANGE;
+    *tflops_out = 0.0;
+    return tc::bench_mfma_peak(instruction, 4000, stream, tflops_out) ? TC_ERR_HIP : TC_OK;
 }
 
 int tc_destroy(tc_plan_t* plan) {
@@ -1145,6 +1166,8 @@ int tc_plan_launch(const tc_plan_t* plan, int index, tc_launch_info_t* out) {
         const FusedShape f = fused_shape(plan, s);
         out->n_products = s.count;
         out->max_terms = f.terms;
+        out->terms_a = s.cfg.nta;
+        out->terms_b = s.cfg.ntb;
         out->depth = f.kb;
         out->tiles = f.tiles;
         out->tail_tiles = s.tail_tiles, out->tail_chunks = s.tail_chunks, out->tail_kc = s.tail_kc;

@@ -62,6 +62,8 @@ constexpr size_t kStaticWorkspaceBytes = (size_t)32 << 20;
 // ---- device entry points (tc_device.hip); each returns a hipError_t cast to int ----
 // Device address of the current GPU's static workspace array (looked up on the first call per device, then cached).
 int dev_static_workspace(void** ptr);
+// MFMA-only loop (kind 0: v_mfma_f64_4x4x4_4b_f64, 1: v_mfma_f64_16x16x4_f64); blocks until done; TFLOP/s achieved
+int bench_mfma_peak(int kind, int iters, void* stream, double* tflops_out);
 int dev_malloc(void** p, size_t bytes);
 int dev_free(void* p);
 int dev_upload(void* dst, const void* src, size_t bytes, void* stream);

@@ -154,6 +154,21 @@ def test_midsize_every_kernel_family(gpu, idxA, idxB):
             _check(gpu, A, B, C, 1.0, 1.0, level, variant, exact=(kind == "smallint"))
 
 
+def test_general_strides_two_levels_one_product_per_launch(gpu):
+    """A 6-D contraction whose A has an odd fastest dimension (gathered element by element) and whose B is gathered
+    pair-wise along the contracted bundle; block extents 272 x 32 x 432 at two levels, so that every launch has three
+    ragged tiles and the last contracted block is shorter than the others.  Run with one product per launch, with
+    the tail cut into chunks of 64 contracted entries, and through the AB temporaries: small integers, bit for bit."""
+    L = {"d": 12, "g": 18, "j": 106, "h": 16, "k": 5, "i": 3, "b": 5, "f": 8}
+    A = workloads.make_tensor("dgjhk", L, 41, 0, "smallint", (183168, 10176, 96, 6, 1))
+    B = workloads.make_tensor("ibhjf", L, 42, 1, "smallint", (17, 51, 1, 255, 27030))
+    C = workloads.make_tensor("gdbifk", L, 43, 2, "smallint", (10080, 35, 7, 420, 1260, 1))
+    for level, variant, kw in ((2, "abc", {}), (2, "abc", {"tail_split": -1, "no_merge": True}), (2, "ab", {"tail_split": -1}),
+                               (2, "abc", {"tail_split": 5}), (1, "abc", {"tail_split": -1, "no_merge": True}), (2, "hybrid", {})):
+        for rep in range(2):
+            _check(gpu, A, B, C, -2.0, 0.0, level, variant, exact=True, **kw)
+
+
 def test_automatic_level_and_variant(gpu):
     """TC_LEVEL_AUTO / TC_VARIANT_AUTO: whatever the model picks, the result is the contraction."""
     import paper_1704_03092_amd as tc
