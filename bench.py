@@ -151,6 +151,11 @@ def main():
         torch.cuda.synchronize()
         del cx, cy
 
+    # ---- the machine's ceiling first: what the matrix cores sustain with nothing else going on (same instruction as the
+    #      kernels; about 50 ms of work, which also brings the GPU out of its idle clocks before anything is timed) ----
+    mfma_only = tc.tc_bench_mfma_peak(0, st)
+    mfma_only_16x16 = tc.tc_bench_mfma_peak(1, st)
+
     # ---- headline mode ----
     wall_ms, ev_ms, info, kern = time_mode(args.level, args.variant, args.steps, args.warmup)
     value = flops / (wall_ms * 1e-3) * 1e-9
@@ -177,7 +182,6 @@ def main():
 
     # ---- roofline of the fused kernel (gather + operand sums + MFMA + update): executed flops / its own launch durations ----
     # (block extents are rounded up to multiples of 16, so the executed flops are what the launches really multiply)
-    mfma_only = tc.tc_bench_mfma_peak(0, st)  # what the matrix cores sustain with nothing else going on, same instruction
     executed = kern["fused_flops"]
     achieved = executed / (kern["fused_ms"] * 1e-3) * 1e-12
     nC = 2.0 if cfg.beta != 0.0 else 1.0
@@ -199,6 +203,7 @@ def main():
                      "families": families,
                      "mfma_tflops": round(achieved, 2), "mfma_frac": round(mfma_frac, 4),
                      "measured_mfma_only_tflops": round(mfma_only, 2), "frac_measured_mfma_peak": round(achieved / mfma_only, 4),
+                     "measured_mfma_only_tflops_16x16x4": round(mfma_only_16x16, 2),
                      "compulsory_hbm_gbs": round(hbm_tbs * 1e3, 1), "hbm_frac": round(hbm_frac, 4)})
 
     # ---- the other modes ----

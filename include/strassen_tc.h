@@ -160,6 +160,10 @@ typedef struct {
     int64_t depth;        /* fused: contracted extent of one product */
     int64_t tiles;        /* fused: 128 x 128 tiles of the launch */
     int64_t tail_kc;      /* contracted entries per chunk */
+    int64_t tiles_table_free; /* fused: tiles gathered by stride, without scatter tables (Sec. 4.1 "Packing": every block
+                               * scatter entry of the tile's rows and columns is non-zero in every summed block, the
+                               * contracted bundle is one constant-stride run, no zero padding in the tile); the other
+                               * tiles of the launch go through the scatter tables */
 } tc_launch_info_t;
 
 /* Modelled time of one tc_contract() with beta != 0, in seconds, split as in Sec. 5 eq. (2)-(4):

@@ -76,7 +76,7 @@ class tc_options_t(ctypes.Structure):
 class tc_launch_info_t(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int), ("n_products", ctypes.c_int), ("max_terms", ctypes.c_int), ("tail_tiles", ctypes.c_int),
                 ("tail_chunks", ctypes.c_int), ("terms_a", ctypes.c_int), ("terms_b", ctypes.c_int), ("reserved", ctypes.c_int * 1), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
-                ("depth", ctypes.c_int64), ("tiles", ctypes.c_int64), ("tail_kc", ctypes.c_int64)]
+                ("depth", ctypes.c_int64), ("tiles", ctypes.c_int64), ("tail_kc", ctypes.c_int64), ("tiles_table_free", ctypes.c_int64)]
 
 
 class tc_plan_info_t(ctypes.Structure):

@@ -236,13 +236,13 @@ __device__ __forceinline__ int64_t uniform64(int64_t v) {
 }
 
 // Per-operand set-up of the table-free gather.  sx / sk: element strides along the free / the contracted bundle;
-// offx / offk: first free / contracted entry of each term; tile0: first free entry of the tile; w: wave index.
+// fx: element offset of the tile's first free entry in each term (its scatter entry); offk: first contracted entry of
+// each term; w: wave index.
 template <int MODE, int NT, int KT>
-__device__ __forceinline__ void setup_affine(Affine<NT>& a, const double* base, int64_t sx, int64_t sk, const int64_t* offx, const int64_t* offk,
-                                             int64_t tile0, int lane, int w, int last) {
+__device__ __forceinline__ void setup_affine(Affine<NT>& a, const double* base, int64_t sx, int64_t sk, const int64_t (&fx)[NT], const int64_t* offk,
+                                             int lane, int w, int last) {
     typedef Map<MODE, KT, true> M;
     constexpr int KB = KT / 16;
-    a.last = last;
     int64_t wx, wk;
     if (MODE == 0) {
         a.voff = (uint32_t)(8 * (2 * lane) * sx);
@@ -259,7 +259,38 @@ __device__ __forceinline__ void setup_affine(Affine<NT>& a, const double* base, 
     a.dS = uniform64(8 * KT * sk);
     a.last = __builtin_amdgcn_readfirstlane(last);
 #pragma unroll
-    for (int t = 0; t < NT; ++t) a.u0[t] = uniform64((int64_t)base + 8 * ((offx[t] + tile0 + wx) * sx + (offk[t] + wk) * sk));
+    for (int t = 0; t < NT; ++t) a.u0[t] = uniform64((int64_t)base + 8 * (fx[t] + wx * sx + (offk[t] + wk) * sk));
+}
+
+// The packing rule of Sec. 4.1 applied to a tile: its 128 free entries [off[t] + tile0, + 128) of every term are
+// regular iff every block scatter entry involved is non-zero (the entries are then equal) and consecutive blocks join
+// up with the same stride; only then may the tile be gathered by stride.  bs: block scatter vector for blocks of 16
+// entries (block offsets and tile origins are multiples of 16).  Lane l of the wave looks at block l % 8 of term l / 8.
+// Returns the common stride and each term's first scatter entry; every wave of the workgroup computes the same answer.
+template <int NT>
+__device__ __forceinline__ bool tile_regular(gvec_t scat, gvec_t bs, const int64_t* off, int64_t tile0, int lane, int64_t& stride,
+                                             int64_t (&first)[NT]) {
+    static_assert(NT * 8 <= 64, "one lane per block and term");
+    const int t = lane >> 3, j = lane & 7;
+    int64_t v = 0, f = 0;
+    bool ok = true;
+    if (t < NT) {
+        const int64_t f0 = off[t] + tile0 + 16 * j;
+        v = bs[f0 >> 4];
+        f = scat[f0];
+        ok = v > 0 && (j == 0 || f - scat[f0 - 1] == v);
+    }
+    const int64_t s0 = uniform64(v);  // lane 0: block 0 of term 0
+    ok = ok && (t >= NT || v == s0);
+    if (!__all(ok ? 1 : 0)) return false;
+    stride = s0;
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+        const int lo = __builtin_amdgcn_readlane((int)(uint32_t)(uint64_t)f, 8 * u);
+        const int hi = __builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)f >> 32), 8 * u);
+        first[u] = (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+    }
+    return true;
 }
 
 // Signed sum of the terms (the operand sum of Sec. 4.1) into the LDS tile.
@@ -358,6 +389,10 @@ __device__ __forceinline__ void issue_fast_part(double (&ld)[NT][TM * KT / NTHRE
 template <int MODE, int NT, int KT, bool BUF, int E0, int E1>
 __device__ __forceinline__ void issue_affine_part(double (&ld)[NT][TM * KT / NTHREADS], const Affine<NT>& a, int target) {
     typedef const __attribute__((address_space(1))) char* gbyte_t;
+    // Without buffer descriptors: the per-lane offset is re-read through an empty asm statement so that its widening
+    // to 64 bits stays next to the loads, which then take the scalar base + 32-bit lane offset form (no vector add).
+    uint32_t vo = a.voff;
+    if constexpr (!BUF) asm volatile("" : "+v"(vo));
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int64_t ub = a.u0[t] + (int64_t)(target < a.last ? target : a.last) * a.dS;
@@ -373,7 +408,7 @@ __device__ __forceinline__ void issue_affine_part(double (&ld)[NT][TM * KT / NTH
         } else {
 #pragma unroll
             for (int e = E0; e < E1; ++e) {
-                const double2_t v = *(gdbl2_t)((gbyte_t)(ub + e * a.dE) + a.voff);
+                const double2_t v = *(gdbl2_t)((gbyte_t)(ub + e * a.dE) + vo);
                 ld[t][2 * e] = v.x;
                 ld[t][2 * e + 1] = v.y;
             }
@@ -861,20 +896,40 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     // No padding anywhere in the tile: the unchecked loop runs to the end.  The gathers it issues for the D k-steps
     // past the end are never used; their table entries (and computed addresses) repeat ones that exist.
     st.all_fast = CF::EXACT && st.kfull == st.nk;
-    // table-free gather for products whose operands are both plain strided matrices (and gathered pair-wise)
+    // Table-free gather (the stride path of Sec. 4.1) for a tile whose operands are regular: along the contracted
+    // bundle the whole scatter vector must be one run of a constant stride (known from the plan); along the free
+    // bundle either the same holds, or the block scatter vectors say that this tile's 128 rows (columns) are regular
+    // in every term.  Gathered pair-wise only.
     constexpr int64_t kStrideLimit = (int64_t)1 << 20;  // keeps the per-lane and per-load byte offsets within 31 bits
     bool affine = false;
     if constexpr (VA && VB && CF::EXACT) {
-        affine = P.A.rs_stride >= 0 && P.A.cs_stride >= 0 && P.B.rs_stride >= 0 && P.B.cs_stride >= 0 && P.A.rs_stride < kStrideLimit &&
-                 P.A.cs_stride < kStrideLimit && P.B.rs_stride < kStrideLimit && P.B.cs_stride < kStrideLimit;
         // (computed addresses of missing rows would leave the operand; a tile with padded k-steps needs the tables
         // for them, and the table-free loop does not keep them up to date)
-        affine = affine && whole && st.all_fast;
-        if (affine) {
-            const int wu = __builtin_amdgcn_readfirstlane(tid >> 6);
-            // A: free bundle = rows, contracted = columns; B: free bundle = columns, contracted = rows
-            setup_affine<AMODE, NTA, KT>(st.afa, Abase + kbeg * P.A.cs_stride, P.A.rs_stride, P.A.cs_stride, P.A.roff, P.A.coff, i0, tid & 63, wu, st.nk - 1);
-            setup_affine<BMODE, NTB, KT>(st.afb, Bbase + kbeg * P.B.rs_stride, P.B.cs_stride, P.B.rs_stride, P.B.coff, P.B.roff, j0, tid & 63, wu, st.nk - 1);
+        if (whole && st.all_fast && P.A.cs_stride >= 0 && P.B.rs_stride >= 0 && P.A.cs_stride < kStrideLimit && P.B.rs_stride < kStrideLimit) {
+            int64_t sxA = P.A.rs_stride, sxB = P.B.cs_stride;
+            int64_t fA[NTA], fB[NTB];
+            bool ok = true;
+            if (sxA >= 0) {
+#pragma unroll
+                for (int t = 0; t < NTA; ++t) fA[t] = (P.A.roff[t] + i0) * sxA;
+            } else {
+                ok = P.A.rbs != nullptr && tile_regular<NTA>(as_global(P.A.rs), as_global(P.A.rbs), P.A.roff, i0, tid & 63, sxA, fA);
+            }
+            if (ok) {
+                if (sxB >= 0) {
+#pragma unroll
+                    for (int t = 0; t < NTB; ++t) fB[t] = (P.B.coff[t] + j0) * sxB;
+                } else {
+                    ok = P.B.cbs != nullptr && tile_regular<NTB>(as_global(P.B.cs), as_global(P.B.cbs), P.B.coff, j0, tid & 63, sxB, fB);
+                }
+            }
+            affine = ok && sxA < kStrideLimit && sxB < kStrideLimit;
+            if (affine) {
+                const int wu = __builtin_amdgcn_readfirstlane(tid >> 6);
+                // A: free bundle = rows, contracted = columns; B: free bundle = columns, contracted = rows
+                setup_affine<AMODE, NTA, KT>(st.afa, Abase + kbeg * P.A.cs_stride, sxA, P.A.cs_stride, fA, P.A.coff, tid & 63, wu, st.nk - 1);
+                setup_affine<BMODE, NTB, KT>(st.afb, Bbase + kbeg * P.B.rs_stride, sxB, P.B.rs_stride, fB, P.B.roff, tid & 63, wu, st.nk - 1);
+            }
         }
     }
     // Such a tile needs no table for its gathers: its first k-steps (one per register set) are issued here, before

@@ -428,8 +428,14 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     auto vec = [p](int id) -> const int64_t* { return p->store_dev ? p->store_dev + p->bundles[id].out_off : nullptr; };
     auto setop = [&](Operand& op, int rs_id, int cs_id, int64_t rs_len, int64_t cs_len, int space, int64_t base_off) {
         set_operand(op, vec(rs_id), vec(cs_id), rs_len, cs_len, space, base_off);
+        op.rs_id = rs_id;
+        op.cs_id = cs_id;
         op.rs_stride = affine_stride(p->bundles[rs_id]);
         op.cs_stride = affine_stride(p->bundles[cs_id]);
+        // the kernel reads the block scatter vectors (blocks of 16 entries) to find tiles whose rows / columns are regular
+        const bool use_bs = p->store_dev && p->bs_block == 16;
+        op.rbs = use_bs ? p->store_dev + p->bundles[rs_id].bs_off : nullptr;
+        op.cbs = use_bs ? p->store_dev + p->bundles[cs_id].bs_off : nullptr;
     };
 
     struct Pending {
@@ -822,6 +828,91 @@ FusedShape fused_shape(const tc_plan_t* p, const Step& s) {
     return f;
 }
 
+// Merged run of a bundle's fastest dimensions: entries [q * len, (q + 1) * len) of its scatter vector are equally
+// spaced by `stride` for every q (dimensions chain while each stride is the previous stride times the previous length).
+struct Run {
+    int64_t stride, len;
+};
+
+Run fastest_run(const BundleDesc& b) {
+    Run r{0, 1};
+    int64_t next = 0;
+    bool first = true;
+    for (int d = 0; d < b.ndim; ++d) {
+        if (b.len[d] <= 1) continue;
+        if (first) {
+            r.stride = b.stride[d];
+            first = false;
+        } else if (b.stride[d] != next) {
+            break;
+        }
+        r.len *= b.len[d];
+        next = b.stride[d] * b.len[d];
+    }
+    if (first) r.len = b.total > 0 ? b.total : 1;  // a single entry
+    return r;
+}
+
+// How many tiles of a fused launch the kernel gathers by stride, without its scatter tables (the kernel decides this
+// per tile from the block scatter vectors; this is the same decision made from the bundle descriptions).
+// A tail tile cut into chunks counts if its chunks do.
+int64_t count_table_free(const tc_plan_t* p, const Step& s) {
+    if (s.kind != STEP_FUSED || !s.cfg.a_vec || !s.cfg.b_vec || s.cfg.nta == 0) return 0;  // pair-wise gathers and exact term counts only
+    const int64_t limit = (int64_t)1 << 20;
+    const int KT = (s.cfg.nta <= 2 && s.cfg.ntb <= 2) ? 32 : 16;
+    const int64_t tiles_m = (s.rows + 127) / 128, tiles_n = (s.cols + 127) / 128;
+    const int64_t per_prod = tiles_m * tiles_n, main_count = (int64_t)s.count * per_prod - s.tail_tiles;
+    int64_t n = 0;
+    for (int pi = 0; pi < s.count; ++pi) {
+        const Product& q = p->prods[s.first + pi];
+        if (q.A.cs_stride < 0 || q.B.rs_stride < 0 || q.A.cs_stride >= limit || q.B.rs_stride >= limit) continue;
+        // the run structure of the scatter vector an operand reads along its free bundle
+        auto run_of = [&](const Operand& op, bool rows) -> Run {
+            const int64_t st = rows ? op.rs_stride : op.cs_stride;
+            if (st >= 0) return Run{st, INT64_MAX};
+            if (p->bs_block != 16) return Run{0, 0};  // the kernel gets no block scatter vectors then
+            return fastest_run(p->bundles[rows ? op.rs_id : op.cs_id]);
+        };
+        const Run ra = run_of(q.A, true), rb = run_of(q.B, false);
+        if (ra.stride >= limit || rb.stride >= limit) continue;
+        if ((ra.len != INT64_MAX && (ra.len < 128 || ra.stride <= 0)) || (rb.len != INT64_MAX && (rb.len < 128 || rb.stride <= 0))) continue;
+        for (int64_t tm = 0; tm < tiles_m; ++tm)
+            for (int64_t tn = 0; tn < tiles_n; ++tn) {
+                const int64_t i0 = tm * 128, j0 = tn * 128;
+                bool ok = true;
+                int64_t klimit = q.kb;
+                for (int t = 0; t < q.A.nterms && ok; ++t) {
+                    ok = std::min(q.mb, q.A.rs_len - q.A.roff[t]) - i0 >= 128;
+                    klimit = std::min(klimit, q.A.cs_len - q.A.coff[t]);
+                    const int64_t f0 = q.A.roff[t] + i0;
+                    if (ok && ra.len != INT64_MAX) ok = f0 % ra.len + 128 <= ra.len;
+                }
+                for (int t = 0; t < q.B.nterms && ok; ++t) {
+                    ok = std::min(q.nb, q.B.cs_len - q.B.coff[t]) - j0 >= 128;
+                    klimit = std::min(klimit, q.B.rs_len - q.B.roff[t]);
+                    const int64_t f0 = q.B.coff[t] + j0;
+                    if (ok && rb.len != INT64_MAX) ok = f0 % rb.len + 128 <= rb.len;
+                }
+                if (!ok) continue;
+                // no padded k-step: every term reaches the full depth, which is a whole, even number of k-steps
+                auto depth_ok = [&](int64_t depth, int64_t real) { return real == depth && depth % (2 * KT) == 0; };
+                // position of the tile in the launch: the last tail_tiles logical ids are cut into chunks
+                const int64_t gsz = 8 * tiles_n, grp = tm / 8, gm0 = grp * 8, gh = std::min<int64_t>(8, tiles_m - gm0);
+                const int64_t lid = (int64_t)pi * per_prod + grp * gsz + tn * gh + (tm - gm0);
+                if (lid < main_count) {
+                    ok = depth_ok(q.kb, klimit);
+                } else {
+                    for (int64_t c = 0; c < s.tail_chunks && ok; ++c) {
+                        const int64_t d = std::min<int64_t>(s.tail_kc, q.kb - c * s.tail_kc);
+                        ok = depth_ok(d, std::min(d, klimit - c * s.tail_kc));
+                    }
+                }
+                n += ok;
+            }
+    }
+    return n;
+}
+
 // Modelled time of a fused launch except its destination updates: whole tiles in whole waves of `units` tiles, the
 // chunks of the tail tiles in whole waves of their own depth, the chunks written and read back, the second launch.
 struct TailCost {
@@ -1168,6 +1259,7 @@ int tc_plan_launch(const tc_plan_t* plan, int index, tc_launch_info_t* out) {
         out->max_terms = f.terms;
         out->terms_a = s.cfg.nta;
         out->terms_b = s.cfg.ntb;
+        out->tiles_table_free = count_table_free(plan, s);
         out->depth = f.kb;
         out->tiles = f.tiles;
         out->tail_tiles = s.tail_tiles, out->tail_chunks = s.tail_chunks, out->tail_kc = s.tail_kc;

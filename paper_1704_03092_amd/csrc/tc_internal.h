@@ -20,9 +20,12 @@ struct Operand {
     int64_t cs_len;
     int32_t space;      // 0: the caller's tensor (A, B or C by role); 1: the workspace
     int32_t nterms;
+    int32_t rs_id, cs_id;  // which of the plan's vectors rs and cs are (host-side bookkeeping)
     int64_t base_off;   // element offset of the matrix view inside its space
     int64_t rs_stride;  // >= 0: rs[i] == i * rs_stride for every i (the bundle is one run of a constant stride); -1 otherwise
     int64_t cs_stride;
+    const int64_t* rbs; // block scatter vectors of rs and cs (Sec. 2.3): stride of each block of 16 entries, 0 = irregular;
+    const int64_t* cbs; // nullptr where the plan's block size is not 16 (the kernel then decides by rs_stride / cs_stride alone)
     int64_t roff[kMaxTerms];  // first row of each block
     int64_t coff[kMaxTerms];  // first column of each block
     double coef[kMaxTerms];   // +1 / -1

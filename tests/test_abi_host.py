@@ -285,6 +285,39 @@ def test_automatic_choice_is_the_argmin_of_the_model():
     assert e.value.status == -6
 
 
+def test_launch_info_counts_tiles_gathered_by_stride():
+    """Sec. 4.1 "Packing": a tile is gathered by stride iff every block scatter entry of its rows and columns is
+    non-zero in every summed block (here also: the contracted bundle is one run, no zero padding in the tile, pairs of
+    entries contiguous).  tc_plan_launch reports how many tiles of each launch that is."""
+    def launches(A, B, C, level=0, variant="abc", **kw):
+        p = _plan(A, B, C, level=level, variant=variant, **kw)
+        out = [(L["tiles"], L["tiles_table_free"]) for L in tc.tc_plan_launches(p) if L["kind"] == 0]
+        tc.tc_destroy(p)
+        return out
+
+    cm = lambda idx, L: (idx, tuple(L[x] for x in idx), tuple(int(np.prod([L[y] for y in idx[:i]])) for i in range(len(idx))))
+    # the rank-k configuration: A[a e b] has rows a + 128 b (a is exactly one tile of rows: every tile regular, the
+    # bundle as a whole not one run), B and C are plain matrices
+    L = dict(a=128, b=128, c=128, d=128, e=256)
+    assert launches(cm("aeb", L), cm("ecd", L), cm("abcd", L)) == [(16384, 16384)]
+    assert launches(cm("aeb", L), cm("ecd", L), cm("abcd", L), level=1) == [(4096, 4096), (8192, 8192), (8192, 8192), (8192, 8192)]
+    assert launches(cm("aeb", L), cm("ecd", L), cm("abcd", L), bs_block=8) == [(16384, 0)]  # the kernel reads blocks of 16 only
+    # lengths 24 next to 128: rows a + 24 b cross a run of 24 in every tile; with a = 192 two tiles of three are regular
+    L = dict(a=24, b=32, c=128, d=2, e=64)
+    assert launches(cm("aeb", L), cm("ecd", L), cm("abcd", L)) == [(12, 0)]
+    L = dict(a=192, b=4, c=128, d=2, e=64)  # rows 0..767: tiles [0,128) ok, [128,256) crosses 192, [256,384) ok, [384,512) ok, [512,640) crosses 576, [640,768) ok
+    assert launches(cm("aeb", L), cm("ecd", L), cm("abcd", L)) == [(12, 8)]
+    # plain matrices: whole tiles without padding only (10001 = 78 * 128 + 17, and 10001 is no multiple of the k-step)
+    g = lambda n, k: (("ik", (n, k), (1, n)), ("kj", (k, n), (1, k)), ("ij", (n, n), (1, n)))
+    assert launches(*g(1024, 512)) == [(64, 64)]
+    assert launches(*g(1000, 512)) == [(64, 49)]
+    assert launches(*g(1024, 500)) == [(64, 0)]
+    assert launches(*g(10001, 10001)) == [(6241, 0)]
+    # element-by-element gathers (odd leading extent next to another dimension): never by stride
+    L = dict(a=127, b=4, c=128, d=2, e=64)
+    assert launches(cm("aeb", L), cm("ecd", L), cm("abcd", L)) == [(8, 0)]
+
+
 def test_split_k_schedule():
     desc = _gemm_desc(9216, 96, 4096)
     plain = _plan(*desc)

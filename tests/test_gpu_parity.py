@@ -169,6 +169,38 @@ def test_general_strides_two_levels_one_product_per_launch(gpu):
             _check(gpu, A, B, C, -2.0, 0.0, level, variant, exact=True, **kw)
 
 
+def test_tiles_gathered_by_stride_next_to_tiles_through_the_tables(gpu):
+    """Contractions whose row bundle is no single constant-stride run: the kernel reads the block scatter vectors and
+    gathers a tile by stride where all its 16-entry blocks are regular and join up (Sec. 4.1 "Packing"), through the
+    scatter tables elsewhere, within one launch.  Lengths 128 (every tile regular), 192 (two tiles of three), 24 and 48
+    (none); small integers, bit for bit; the launch info reports the split."""
+    import torch
+
+    import paper_1704_03092_amd as tc
+
+    cases = [  # lengths, padding after the fastest dimension of A, gap between B's slices, tiles gathered by stride at level 0 (of how many)
+        (dict(a=128, b=4, c=128, d=2, e=64), 0, 0, (8, 8)),
+        (dict(a=128, b=4, c=128, d=2, e=64), 6, 0, (8, 8)),
+        (dict(a=192, b=4, c=128, d=2, e=64), 0, 0, (8, 12)),
+        (dict(a=192, b=4, c=192, d=2, e=128), 0, 0, (12, 18)),  # rows: four of six tiles regular; B is one run as a whole
+        (dict(a=192, b=4, c=192, d=2, e=128), 0, 5, (8, 18)),   # B's slices d apart from each other: two of three column tiles regular
+        (dict(a=24, b=16, c=48, d=8, e=64), 0, 0, (0, 9)),
+        (dict(a=128, b=5, c=128, d=3, e=96), 0, 0, (0, 15)),     # k = 96 is no even number of 32-deep steps: zero padding in every tile
+    ]
+    st = torch.cuda.current_stream()
+    for L, pad, gap, (free, total) in cases:
+        lensA = [L[x] for x in "aeb"]
+        A = workloads.make_tensor("aeb", L, 61, 0, "smallint", strides_for_order(lensA, [0, 1, 2], pad=pad))
+        B = workloads.make_tensor("ecd", L, 62, 1, "smallint", (1, L["e"], L["e"] * (L["c"] + gap)))
+        C = workloads.make_tensor("abcd", L, 63, 2, "smallint")
+        plan = tc.tc_plan(A, B, C, 0, "abc", st, tail_split=-1)
+        fused = [x for x in tc.tc_plan_launches(plan) if x["kind"] == 0]
+        tc.tc_destroy(plan)
+        assert [(x["tiles_table_free"], x["tiles"]) for x in fused] == [(free, total)], (L, pad, gap)
+        for level, variant, kw in ((0, "abc", {}), (0, "abc", {"tail_split": 2}), (1, "abc", {}), (2, "abc", {}), (1, "hybrid", {}), (1, "ab", {})):
+            _check(gpu, A, B, C, 2.0, -1.0, level, variant, exact=True, **kw)
+
+
 def test_automatic_level_and_variant(gpu):
     """TC_LEVEL_AUTO / TC_VARIANT_AUTO: whatever the model picks, the result is the contraction."""
     import paper_1704_03092_amd as tc
