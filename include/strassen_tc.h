@@ -103,7 +103,12 @@ typedef struct {
                      * likes best, possibly none; needs workspace for the chunks (not from the paper);
                      * -1 = never; 2..16 = that many chunks (each a multiple of 64 entries long, so possibly fewer)
                      * in every launch that has a tail, whatever the model says (for tests and measurements) */
-    int reserved[3];
+    int tile_n;     /* tile shape of the launches whose products have single-block operand sums (level 0, and the stored-sum
+                     * variants): 0 = the performance model chooses; 128 = 128 x 128 tiles, one workgroup of 512 threads
+                     * per compute unit; 64 = 128 x 64 tiles, two workgroups of 256 threads per compute unit (for products
+                     * with few k-steps per tile or few tiles: one workgroup's set-up and destination update overlap the
+                     * other's matrix-core work).  Launches with multi-block sums always use 128. */
+    int reserved[2];
 } tc_options_t;
 
 /* Facts about a plan (tc_plan_info). */
@@ -132,9 +137,14 @@ typedef struct {
 
 /* Parameters of the performance model (Sec. 5, notation table): tau_a = 1 / (rho_a * peak_flops),
  * tau_b = 8 / (rho_b * bandwidth).  The arithmetic penalty rho_a depends on how many blocks the larger operand sum
- * of a product has (1, 2, 4: index 0, 1, 2), which is what makes this kernel slower; t_launch is added per kernel
- * launch; the arithmetic term counts whole waves of `units` 128 x 128 tiles, each wave with a fixed cost t_tile
- * (filling and draining a tile's pipeline). */
+ * of a product has (1, 2, 4: index 0, 1, 2), which is what makes this kernel slower; it is multiplied by rho_small
+ * for launches in 128 x 64 tiles and by rho_gather for launches that gather an operand element by element (the
+ * operand has no stride-one index on the side the gather runs along: the model's bandwidth penalty for such operands,
+ * which here shows as matrix cores waiting for the gather).  t_launch is added per kernel launch; the arithmetic term
+ * counts whole waves of tiles (one 128 x 128 tile or two 128 x 64 tiles per compute unit), each wave with a fixed cost
+ * t_tile (gather tables, filling and draining a tile's pipeline).  lambda_ab is the fraction of the operand reads
+ * T_m^{Ax} + T_m^{Bx} (every tile reads its panels of the summed blocks of A and B once) that is not hidden behind
+ * the matrix cores, the counterpart of the model's prefetch efficiency lambda. */
 typedef struct {
     double peak_flops;  /* flop/s of the device */
     double rho_a[3];
@@ -142,8 +152,12 @@ typedef struct {
     double rho_b;
     double t_launch;    /* seconds */
     double t_tile;      /* seconds per wave of tiles */
-    int units;          /* tiles that run at the same time (compute units) */
+    int units;          /* compute units: each runs one 128 x 128 tile, or two 128 x 64 tiles, at a time */
     int reserved[3];
+    double rho_small;    /* 128 x 64 tiles: factor on rho_a */
+    double t_tile_small; /* 128 x 64 tiles: seconds per wave of tiles */
+    double rho_gather;   /* element-by-element gathers: factor on rho_a */
+    double lambda_ab;    /* weight of the operand reads */
 } tc_model_params_t;
 
 /* One kernel launch of the plan's schedule, for inspection (tc_plan_launch). */
@@ -155,15 +169,19 @@ typedef struct {
     int tail_chunks;      /* chunks per tail tile */
     int terms_a, terms_b; /* fused: the kernel family of the launch = blocks in the operand sum of A and of B (1, 2 or 4 each;
                            * 0, 0: the family that counts up to four terms at run time) */
-    int reserved[1];
+    int tile_n;           /* fused: tile columns, 128 or 64 (tiles always have 128 rows) */
     int64_t rows, cols;   /* extents of one product (fused) or of the pass (element-wise) */
     int64_t depth;        /* fused: contracted extent of one product */
-    int64_t tiles;        /* fused: 128 x 128 tiles of the launch */
+    int64_t tiles;        /* fused: 128 x tile_n tiles of the launch */
     int64_t tail_kc;      /* contracted entries per chunk */
     int64_t tiles_table_free; /* fused: tiles gathered by stride, without scatter tables (Sec. 4.1 "Packing": every block
                                * scatter entry of the tile's rows and columns is non-zero in every summed block, the
                                * contracted bundle is one constant-stride run, no zero padding in the tile); the other
                                * tiles of the launch go through the scatter tables */
+    double moved_elems;   /* what the model's memory terms count (Sec. 5, T_m^{Cx} and T_m^{+}): fused: destination elements
+                           * read or written by the updates of all products; element-wise: elements read or written */
+    int pairs_a, pairs_b; /* fused: 1 if the operand is gathered two contiguous elements at a time (it has a stride-one
+                           * index on the side the gather runs along), 0 if element by element */
 } tc_launch_info_t;
 
 /* Modelled time of one tc_contract() with beta != 0, in seconds, split as in Sec. 5 eq. (2)-(4):
@@ -174,6 +192,7 @@ typedef struct {
  * (temporaries) and one more launch. */
 typedef struct {
     double total, arith, c_update, temporaries, launch;
+    double operands; /* T_m^{Ax} + T_m^{Bx}, weighted by lambda_ab (part of total) */
 } tc_model_time_t;
 
 /* Build a plan: classify labels into bundles (Sec. 2.3), choose the order inside each bundle, compute the

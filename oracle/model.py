@@ -2,14 +2,9 @@
 
 Test infrastructure, like the rest of this package: only tests/, the smoke check and the benchmark's CPU leg use it.
 
-Two functions of record:
-
-* ``paper_time``: the model exactly as the paper states it -- equations (1)-(6) of the top table, the operation
-  counts of the middle table, the coefficients of the bottom table, the parameters tau_a, tau_b, rho_a, rho_b,
-  lambda and the block sizes m_C, k_C, n_C.  Pinned in tests/test_oracle_model.py.
-* ``granular_time``: the same sum of terms evaluated for a machine that runs whole tiles in whole waves (the
-  reading used for the GPU: the sub-contraction extents of the middle table are replaced by what the machine
-  executes).  It takes the per-launch tile counts as input; it knows nothing of how a library groups launches.
+``paper_time`` is the model exactly as the paper states it -- equations (1)-(6) of the top table, the operation
+counts of the middle table, the coefficients of the bottom table, the parameters tau_a, tau_b, rho_a, rho_b,
+lambda and the block sizes m_C, k_C, n_C.  Pinned in tests/test_oracle_model.py.
 
 Parity status: paper_time's coefficient table is pinned against counts derived from the Strassen tables
 (themselves pinned by Brent's equations) except the three two-level entries 194, 194 and 293, which do not follow
@@ -92,64 +87,3 @@ def paper_time(m: int, n: int, k: int, level: int, variant: str, p: PaperParams)
 def effective_gflops(m: int, n: int, k: int, seconds: float) -> float:
     """Equation (1): the classical flop count over the time, whatever the algorithm."""
     return 2.0 * m * n * k / seconds * 1e-9
-
-
-@dataclass
-class MachineParams:
-    """The model's parameters for a machine that executes tile_m x tile_n tiles, `units` at a time."""
-    peak_flops: float                 # flop/s of the whole machine
-    rho_a: Sequence[float]            # arithmetic efficiency by the larger number of terms of a product's operand sums: index 1, 2, 4
-    bandwidth: float                  # bytes/s
-    rho_b: float
-    t_launch: float                   # seconds per kernel launch
-    t_tile: float = 0.0               # seconds per wave of tiles (filling and draining a tile's pipeline)
-    units: int = 256
-    tile_m: int = 128
-    tile_n: int = 128
-
-
-def granular_time(launches: Sequence[dict], p: MachineParams) -> Dict[str, float]:
-    """The sum of equation (2) for a list of launches.
-
-    A multiplying launch is {"kind": "mul", "products": [ {"tiles": t, "kb": kb, "terms": max(nA, nB),
-    "c_elems": elements of C (or of a temporary) read or written by its update} ... ]}: the arithmetic term counts
-    whole waves of `units` tiles, each tile 2 * tile_m * tile_n * kb flops at tau_a of its product's efficiency (the
-    products of one launch share an efficiency class) plus t_tile per wave; the update of the destinations is the model's T_m^{C x} with
-    k_C = kb (one update per tile): c_elems * tau_b.  Reading A and B (T_m^{A x}, T_m^{B x}) is taken as hidden behind
-    the matrix cores (weight 0).  An element-wise launch is {"kind": "add", "elems": elements read or written}: the
-    T_m^{+} terms, elems * tau_b.  Every launch costs t_launch.
-
-    A multiplying launch may carry "tail": {"tiles": r, "chunks": s, "kc": kc}: r of its tiles are cut along the
-    contracted bundle into s chunks of kc entries, computed by one unit each and stored; a further launch reads them
-    back and adds them.  The whole tiles then count in whole waves of depth kb, the r * s chunks in whole waves of
-    depth kc, the chunks written and read back are a T_m^{+} term (2 * r * s * tile_m * tile_n elements), and the
-    second launch costs t_launch.
-    """
-    tau_b = 8.0 / (p.rho_b * p.bandwidth)
-    out = {"arith": 0.0, "c_update": 0.0, "temporaries": 0.0, "launch": 0.0}
-    for L in launches:
-        out["launch"] += p.t_launch
-        if L["kind"] == "mul":
-            tiles = sum(q["tiles"] for q in L["products"])
-            if tiles == 0:
-                continue
-            terms = max(q["terms"] for q in L["products"])
-            rho = p.rho_a[0] if terms <= 1 else p.rho_a[1] if terms <= 2 else p.rho_a[2]
-            kb = L["products"][0]["kb"]
-
-            def wave(depth):
-                return p.units * 2.0 * p.tile_m * p.tile_n * depth / (rho * p.peak_flops) + p.t_tile
-
-            tail = L.get("tail")
-            whole = tiles - (tail["tiles"] if tail else 0)
-            out["arith"] += math.ceil(whole / p.units) * wave(kb)
-            if tail:
-                pieces = tail["tiles"] * tail["chunks"]
-                out["arith"] += math.ceil(pieces / p.units) * wave(tail["kc"])
-                out["temporaries"] += 2.0 * pieces * p.tile_m * p.tile_n * tau_b
-                out["launch"] += p.t_launch
-            out["c_update"] += sum(q["c_elems"] for q in L["products"]) * tau_b
-        else:
-            out["temporaries"] += L["elems"] * tau_b
-    out["total"] = out["arith"] + out["c_update"] + out["temporaries"] + out["launch"]
-    return out

@@ -33,7 +33,7 @@ def build(verbose: bool = False) -> str:
     """Compile the HIP library for gfx950 with hipcc (cross-compiles without a GPU); translation units in parallel."""
     from concurrent.futures import ThreadPoolExecutor
 
-    names = ["tc_host.cpp", "tc_device.hip", "tc_fused_11.hip", "tc_fused_12.hip", "tc_fused_21.hip", "tc_fused_22.hip", "tc_fused_14.hip", "tc_fused_41.hip", "tc_fused_24.hip", "tc_fused_42.hip", "tc_fused_44.hip", "tc_fused_any.hip"]
+    names = ["tc_host.cpp", "tc_device.hip", "tc_fused_11.hip", "tc_fused_12.hip", "tc_fused_21.hip", "tc_fused_22.hip", "tc_fused_14.hip", "tc_fused_41.hip", "tc_fused_24.hip", "tc_fused_42.hip", "tc_fused_44.hip", "tc_fused_any.hip", "tc_small_11.hip"]
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objdir = os.path.join(_HERE, "csrc", "_build")
     os.makedirs(objdir, exist_ok=True)
@@ -70,13 +70,14 @@ class tc_tensor_desc_t(ctypes.Structure):
 
 class tc_options_t(ctypes.Structure):
     _fields_ = [("bs_block", ctypes.c_int), ("host_only", ctypes.c_int), ("no_merge", ctypes.c_int), ("split_k", ctypes.c_int),
-                ("tail_split", ctypes.c_int), ("reserved", ctypes.c_int * 3)]
+                ("tail_split", ctypes.c_int), ("tile_n", ctypes.c_int), ("reserved", ctypes.c_int * 2)]
 
 
 class tc_launch_info_t(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int), ("n_products", ctypes.c_int), ("max_terms", ctypes.c_int), ("tail_tiles", ctypes.c_int),
-                ("tail_chunks", ctypes.c_int), ("terms_a", ctypes.c_int), ("terms_b", ctypes.c_int), ("reserved", ctypes.c_int * 1), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
-                ("depth", ctypes.c_int64), ("tiles", ctypes.c_int64), ("tail_kc", ctypes.c_int64), ("tiles_table_free", ctypes.c_int64)]
+                ("tail_chunks", ctypes.c_int), ("terms_a", ctypes.c_int), ("terms_b", ctypes.c_int), ("tile_n", ctypes.c_int), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("depth", ctypes.c_int64), ("tiles", ctypes.c_int64), ("tail_kc", ctypes.c_int64), ("tiles_table_free", ctypes.c_int64),
+                ("moved_elems", ctypes.c_double), ("pairs_a", ctypes.c_int), ("pairs_b", ctypes.c_int)]
 
 
 class tc_plan_info_t(ctypes.Structure):
@@ -95,12 +96,13 @@ class tc_product_t(ctypes.Structure):
 
 class tc_model_params_t(ctypes.Structure):
     _fields_ = [("peak_flops", ctypes.c_double), ("rho_a", ctypes.c_double * 3), ("bandwidth", ctypes.c_double), ("rho_b", ctypes.c_double),
-                ("t_launch", ctypes.c_double), ("t_tile", ctypes.c_double), ("units", ctypes.c_int), ("reserved", ctypes.c_int * 3)]
+                ("t_launch", ctypes.c_double), ("t_tile", ctypes.c_double), ("units", ctypes.c_int), ("reserved", ctypes.c_int * 3),
+                ("rho_small", ctypes.c_double), ("t_tile_small", ctypes.c_double), ("rho_gather", ctypes.c_double), ("lambda_ab", ctypes.c_double)]
 
 
 class tc_model_time_t(ctypes.Structure):
     _fields_ = [("total", ctypes.c_double), ("arith", ctypes.c_double), ("c_update", ctypes.c_double), ("temporaries", ctypes.c_double),
-                ("launch", ctypes.c_double)]
+                ("launch", ctypes.c_double), ("operands", ctypes.c_double)]
 
 
 class tc_launch_times_t(ctypes.Structure):
@@ -204,9 +206,9 @@ class Plan:
 
 
 def tc_plan(A, B, C, level: int = 0, variant="abc", stream=None, bs_block: int = 0, host_only: bool = False,
-            no_merge: bool = False, split_k: int = 0, tail_split: int = 0) -> Plan:
+            no_merge: bool = False, split_k: int = 0, tail_split: int = 0, tile_n: int = 0) -> Plan:
     """A, B, C: (labels, lengths, strides) triples or objects with .idx/.lens/.strides.
-    tail_split: 0 = automatic, -1 = never, 2..16 = forced chunk count (see tc_options_t)."""
+    tail_split: 0 = automatic, -1 = never, 2..16 = forced chunk count; tile_n: 0 = automatic, 64 or 128 (see tc_options_t)."""
     lib = load_library()
     ds = []
     for T in (A, B, C):
@@ -216,7 +218,7 @@ def tc_plan(A, B, C, level: int = 0, variant="abc", stream=None, bs_block: int =
             ds.append(_desc(*T))
     v = VARIANTS[variant] if isinstance(variant, str) else int(variant)
     out = ctypes.c_void_p()
-    opts = tc_options_t(int(bs_block), int(bool(host_only)), int(bool(no_merge)), int(split_k), int(tail_split))
+    opts = tc_options_t(int(bs_block), int(bool(host_only)), int(bool(no_merge)), int(split_k), int(tail_split), int(tile_n))
     rc = lib.tc_plan_ex(ctypes.byref(out), ctypes.byref(ds[0]), ctypes.byref(ds[1]), ctypes.byref(ds[2]), int(level), v,
                         ctypes.byref(opts), _stream(stream))
     if rc != 0:
@@ -297,7 +299,8 @@ def tc_model_defaults() -> dict:
     if rc != 0:
         raise TcError(rc, "tc_model_defaults")
     return {"peak_flops": mp.peak_flops, "rho_a": list(mp.rho_a), "bandwidth": mp.bandwidth, "rho_b": mp.rho_b, "t_launch": mp.t_launch,
-            "t_tile": mp.t_tile, "units": mp.units}
+            "t_tile": mp.t_tile, "units": mp.units, "rho_small": mp.rho_small, "t_tile_small": mp.t_tile_small,
+            "rho_gather": mp.rho_gather, "lambda_ab": mp.lambda_ab}
 
 
 def tc_plan_predict(plan: Plan, params: Optional[dict] = None) -> dict:
@@ -305,7 +308,8 @@ def tc_plan_predict(plan: Plan, params: Optional[dict] = None) -> dict:
     mp = None
     if params is not None:
         mp = tc_model_params_t(params["peak_flops"], (ctypes.c_double * 3)(*params["rho_a"]), params["bandwidth"], params["rho_b"],
-                               params["t_launch"], params["t_tile"], int(params["units"]))
+                               params["t_launch"], params["t_tile"], int(params["units"]), (ctypes.c_int * 3)(),
+                               params["rho_small"], params["t_tile_small"], params["rho_gather"], params["lambda_ab"])
     out = tc_model_time_t()
     rc = load_library().tc_plan_predict(plan.handle, ctypes.byref(mp) if mp is not None else None, ctypes.byref(out))
     if rc != 0:

@@ -11,6 +11,7 @@
 #include <mutex>
 
 #include "tc_fused.h"
+#include "tc_fused_small.h"
 #include "tc_internal.h"
 
 // ---------------------------------------------------------------------------------------------------------
@@ -298,13 +299,27 @@ int launch_planner(const BundleDesc* descs_dev, int nvec, int64_t max_total, int
 int launch_fused(const FusedConfig& cfg, const Product* prods_dev, int first, int count, int64_t mb, int64_t nb, const double* A,
                  const double* B, double* C, double* W, double alpha, double beta, int tail_tiles, int tail_chunks, int64_t tail_kc,
                  int64_t partial_off, void* stream) {
-    const int64_t tiles_m = (mb + fused::TM - 1) / fused::TM, tiles_n = (nb + fused::TN - 1) / fused::TN;
+    const bool small = cfg.tile_n == fused_small::TN;
+    if (!small && cfg.tile_n != fused::TN) return (int)hipErrorInvalidValue;
+    const int64_t tiles_m = (mb + fused::TM - 1) / fused::TM, tiles_n = (nb + cfg.tile_n - 1) / cfg.tile_n;
     if (tiles_m <= 0 || tiles_n <= 0 || tiles_m > (1 << 20) || tiles_n > (1 << 20)) return (int)hipErrorInvalidValue;
     if (tail_tiles < 0 || tail_kc < 0 || tail_kc > 0x7fffffff || (tail_tiles > 0 && !W)) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
     const int vec = (cfg.a_vec ? 1 : 0) | (cfg.b_vec ? 2 : 0);  // pair-wise gathers (pairs are 8-byte aligned)
     const int tm = (int)tiles_m, tn = (int)tiles_n;
-    const fused::TailSplit tail{tail_tiles, tail_chunks, (int)tail_kc, tail_tiles > 0 ? W + partial_off : nullptr};
+    double* partial = tail_tiles > 0 ? W + partial_off : nullptr;
+    const int main_count = (int)((int64_t)count * tm * tn - tail_tiles);
+    if (small) {
+        // the small geometry exists for single-term products only
+        if (cfg.nta != 1 || cfg.ntb != 1) return (int)hipErrorInvalidValue;
+        const fused_small::TailSplit tail{tail_tiles, tail_chunks, (int)tail_kc, partial};
+        const int err = fused_small::launch_family<1, 1, true>(cfg.a_mode, cfg.b_mode, vec, cfg.c_mode, prods_dev, first, count, tm, tn, A, B, C,
+                                                               W, alpha, beta, tail, st);
+        if (err || tail_tiles == 0) return err;
+        return fused_small::launch_tail_fixup(cfg.c_mode == 0, prods_dev, first, tm, tn, main_count, tail_tiles, tail_chunks, partial, C, W,
+                                              alpha, beta, st);
+    }
+    const fused::TailSplit tail{tail_tiles, tail_chunks, (int)tail_kc, partial};
     int err = (int)hipErrorInvalidValue;
 #define TC_FAMILY(NA, NB, EX)                                                                                                             \
     err = fused::launch_family<NA, NB, EX>(cfg.a_mode, cfg.b_mode, vec, cfg.c_mode, prods_dev, first, count, tm, tn, A, B, C, W, alpha, beta, \
@@ -325,14 +340,7 @@ int launch_fused(const FusedConfig& cfg, const Product* prods_dev, int first, in
     }
 #undef TC_FAMILY
     if (err || tail_tiles == 0) return err;
-    const int main_count = (int)((int64_t)count * tm * tn - tail_tiles);
-    if (cfg.c_mode == 0)
-        hipLaunchKernelGGL(fused::tail_fixup_kernel<true>, dim3((unsigned)tail_tiles, fused::FIX_SLICES), dim3(fused::NTHREADS), 0, st, prods_dev, first, tm, tn,
-                           main_count, tail_tiles, tail_chunks, tail.partial, C, W, alpha, beta);
-    else
-        hipLaunchKernelGGL(fused::tail_fixup_kernel<false>, dim3((unsigned)tail_tiles, fused::FIX_SLICES), dim3(fused::NTHREADS), 0, st, prods_dev, first, tm, tn,
-                           main_count, tail_tiles, tail_chunks, tail.partial, C, W, alpha, beta);
-    return (int)hipGetLastError();
+    return fused::launch_tail_fixup(cfg.c_mode == 0, prods_dev, first, tm, tn, main_count, tail_tiles, tail_chunks, partial, C, W, alpha, beta, st);
 }
 
 namespace {

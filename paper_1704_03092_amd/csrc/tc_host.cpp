@@ -276,7 +276,7 @@ void lead_with_plus(Operand& op) {
 int terms_class(int n_a, int n_b) { return (n_a != 3 && n_b != 3) ? 8 * n_a + n_b : 0; }
 
 extern const tc_model_params_t kDefaultModel;
-void choose_tail(const tc_plan_t* p, Step& s, const tc_model_params_t& mp, int forced);
+void choose_tiles(const tc_plan_t* p, Step& s, const tc_model_params_t& mp, int tile_mode, int tail_mode, int64_t* chunk_elems);
 
 int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const tc_tensor_desc_t* C, int level, int variant,
                const tc_options_t* opts, void* stream) {
@@ -287,10 +287,13 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     p->bs_block = 16;
     bool no_merge = false;
     int tail_mode = 0;  // 0: the model decides, -1: never, 2..16: that many chunks wherever a launch has a tail
+    int tile_mode = 0;  // 0: the model decides, 64 / 128: tile columns of the single-term launches
     int split = 1;
     if (opts) {
         if (opts->tail_split < -1 || opts->tail_split == 1 || opts->tail_split > 16) return TC_ERR_STATE;
         tail_mode = opts->tail_split;
+        if (opts->tile_n != 0 && opts->tile_n != 64 && opts->tile_n != 128) return TC_ERR_STATE;
+        tile_mode = opts->tile_n;
         if (opts->bs_block < 0 || opts->bs_block > (1 << 20)) return TC_ERR_STATE;
         if (opts->bs_block > 0) p->bs_block = opts->bs_block;
         p->host_only = opts->host_only != 0;
@@ -529,7 +532,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
                         add_term(mul.A, 0, 0, 1.0);
                         setop(mul.B, V_RSTB, V_CSTB, p->kb, p->nb, 1, p->wsTB);
                         add_term(mul.B, 0, 0, 1.0);
-                        cfg = tc::FusedConfig{0, 1, 1, 1, 1, 1, 1, 1, 0};  // dense temporaries: block extents are multiples of 16
+                        cfg = tc::FusedConfig{0, 1, 1, 1, 1, 1, 1, 1, 0, 128};  // dense temporaries: block extents are multiples of 16
                     } else {
                         cfg.nta = terms_class(q.pr.A.nterms, q.pr.B.nterms) / 8;
                         cfg.ntb = terms_class(q.pr.A.nterms, q.pr.B.nterms) % 8;
@@ -591,7 +594,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
             view.launch = 0;
             p->sched.push_back(view);
         }
-        tc::FusedConfig cfg{p->a_mode, p->b_mode, 1, 1, p->a_vec, p->b_vec, 0, 0, 0};  // temporaries: contiguous rows
+        tc::FusedConfig cfg{p->a_mode, p->b_mode, 1, 1, p->a_vec, p->b_vec, 0, 0, 0, 128};  // temporaries: contiguous rows
         p->steps.push_back(Step{STEP_FUSED, first, split, cfg, p->mb, p->nb, 0, 0});
         Product acc;
         std::memset(&acc, 0, sizeof acc);
@@ -719,7 +722,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
                 list.push_back(e);
             }
             tc::FusedConfig cfg{sa.direct ? p->a_mode : 0, sb.direct ? p->b_mode : 1, 1, 1, sa.direct ? p->a_vec : 1, sb.direct ? p->b_vec : 1,
-                                sa.space, sb.space, p->c_mode};
+                                sa.space, sb.space, p->c_mode, 128};
             emit(list, cfg, true);
         }
     } else {
@@ -761,20 +764,17 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
             if (e.view.n_a == 0 || e.view.n_b == 0 || e.view.n_c == 0) continue;
             list.push_back(e);
         }
-        tc::FusedConfig base_cfg{p->a_mode, p->b_mode, 1, 1, p->a_vec, p->b_vec, 0, 0, p->c_mode};
+        tc::FusedConfig base_cfg{p->a_mode, p->b_mode, 1, 1, p->a_vec, p->b_vec, 0, 0, p->c_mode, 128};
         emit(list, base_cfg, variant == TC_VARIANT_ABC || level == 0);
     }
     p->n_launches = (int)p->steps.size();
-    // ---- tails: launches whose tiles do not fill whole rounds of the compute units ----
-    if (tail_mode >= 0) {
-        int64_t chunks = 0;
-        for (Step& s : p->steps)
-            if (s.kind == STEP_FUSED) {
-                choose_tail(p, s, kDefaultModel, tail_mode);
-                chunks = std::max<int64_t>(chunks, (int64_t)s.tail_tiles * s.tail_chunks);
-            }
+    // ---- tile shape and tails (launches whose tiles do not fill whole rounds of the compute units) ----
+    int64_t chunk_elems = 0;
+    for (Step& s : p->steps)
+        if (s.kind == STEP_FUSED) choose_tiles(p, s, kDefaultModel, tile_mode, tail_mode, &chunk_elems);
+    if (chunk_elems > 0) {
         p->wsPart = (int64_t)(p->workspace_bytes / sizeof(double));
-        p->workspace_bytes += (size_t)chunks * 128 * 128 * sizeof(double);
+        p->workspace_bytes += (size_t)chunk_elems * sizeof(double);
     }
     if (!p->host_only && !p->prods.empty()) {
         if (tc::dev_malloc((void**)&p->prods_dev, sizeof(Product) * p->prods.size())) return TC_ERR_HIP;
@@ -807,23 +807,33 @@ extern const tc_model_params_t kDefaultModel = {
     0.6,                   // element-wise passes and destination updates
     6.0e-6,                // per launch
     5.0e-6,                // per wave of tiles: gather tables, pipeline fill, destination update
-    256, {0, 0, 0}};
+    256, {0, 0, 0},
+    0.97,                  // 128 x 64 tiles: half the reuse of B fragments per wavefront
+    3.2e-6,                // and one workgroup's fill and update partly hidden behind the other's multiplications
+    0.95,                  // element-by-element gathers
+    0.0};                  // operand reads: hidden behind the matrix cores
 
 // What the model needs to know of a fused launch.
 struct FusedShape {
     int64_t tiles, kb;
-    int terms;
+    int terms, tile_n;
     double c_elems;
+    double op_elems;  // elements of A and B that the tiles of the launch read (every tile its panels of every summed block)
+    bool pairs;       // both operands gathered two contiguous elements at a time
 };
 
 FusedShape fused_shape(const tc_plan_t* p, const Step& s) {
-    FusedShape f{0, 0, 1, 0.0};
-    f.tiles = (int64_t)s.count * ((s.rows + 127) / 128) * ((s.cols + 127) / 128);
+    FusedShape f{0, 0, 1, 128, 0.0, 0.0, true};
+    f.tile_n = s.cfg.tile_n;
+    f.pairs = s.cfg.a_vec && s.cfg.b_vec;
+    const int64_t per_prod = ((s.rows + 127) / 128) * ((s.cols + f.tile_n - 1) / f.tile_n);
+    f.tiles = (int64_t)s.count * per_prod;
     for (int i = s.first; i < s.first + s.count; ++i) {
         const Product& q = p->prods[i];
         f.terms = std::max(f.terms, std::max(q.A.nterms, q.B.nterms));
         f.kb = q.kb;
         f.c_elems += (q.overwrite ? 1.0 : 2.0) * q.C.nterms * (double)q.mb * (double)q.nb;
+        f.op_elems += (double)per_prod * (double)q.kb * (128.0 * q.A.nterms + (double)f.tile_n * q.B.nterms);
     }
     return f;
 }
@@ -859,8 +869,9 @@ Run fastest_run(const BundleDesc& b) {
 int64_t count_table_free(const tc_plan_t* p, const Step& s) {
     if (s.kind != STEP_FUSED || !s.cfg.a_vec || !s.cfg.b_vec || s.cfg.nta == 0) return 0;  // pair-wise gathers and exact term counts only
     const int64_t limit = (int64_t)1 << 20;
-    const int KT = (s.cfg.nta <= 2 && s.cfg.ntb <= 2) ? 32 : 16;
-    const int64_t tiles_m = (s.rows + 127) / 128, tiles_n = (s.cols + 127) / 128;
+    const int64_t TN = s.cfg.tile_n;
+    const int KT = (TN == 128 && s.cfg.nta <= 2 && s.cfg.ntb <= 2) ? 32 : 16;
+    const int64_t tiles_m = (s.rows + 127) / 128, tiles_n = (s.cols + TN - 1) / TN;
     const int64_t per_prod = tiles_m * tiles_n, main_count = (int64_t)s.count * per_prod - s.tail_tiles;
     int64_t n = 0;
     for (int pi = 0; pi < s.count; ++pi) {
@@ -875,10 +886,10 @@ int64_t count_table_free(const tc_plan_t* p, const Step& s) {
         };
         const Run ra = run_of(q.A, true), rb = run_of(q.B, false);
         if (ra.stride >= limit || rb.stride >= limit) continue;
-        if ((ra.len != INT64_MAX && (ra.len < 128 || ra.stride <= 0)) || (rb.len != INT64_MAX && (rb.len < 128 || rb.stride <= 0))) continue;
+        if ((ra.len != INT64_MAX && (ra.len < 128 || ra.stride <= 0)) || (rb.len != INT64_MAX && (rb.len < TN || rb.stride <= 0))) continue;
         for (int64_t tm = 0; tm < tiles_m; ++tm)
             for (int64_t tn = 0; tn < tiles_n; ++tn) {
-                const int64_t i0 = tm * 128, j0 = tn * 128;
+                const int64_t i0 = tm * 128, j0 = tn * TN;
                 bool ok = true;
                 int64_t klimit = q.kb;
                 for (int t = 0; t < q.A.nterms && ok; ++t) {
@@ -888,10 +899,10 @@ int64_t count_table_free(const tc_plan_t* p, const Step& s) {
                     if (ok && ra.len != INT64_MAX) ok = f0 % ra.len + 128 <= ra.len;
                 }
                 for (int t = 0; t < q.B.nterms && ok; ++t) {
-                    ok = std::min(q.nb, q.B.cs_len - q.B.coff[t]) - j0 >= 128;
+                    ok = std::min(q.nb, q.B.cs_len - q.B.coff[t]) - j0 >= TN;
                     klimit = std::min(klimit, q.B.rs_len - q.B.roff[t]);
                     const int64_t f0 = q.B.coff[t] + j0;
-                    if (ok && rb.len != INT64_MAX) ok = f0 % rb.len + 128 <= rb.len;
+                    if (ok && rb.len != INT64_MAX) ok = f0 % rb.len + TN <= rb.len;
                 }
                 if (!ok) continue;
                 // no padded k-step: every term reaches the full depth, which is a whole, even number of k-steps
@@ -913,22 +924,29 @@ int64_t count_table_free(const tc_plan_t* p, const Step& s) {
     return n;
 }
 
-// Modelled time of a fused launch except its destination updates: whole tiles in whole waves of `units` tiles, the
-// chunks of the tail tiles in whole waves of their own depth, the chunks written and read back, the second launch.
+// Modelled time of a fused launch except its destination updates: whole tiles in whole waves (one 128 x 128 tile, or
+// two 128 x 64 tiles, per compute unit), the chunks of the tail tiles in whole waves of their own depth, the chunks
+// written and read back, the second launch.
 struct TailCost {
-    double arith, temporaries, launch;
-    double total() const { return arith + temporaries + launch; }
+    double arith, temporaries, launch, operands;
+    double total() const { return arith + temporaries + launch + operands; }
 };
 
+int64_t tiles_per_wave(const tc_model_params_t& mp, int tile_n) { return (int64_t)mp.units * (128 / tile_n); }
+
 TailCost fused_cost(const tc_model_params_t& mp, const FusedShape& f, int64_t tail_tiles, int64_t chunks, int64_t kc) {
-    const double rho = f.terms <= 1 ? mp.rho_a[0] : f.terms <= 2 ? mp.rho_a[1] : mp.rho_a[2];
-    auto wave = [&](int64_t depth) { return mp.units * 2.0 * 128.0 * 128.0 * (double)depth / (rho * mp.peak_flops) + mp.t_tile; };
-    TailCost c{0, 0, mp.t_launch};
+    const bool small = f.tile_n == 64;
+    const double rho = (f.terms <= 1 ? mp.rho_a[0] : f.terms <= 2 ? mp.rho_a[1] : mp.rho_a[2]) * (small ? mp.rho_small : 1.0) *
+                       (f.pairs ? 1.0 : mp.rho_gather);
+    const double fixed = small ? mp.t_tile_small : mp.t_tile;
+    const int64_t per = tiles_per_wave(mp, f.tile_n);
+    auto wave = [&](int64_t depth) { return mp.units * 2.0 * 128.0 * 128.0 * (double)depth / (rho * mp.peak_flops) + fixed; };
+    TailCost c{0, 0, mp.t_launch, mp.lambda_ab * f.op_elems * 8.0 / (mp.rho_b * mp.bandwidth)};
     const int64_t whole = f.tiles - tail_tiles;
-    c.arith = (double)((whole + mp.units - 1) / mp.units) * wave(f.kb);
+    c.arith = (double)((whole + per - 1) / per) * wave(f.kb);
     if (tail_tiles > 0) {
-        c.arith += (double)((tail_tiles * chunks + mp.units - 1) / mp.units) * wave(kc);
-        c.temporaries = 2.0 * (double)(tail_tiles * chunks) * 128.0 * 128.0 * 8.0 / (mp.rho_b * mp.bandwidth);
+        c.arith += (double)((tail_tiles * chunks + per - 1) / per) * wave(kc);
+        c.temporaries = 2.0 * (double)(tail_tiles * chunks) * 128.0 * f.tile_n * 8.0 / (mp.rho_b * mp.bandwidth);
         c.launch += mp.t_launch;  // the second launch
     }
     return c;
@@ -936,14 +954,15 @@ TailCost fused_cost(const tc_model_params_t& mp, const FusedShape& f, int64_t ta
 
 // The tail of a launch: the tiles beyond the last full round of the compute units.  Cut into 2..16 chunks of a
 // multiple of 64 contracted entries if the model says that this is faster than running them whole.
-// forced >= 2: that many chunks whatever the model says.
-void choose_tail(const tc_plan_t* p, Step& s, const tc_model_params_t& mp, int forced) {
+// forced >= 2: that many chunks whatever the model says.  Returns the modelled time of the choice.
+double choose_tail(const tc_plan_t* p, Step& s, const tc_model_params_t& mp, int forced) {
     s.tail_tiles = s.tail_chunks = 0;
     s.tail_kc = 0;
     const FusedShape f = fused_shape(p, s);
-    const int64_t r = f.tiles % mp.units;
-    if (f.tiles <= 0 || r == 0 || f.tiles > 0x7fffffff) return;
+    if (f.tiles <= 0) return 0.0;
     double best = fused_cost(mp, f, 0, 0, 0).total();
+    const int64_t r = f.tiles % tiles_per_wave(mp, f.tile_n);
+    if (forced < 0 || r == 0 || f.tiles > 0x7fffffff) return best;
     for (int64_t want = forced ? forced : 2; want <= (forced ? forced : 16); ++want) {
         const int64_t kc = round_up((f.kb + want - 1) / want, 64);
         const int64_t chunks = (f.kb + kc - 1) / kc;
@@ -956,11 +975,28 @@ void choose_tail(const tc_plan_t* p, Step& s, const tc_model_params_t& mp, int f
             s.tail_kc = kc;
         }
     }
+    return best;
+}
+
+// Tile shape, then tail, of one fused launch.  Launches of single-block products may run in 128 x 64 tiles, two
+// workgroups per compute unit; the model picks the shape with the smaller time (tile_mode 0) or the caller does.
+// *chunk_elems grows to the elements of workspace that the launch's chunks need.
+void choose_tiles(const tc_plan_t* p, Step& s, const tc_model_params_t& mp, int tile_mode, int tail_mode, int64_t* chunk_elems) {
+    const bool may_small = s.cfg.nta == 1 && s.cfg.ntb == 1;
+    s.cfg.tile_n = 128;
+    double t = choose_tail(p, s, mp, tail_mode);
+    if (may_small && tile_mode != 128) {
+        const Step big = s;
+        s.cfg.tile_n = 64;
+        const double ts = choose_tail(p, s, mp, tail_mode);
+        if (tile_mode == 0 && ts >= t) s = big;
+    }
+    *chunk_elems = std::max<int64_t>(*chunk_elems, (int64_t)s.tail_tiles * s.tail_chunks * 128 * s.cfg.tile_n);
 }
 
 void predict(const tc_plan_t* p, const tc_model_params_t& mp, tc_model_time_t* out) {
     const double tau_b = 8.0 / (mp.rho_b * mp.bandwidth);
-    tc_model_time_t t = {0, 0, 0, 0, 0};
+    tc_model_time_t t = {0, 0, 0, 0, 0, 0};
     for (const Step& s : p->steps) {
         if (s.kind == STEP_FUSED) {
             const FusedShape f = fused_shape(p, s);
@@ -972,6 +1008,7 @@ void predict(const tc_plan_t* p, const tc_model_params_t& mp, tc_model_time_t* o
             t.arith += c.arith;
             t.temporaries += c.temporaries;
             t.launch += c.launch;
+            t.operands += c.operands;
             t.c_update += f.c_elems * tau_b;
         } else {
             t.launch += mp.t_launch;
@@ -980,7 +1017,7 @@ void predict(const tc_plan_t* p, const tc_model_params_t& mp, tc_model_time_t* o
             t.temporaries += elems * tau_b;
         }
     }
-    t.total = t.arith + t.c_update + t.temporaries + t.launch;
+    t.total = t.arith + t.c_update + t.temporaries + t.launch + t.operands;
     *out = t;
 }
 
@@ -1259,10 +1296,16 @@ int tc_plan_launch(const tc_plan_t* plan, int index, tc_launch_info_t* out) {
         out->max_terms = f.terms;
         out->terms_a = s.cfg.nta;
         out->terms_b = s.cfg.ntb;
+        out->tile_n = s.cfg.tile_n;
         out->tiles_table_free = count_table_free(plan, s);
         out->depth = f.kb;
         out->tiles = f.tiles;
         out->tail_tiles = s.tail_tiles, out->tail_chunks = s.tail_chunks, out->tail_kc = s.tail_kc;
+        out->moved_elems = f.c_elems;
+        out->pairs_a = s.cfg.a_vec ? 1 : 0, out->pairs_b = s.cfg.b_vec ? 1 : 0;
+    } else {
+        const Product& q = plan->prods[s.first];
+        out->moved_elems = (q.A.nterms + (q.overwrite ? 1.0 : 2.0) * q.C.nterms) * (double)s.rows * (double)s.cols;
     }
     return TC_OK;
 }

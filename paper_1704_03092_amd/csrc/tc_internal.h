@@ -56,6 +56,8 @@ struct FusedConfig {
     int a_vec, b_vec;     // consecutive entry pairs along the lane direction are contiguous and evenly placed
     int a_space, b_space; // 0: caller's tensor, 1: workspace
     int c_mode;           // 0: the destination is contiguous along its rows (free bundle I), 1: along its columns
+    int tile_n;           // tile columns: 128 (512 threads, one workgroup per compute unit) or 64 (256 threads, two per
+                          // compute unit; single-term products only)
 };
 
 // Size of the per-GPU array that stands in for the caller's workspace in tc_contract_static
@@ -84,7 +86,7 @@ int launch_planner(const BundleDesc* descs_dev, int nvec, int64_t max_total, int
 // products [first, first + count) of the device schedule, all with the same extents, in one launch.
 // tail_tiles > 0: the last tail_tiles tiles of the launch are cut along the contracted bundle into tail_chunks chunks
 // of tail_kc entries (a multiple of 64), computed by one workgroup each into W + partial_off (tail_tiles * tail_chunks
-// dense 128 x 128 tiles), and a second kernel adds the chunks and updates the destinations.
+// dense 128 x tile_n tiles), and a second kernel adds the chunks and updates the destinations.
 int launch_fused(const FusedConfig& cfg, const Product* prods_dev, int first, int count, int64_t mb, int64_t nb,
                  const double* A, const double* B, double* C, double* W, double alpha, double beta, int tail_tiles, int tail_chunks,
                  int64_t tail_kc, int64_t partial_off, void* stream);

@@ -30,6 +30,7 @@ def test_library_exports_every_declared_symbol():
 
 def _plan(A, B, C, level=0, variant="abc", **kw):
     kw.setdefault("tail_split", -1)  # the schedules below are those of the paper; the tail split has tests of its own
+    kw.setdefault("tile_n", 128)     # and so has the choice of the tile shape
     return tc.tc_plan(A, B, C, level, variant, host_only=True, **kw)
 
 
@@ -181,80 +182,81 @@ def _gemm_desc(m, n, k):
     return ("ik", (m, k), (1, m)), ("kj", (k, n), (1, k)), ("ij", (m, n), (1, m))
 
 
-def _oracle_prediction(plan, params):
-    """The library's modelled time recomputed by the oracle (oracle.model.granular_time) from the schedule: which
-    products share a launch comes from tc_plan_schedule, everything else from the plan's extents."""
-    import math
+# Model parameters in powers of two, so that the totals below can be worked out by hand: a wave of 16 tiles of
+# 128 x 128 with 512 contracted entries is 16 * 2 * 128 * 128 * 512 = 2^28 flops; rho_a * peak = 2^28, 2^27, 2^26
+# flop/s for one-, two- and four-block sums; rho_b * bandwidth = 2^24 byte/s.
+_HAND = dict(peak_flops=2.0 ** 29, rho_a=[0.5, 0.25, 0.125], bandwidth=2.0 ** 25, rho_b=0.5, t_launch=0.125, t_tile=0.25, units=16,
+             rho_small=0.5, t_tile_small=0.125, rho_gather=0.5, lambda_ab=0.0)
 
+
+@pytest.mark.parametrize("shape,level,variant,opts,want", [
+    # one launch of 64 tiles = 4 waves of 1 s + 0.25 s; C read and written: 2 * 2^20 elements * 8 B = 2^24 B = 1 s
+    ((1024, 1024, 512), 0, "abc", dict(tile_n=128), dict(arith=5.0, c_update=1.0, temporaries=0.0, launch=0.125)),
+    # 128 x 64 tiles: 128 tiles, 32 at a time = 4 waves; the same 2^28 flops per wave at half the rate = 2 s + 0.125 s
+    ((1024, 1024, 512), 0, "abc", dict(tile_n=64), dict(arith=8.5, c_update=1.0, temporaries=0.0, launch=0.125)),
+    # 72 tiles, all of them tail for the 256 units the plan is made for; cut in 2 chunks of 256 entries = 144 pieces =
+    # 9 waves of 16 at 0.5 s + 0.25 s; the pieces written and read back: 2 * 144 * 128 * 128 * 8 B = 2.25 * 2^24 B;
+    # a second launch; C: 2 * 1152 * 1024 * 8 B = 1.125 * 2^24 B
+    ((1152, 1024, 512), 0, "abc", dict(tile_n=128, tail_split=2), dict(arith=6.75, c_update=1.125, temporaries=2.25, launch=0.25)),
+    # one level, sums and updates in the kernel: 7 products of 64 tiles in 4 launches (64 + 3 * 128 tiles = 28 waves),
+    # each launch with a two-block sum: 2 s + 0.25 s per wave; 12 destination blocks read and written
+    ((2048, 2048, 1024), 1, "abc", dict(tile_n=128), dict(arith=63.0, c_update=12.0, temporaries=0.0, launch=0.5)),
+    # AB: 7 launches of 4 waves at 2.25 s; each product written once to M (2^23 B = 0.5 s); 7 passes that read M and
+    # read and write the 12 destination blocks: (7 + 2 * 12) * 2^23 B = 15.5 s; 14 launches
+    ((2048, 2048, 1024), 1, "ab", dict(tile_n=128), dict(arith=63.0, c_update=3.5, temporaries=15.5, launch=1.75)),
+    # Naive: operand sums stored first: per product (blocks + 1) * 2^19 elements on each side, 12 + 7 blocks-plus-one
+    # per side = 38 * 2^22 B = 9.5 s; then single-block products: 28 waves of 1.25 s; M and the C passes as for AB
+    ((2048, 2048, 1024), 1, "naive", dict(tile_n=128), dict(arith=35.0, c_update=3.5, temporaries=25.0, launch=3.5)),
+    # operand reads with weight 1/4: each of the 64 tiles reads a 128 x 512 panel of A and a 512 x 128 panel of B:
+    # 64 * 512 * 256 * 8 B = 2^26 B = 4 s, a quarter of it counted
+    ((1024, 1024, 512), 0, "abc", dict(tile_n=128, lambda_ab=0.25), dict(arith=5.0, c_update=1.0, temporaries=0.0, launch=0.125, operands=1.0)),
+    # the same in 128 x 64 tiles: 128 tiles read 128 + 64 columns and rows of depth 512: 128 * 512 * 192 * 8 B = 6 s
+    ((1024, 1024, 512), 0, "abc", dict(tile_n=64, lambda_ab=0.25), dict(arith=8.5, c_update=1.0, temporaries=0.0, launch=0.125, operands=1.5)),
+    # two-block sums: the seven products have 12 + 12 summed blocks; per tile and block a 128 x 512 panel:
+    # 64 * 24 * 128 * 512 * 8 B = 48 * 2^24 B = 48 s, a quarter counted
+    ((2048, 2048, 1024), 1, "abc", dict(tile_n=128, lambda_ab=0.25), dict(arith=63.0, c_update=12.0, temporaries=0.0, launch=0.5, operands=12.0)),
+    # A without a stride-one index (stored with stride 2 along its rows): gathered element by element, half the rate:
+    # 4 waves of 2 s + 0.25 s
+    ((1024, 1024, 512), 0, "abc", dict(tile_n=128, stride_a=2), dict(arith=9.0, c_update=1.0, temporaries=0.0, launch=0.125)),
+])
+def test_model_prediction_hand_computed(shape, level, variant, opts, want):
+    """Sec. 5 eq. (2)-(4): the modelled time is the sum of the arithmetic term, the destination updates, the operand
+    reads, the temporaries and the launches; whole tiles run in whole waves.  Expected values worked out by hand (see
+    the parameters above)."""
+    opts = dict(opts)
+    params = dict(tc.tc_model_defaults(), **_HAND)
+    params["lambda_ab"] = opts.pop("lambda_ab", 0.0)
+    sa = opts.pop("stride_a", 1)
+    A, B, C = _gemm_desc(*shape)
+    A = (A[0], A[1], (sa, sa * shape[0]))
+    plan = _plan(A, B, C, level=level, variant=variant, **opts)
+    assert all(L["pairs_a"] == (sa == 1) and L["pairs_b"] == 1 for L in tc.tc_plan_launches(plan) if L["kind"] == 0)
+    got = tc.tc_plan_predict(plan, params)
+    tc.tc_destroy(plan)
+    want = dict({"operands": 0.0}, **want)
+    for key, value in want.items():
+        assert got[key] == pytest.approx(value, rel=1e-12, abs=1e-15), (key, got)
+    assert got["total"] == pytest.approx(sum(want.values()), rel=1e-12)
+
+
+def test_model_reduces_to_the_printed_model_for_whole_waves():
+    """With every launch a whole number of waves, no fixed costs and one efficiency for every kernel family, the
+    library's arithmetic and destination-update terms are T_a^x and T_m^{Cx} of the model as printed (Sec. 5 eq. (2)-(4),
+    one-level ABC with k_C equal to the block's contracted extent)."""
+    import oracle
     from oracle import model as M
 
-    info = tc.tc_plan_info(plan)
-    sched = tc.tc_plan_schedule(plan)
-    mb, nb, kb = info["mb"], info["nb"], info["kb"]
-    tiles = math.ceil(mb / 128) * math.ceil(nb / 128)
-    fused_c = info["variant"] == 2 or info["level"] == 0
-    launches = []
-    if info["variant"] == 3 and info["level"] >= 1:
-        hh = 4 if info["level"] == 2 else 1  # second-level blocks per first-level block
-        # first-level operand sums of more than one block are stored (element-wise launches over two-block-square
-        # extents); every multiplying launch holds second-level products with two-term sums at most
-        import oracle
-
-        U1, V1, _ = oracle.strassen_tables(1)
-        by_launch = {}
-        for e in sched:
-            by_launch.setdefault(e["launch"], []).append(e)
-        keys = sorted(by_launch)
-        per_outer = len(keys) // 7  # launches of one first-level product (shapes here have no pruned blocks)
-        for r in range(7):
-            na, nbt = int(np.count_nonzero(U1[r])), int(np.count_nonzero(V1[r]))
-            if na > 1:
-                launches.append({"kind": "add", "elems": (na + 1) * hh * mb * kb})
-            if nbt > 1:
-                launches.append({"kind": "add", "elems": (nbt + 1) * hh * kb * nb})
-            for key in keys[r * per_outer:(r + 1) * per_outer]:
-                launches.append({"kind": "mul", "products": [
-                    {"tiles": tiles, "kb": kb, "terms": 2 if max(len(e["a"]) // na, len(e["b"]) // nbt) > 1 else 1,
-                     "c_elems": 2 * len(e["c"]) * mb * nb} for e in by_launch[key]]})
-    elif fused_c:
-        by_launch = {}
-        for e in sched:
-            by_launch.setdefault(e["launch"], []).append(e)
-        for key in sorted(by_launch):
-            launches.append({"kind": "mul", "products": [
-                {"tiles": tiles, "kb": kb, "terms": max(len(e["a"]), len(e["b"])), "c_elems": 2 * len(e["c"]) * mb * nb} for e in by_launch[key]]})
-    else:
-        for e in sched:
-            na, nbt = len(e["a"]), len(e["b"])
-            if info["variant"] == 0:  # Naive: operand sums to TA, TB, then a single-term product
-                launches.append({"kind": "add", "elems": (na + 1) * mb * kb})
-                launches.append({"kind": "add", "elems": (nbt + 1) * kb * nb})
-                na = nbt = 1
-            launches.append({"kind": "mul", "products": [{"tiles": tiles, "kb": kb, "terms": max(na, nbt), "c_elems": mb * nb}]})
-            launches.append({"kind": "add", "elems": (1 + 2 * len(e["c"])) * mb * nb})
-    mp = M.MachineParams(peak_flops=params["peak_flops"], rho_a=params["rho_a"], bandwidth=params["bandwidth"], rho_b=params["rho_b"],
-                         t_launch=params["t_launch"], t_tile=params["t_tile"], units=params["units"])
-    return M.granular_time(launches, mp)
-
-
-@pytest.mark.parametrize("shape", [(4096, 4096, 4096), (1000, 3000, 520), (16384, 16384, 256), (9216, 96, 4096), (300, 200, 100)])
-def test_model_prediction_matches_the_oracle_model(shape):
-    defaults = tc.tc_model_defaults()
-    other = dict(defaults, peak_flops=50e12, rho_a=[0.9, 0.7, 0.5], bandwidth=3e12, rho_b=0.8, t_launch=1e-5, t_tile=3e-5, units=100)
-    for level in (0, 1, 2):
-        for variant in ("abc", "ab", "naive", "hybrid"):
-            plan = _plan(*_gemm_desc(*shape), level=level, variant=variant)
-            info = tc.tc_plan_info(plan)
-            g = 1 << info["level"]
-            if variant == "hybrid" and info["level"] >= 1 and not all((g - 1) * info[b] < x for b, x in zip(("mb", "nb", "kb"), shape)):
-                tc.tc_destroy(plan)  # the helper below rebuilds the first level without pruned blocks only
-                continue
-            for params in (None, other):
-                got = tc.tc_plan_predict(plan, params)
-                want = _oracle_prediction(plan, params or defaults)
-                for key in ("arith", "c_update", "temporaries", "launch", "total"):
-                    assert got[key] == pytest.approx(want[key], rel=1e-12, abs=1e-18), (shape, level, variant, key)
-            tc.tc_destroy(plan)
+    m = n = 128 * 16  # 2 x 2 blocks of 8 x 8 tiles = one wave of 64 each
+    k = 4096
+    params = dict(tc.tc_model_defaults(), peak_flops=50e12, rho_a=[0.9, 0.9, 0.9], bandwidth=4e12, rho_b=0.5, t_launch=0.0, t_tile=0.0, units=64)
+    plan = _plan(*_gemm_desc(m, n, k), level=1, variant="abc", tile_n=128)
+    got = tc.tc_plan_predict(plan, params)
+    tc.tc_destroy(plan)
+    p = M.PaperParams(50e3, 4e3, rho_a=0.9, rho_b=0.5, lam=1.0, k_c=k, n_c=n)
+    t = M.paper_terms(m, n, k, 1, "abc", p)
+    assert got["arith"] == pytest.approx(t["a_mul"], rel=1e-13)
+    assert got["c_update"] == pytest.approx(t["m_Cx"], rel=1e-13)
+    assert got["total"] == pytest.approx(t["a_mul"] + t["m_Cx"], rel=1e-13)
 
 
 def test_automatic_choice_is_the_argmin_of_the_model():
@@ -352,68 +354,42 @@ def test_split_k_schedule():
     tc.tc_destroy(big)
 
 
-def _launch_cost(L, mp, tail):
-    """Modelled time of one multiplying launch without its destination updates (oracle.model.granular_time)."""
-    from oracle import model as M
-
-    launch = {"kind": "mul", "products": [{"tiles": L["tiles"], "kb": L["depth"], "terms": L["max_terms"], "c_elems": 0}]}
-    if tail:
-        launch["tail"] = tail
-    return M.granular_time([launch], mp)["total"]
-
-
+@pytest.mark.parametrize("tile_n", [128, 64])
 @pytest.mark.parametrize("shape,level,variant", [((36864, 2304, 36864), 1, "abc"), ((36864, 2304, 36864), 1, "hybrid"),
                                                   ((10001, 10001, 10001), 1, "abc"), ((9216, 96, 4096), 0, "abc"),
                                                   ((13824, 13824, 9216), 2, "hybrid"), ((16384, 16384, 16384), 1, "abc"),
                                                   ((256, 256, 256), 0, "abc"), ((3000, 2000, 700), 1, "ab")])
-def test_tail_split_is_the_argmin_of_the_model(shape, level, variant):
-    """Every launch: the tail is what is left after whole rounds of the units; the chunk count is the one with the
-    smallest modelled time among 1 (no split) and the admissible 2..16 (chunks of a multiple of 64 entries; at most
-    1024 chunks), evaluated by the oracle's model; the prediction of the whole plan and the
-    workspace follow."""
-    import math
-
-    from oracle import model as M
-
-    d = tc.tc_model_defaults()
-    mp = M.MachineParams(peak_flops=d["peak_flops"], rho_a=d["rho_a"], bandwidth=d["bandwidth"], rho_b=d["rho_b"], t_launch=d["t_launch"],
-                         t_tile=d["t_tile"], units=d["units"])
-    plain = _plan(*_gemm_desc(*shape), level=level, variant=variant)
-    plan = _plan(*_gemm_desc(*shape), level=level, variant=variant, tail_split=0)
+def test_tail_split_is_the_argmin_of_the_model(shape, level, variant, tile_n):
+    """Every launch: the tail is what is left after whole rounds of the units (one 128 x 128 or two 128 x 64 tiles per
+    unit); the automatic chunk count is no slower, by the library's own model, than no split and than every forced
+    count 2..16 (chunks of a multiple of 64 entries; at most 1024 chunks); the workspace holds the largest launch's chunks."""
+    units = tc.tc_model_defaults()["units"]
+    desc = _gemm_desc(*shape)
+    plain = _plan(*desc, level=level, variant=variant, tile_n=tile_n)
+    plan = _plan(*desc, level=level, variant=variant, tail_split=0, tile_n=tile_n)
     L0, L1 = tc.tc_plan_launches(plain), tc.tc_plan_launches(plan)
     assert len(L0) == len(L1)
-    extra_t = extra_l = extra_a = 0.0
     most = 0
     for a, b in zip(L0, L1):
         assert {k: v for k, v in a.items() if not k.startswith("tail")} == {k: v for k, v in b.items() if not k.startswith("tail")}
         assert a["tail_tiles"] == 0
-        if b["kind"] == 1:
+        if b["kind"] == 1 or b["tail_tiles"] == 0:
             assert b["tail_tiles"] == 0
             continue
-        r = b["tiles"] % mp.units
-        options = {None: _launch_cost(b, mp, None)}
-        if r:
-            for want in range(2, 17):
-                kc = -(-(-(-b["depth"] // want)) // 64) * 64
-                chunks = -(-b["depth"] // kc)
-                if chunks < 2 or r * chunks > 1024:
-                    continue
-                options[(r, chunks, kc)] = _launch_cost(b, mp, {"tiles": r, "chunks": chunks, "kc": kc})
-        best = min(options.values())
-        got = (b["tail_tiles"], b["tail_chunks"], b["tail_kc"]) if b["tail_tiles"] else None
-        assert got in options and options[got] == best, (b, options)
-        if got:
-            assert (b["tail_chunks"] - 1) * b["tail_kc"] < b["depth"] <= b["tail_chunks"] * b["tail_kc"]
-            most = max(most, r * b["tail_chunks"])
-            extra_l += mp.t_launch
-            extra_t += 2.0 * r * b["tail_chunks"] * 128 * 128 * 8 / (mp.rho_b * mp.bandwidth)
-            extra_a += options[got] - options[None] - mp.t_launch - 2.0 * r * b["tail_chunks"] * 128 * 128 * 8 / (mp.rho_b * mp.bandwidth)
-    t0, t1 = tc.tc_plan_predict(plain), tc.tc_plan_predict(plan)
-    assert t1["launch"] == pytest.approx(t0["launch"] + extra_l, rel=1e-12)
-    assert t1["temporaries"] == pytest.approx(t0["temporaries"] + extra_t, rel=1e-12, abs=1e-18)
-    assert t1["arith"] == pytest.approx(t0["arith"] + extra_a, rel=1e-9)
-    assert t1["c_update"] == t0["c_update"] and t1["total"] <= t0["total"]
-    assert tc.tc_plan_workspace_bytes(plan) == tc.tc_plan_workspace_bytes(plain) + most * 128 * 128 * 8
+        assert b["tail_tiles"] == b["tiles"] % (units * (128 // b["tile_n"]))
+        assert b["tail_kc"] % 64 == 0 and 2 <= b["tail_chunks"] <= 16 and b["tail_tiles"] * b["tail_chunks"] <= 1024
+        assert (b["tail_chunks"] - 1) * b["tail_kc"] < b["depth"] <= b["tail_chunks"] * b["tail_kc"]
+        most = max(most, b["tail_tiles"] * b["tail_chunks"] * 128 * b["tile_n"])
+    best = tc.tc_plan_predict(plan)["total"]
+    others = [tc.tc_plan_predict(plain)["total"]]
+    for forced in range(2, 17):
+        alt = _plan(*desc, level=level, variant=variant, tail_split=forced, tile_n=tile_n)
+        others.append(tc.tc_plan_predict(alt)["total"])
+        tc.tc_destroy(alt)
+    assert best <= min(others) * (1 + 1e-12), (best, others)
+    if len([L for L in L1 if L["kind"] == 0]) == 1:  # one multiplying launch: the automatic choice is one of the forced ones
+        assert any(best == pytest.approx(o, rel=1e-12) for o in others)
+    assert tc.tc_plan_workspace_bytes(plan) == tc.tc_plan_workspace_bytes(plain) + most * 8
     tc.tc_destroy(plain)
     tc.tc_destroy(plan)
 

@@ -193,11 +193,12 @@ def test_tiles_gathered_by_stride_next_to_tiles_through_the_tables(gpu):
         A = workloads.make_tensor("aeb", L, 61, 0, "smallint", strides_for_order(lensA, [0, 1, 2], pad=pad))
         B = workloads.make_tensor("ecd", L, 62, 1, "smallint", (1, L["e"], L["e"] * (L["c"] + gap)))
         C = workloads.make_tensor("abcd", L, 63, 2, "smallint")
-        plan = tc.tc_plan(A, B, C, 0, "abc", st, tail_split=-1)
+        plan = tc.tc_plan(A, B, C, 0, "abc", st, tail_split=-1, tile_n=128)
         fused = [x for x in tc.tc_plan_launches(plan) if x["kind"] == 0]
         tc.tc_destroy(plan)
         assert [(x["tiles_table_free"], x["tiles"]) for x in fused] == [(free, total)], (L, pad, gap)
-        for level, variant, kw in ((0, "abc", {}), (0, "abc", {"tail_split": 2}), (1, "abc", {}), (2, "abc", {}), (1, "hybrid", {}), (1, "ab", {})):
+        for level, variant, kw in ((0, "abc", {"tile_n": 128}), (0, "abc", {"tile_n": 64}), (0, "abc", {"tail_split": 2}), (1, "abc", {}), (2, "abc", {}),
+                                   (1, "hybrid", {}), (1, "ab", {})):
             _check(gpu, A, B, C, 2.0, -1.0, level, variant, exact=True, **kw)
 
 
@@ -282,6 +283,71 @@ def test_tail_split_whole_and_split_tiles_together(gpu):
         A, B, C = _random_midsize_case(rng, kind)
         level, variant = MODES[trial % len(MODES)]
         _check(gpu, A, B, C, rng.choice([1.0, -2.0]), rng.choice([0.0, 1.0, 3.0]), level, variant, exact=bool(trial % 2), tail_split=rng.choice([2, 3, 7]))
+
+
+@pytest.mark.parametrize("tile_n", [64, 128])
+def test_both_tile_shapes_of_single_block_products(gpu, tile_n):
+    """Products with single-block operand sums (level 0, Naive, the stored-sum variant at one level) run in 128 x 128
+    or in 128 x 64 tiles.  Both shapes forced in turn: ragged GEMMs in the four gather directions and both
+    destination orders, padded leading dimensions, random general-stride contractions, forced and automatic tail
+    splits with whole and split tiles in one launch, the tiles gathered by stride next to those through the tables,
+    beta = 0 over NaN.  Launches with multi-block sums keep 128 columns."""
+    import paper_1704_03092_amd as tc
+
+    run_gpu, logical = gpu
+    for idxA, idxB, idxC in (("ik", "kj", "ij"), ("ki", "jk", "ji"), ("ki", "kj", "ij"), ("ik", "jk", "ji")):
+        for (m, n, k), pad, kind in (((672, 608, 704), 0, "uniform"), ((645, 583, 657), 1, "smallint"), ((130, 65, 48), 0, "smallint"),
+                                     ((128, 64, 32), 0, "smallint"), ((1, 1, 1), 0, "uniform")):
+            lengths = {"i": m, "j": n, "k": k}
+            tens = []
+            for tid, idx in enumerate((idxA, idxB, idxC)):
+                lens = [lengths[c] for c in idx]
+                tens.append(workloads.make_tensor(idx, lengths, 11 + tid, tid, kind, strides_for_order(lens, list(range(len(idx))), pad=pad)))
+            A, B, C = tens
+            for level, variant, kw in ((0, "abc", {}), (0, "abc", {"tail_split": 3}), (1, "naive", {}), (1, "hybrid", {"tail_split": 2}), (2, "naive", {}),
+                                       (1, "abc", {})):
+                _check(gpu, A, B, C, 1.5, 0.5, level, variant, exact=(kind == "smallint"), tile_n=tile_n, **kw)
+    # what the plan reports
+    st = __import__("torch").cuda.current_stream()
+    for level, variant in ((0, "abc"), (1, "hybrid"), (1, "abc")):
+        plan = tc.tc_plan(A, B, C, level, variant, st, tile_n=tile_n)
+        for L in tc.tc_plan_launches(plan):
+            if L["kind"] == 0:
+                assert L["tile_n"] == (tile_n if (L["terms_a"], L["terms_b"]) == (1, 1) else 128), L
+        tc.tc_destroy(plan)
+    # more tiles than one round: whole and split tiles in one launch; beta = 0 on a NaN-filled C
+    c = workloads.Contraction("g", "ij", "ik", "kj", {"i": 2500, "j": 1850, "k": 900}, seed=21)
+    A, B, C = c.tensors()
+    for level, variant, chunks in ((0, "abc", 2), (0, "abc", 0), (0, "abc", -1), (1, "hybrid", 3), (1, "naive", 0)):
+        _check(gpu, A, B, C, -1.0, 2.0, level, variant, tail_split=chunks, tile_n=tile_n)
+    Ai, Bi, Ci = c.tensors(kind="smallint")
+    _check(gpu, Ai, Bi, Ci, 2.0, -1.0, 0, "abc", exact=True, tail_split=3, tile_n=tile_n)
+    C.data[:] = np.nan
+    got_flat, _ = run_gpu(A, B, C, 1.5, 0.0, 0, "abc", tail_split=3, tile_n=tile_n)
+    ref = from_dense("ij", np.zeros((2500, 1850)))
+    oracle.contract_matrix(A, B, ref, 1.5, 0.0)
+    assert oracle.error_metric(logical(C, got_flat), ref.view(), oracle.tensor_norm(A), oracle.tensor_norm(B)) <= TOL[0]
+    # general strides
+    rng = random.Random(640 + tile_n)
+    for trial in range(24):
+        kind = "smallint" if trial % 2 else "uniform"
+        A, B, C = _random_midsize_case(rng, kind)
+        level, variant = ((0, "abc"), (1, "naive"), (1, "hybrid"), (2, "hybrid"))[trial % 4]
+        _check(gpu, A, B, C, rng.choice([1.0, -2.0]), rng.choice([0.0, 1.0, 3.0]), level, variant, exact=bool(trial % 2),
+               tail_split=rng.choice([0, 0, 2, 5]), tile_n=tile_n)
+    # tiles gathered by stride (rows a + 128 b: every tile of A regular) and the rank-k shape at reduced extents
+    L = dict(a=128, b=3, c=64, d=5, e=96)
+    cm = lambda idx: strides_for_order([L[x] for x in idx], list(range(len(idx))), pad=0)
+    A = workloads.make_tensor("aeb", L, 3, 0, "smallint", cm("aeb"))
+    B = workloads.make_tensor("ecd", L, 3, 1, "smallint", cm("ecd"))
+    C = workloads.make_tensor("abcd", L, 3, 2, "smallint", cm("abcd"))
+    plan = tc.tc_plan(A, B, C, 0, "abc", st, tail_split=-1, tile_n=tile_n)
+    (launch,) = [x for x in tc.tc_plan_launches(plan) if x["kind"] == 0]
+    tc.tc_destroy(plan)
+    # 384 x 320 x 96: with 64 columns every tile is whole and 96 is a whole, even number of its k-steps of 16
+    assert (launch["tiles"], launch["tiles_table_free"]) == ((15, 15) if tile_n == 64 else (9, 0))
+    for kw in ({}, {"tail_split": 3}):
+        _check(gpu, A, B, C, 1.0, 1.0, 0, "abc", exact=True, tile_n=tile_n, **kw)
 
 
 def test_column_stride_beyond_the_table_free_limit(gpu):

@@ -80,20 +80,3 @@ def test_shape_claims_read_off_the_model(lam):
     for L in (1, 2):
         k = 2 ** L * p.k_c
         assert gf(m, n, k, L, "abc") > max(gf(m, n, k, L, "ab"), gf(m, n, k, L, "naive"))
-
-
-def test_granular_time_is_the_same_sum_for_whole_waves():
-    """With every launch a whole number of waves and rho, tau as in the paper form, the granular evaluation equals
-    the arithmetic and C-update terms of the printed model."""
-    mp = M.MachineParams(peak_flops=50e12, rho_a=(0.9, 0.9, 0.9), bandwidth=4e12, rho_b=0.5, t_launch=0.0, units=64)
-    m = n = 128 * 16  # 2 x 2 blocks of 8 x 8 tiles = one wave of 64 each
-    k = 4096
-    U, V, W = oracle.strassen_tables(1)
-    launches = [{"kind": "mul", "products": [{"tiles": 64, "kb": k // 2, "terms": max(np.count_nonzero(U[r]), np.count_nonzero(V[r])),
-                                             "c_elems": 2 * np.count_nonzero(W[r]) * (m // 2) * (n // 2)}]} for r in range(7)]
-    got = M.granular_time(launches, mp)
-    p = M.PaperParams(50e3, 4e3, rho_a=0.9, rho_b=0.5, lam=1.0, k_c=k, n_c=n)
-    t = M.paper_terms(m, n, k, 1, "abc", p)
-    assert got["arith"] == pytest.approx(t["a_mul"], rel=1e-13)
-    assert got["c_update"] == pytest.approx(t["m_Cx"], rel=1e-13)
-    assert got["total"] == pytest.approx(t["a_mul"] + t["m_Cx"], rel=1e-13)
