@@ -137,7 +137,9 @@ typedef struct {
 
 /* Parameters of the performance model (Sec. 5, notation table): tau_a = 1 / (rho_a * peak_flops),
  * tau_b = 8 / (rho_b * bandwidth).  The arithmetic penalty rho_a depends on how many blocks the larger operand sum
- * of a product has (1, 2, 4: index 0, 1, 2), which is what makes this kernel slower; it is multiplied by rho_small
+ * of a product has (1, 2, 4: index 0, 1, 2), which is what makes this kernel slower; rho_a holds for the tiles gathered
+ * by stride, rho_table for the tiles gathered through the scatter tables (general layouts: the fraction of each kind
+ * in a launch is what tc_launch_info_t.tiles_table_free reports); both are multiplied by rho_small
  * for launches in 128 x 64 tiles and by rho_gather for launches that gather an operand element by element (the
  * operand has no stride-one index on the side the gather runs along: the model's bandwidth penalty for such operands,
  * which here shows as matrix cores waiting for the gather).  t_launch is added per kernel launch; the arithmetic term
@@ -158,6 +160,7 @@ typedef struct {
     double t_tile_small; /* 128 x 64 tiles: seconds per wave of tiles */
     double rho_gather;   /* element-by-element gathers: factor on rho_a */
     double lambda_ab;    /* weight of the operand reads */
+    double rho_table[3]; /* as rho_a, for tiles gathered through the scatter tables */
 } tc_model_params_t;
 
 /* One kernel launch of the plan's schedule, for inspection (tc_plan_launch). */

@@ -921,9 +921,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     constexpr int64_t kStrideLimit = (int64_t)1 << 20;  // keeps the per-lane and per-load byte offsets within 31 bits
     bool affine = false;
     if constexpr (VA && VB && CF::EXACT) {
-        // (computed addresses of missing rows would leave the operand; a tile with padded k-steps needs the tables
-        // for them, and the table-free loop does not keep them up to date)
-        if (whole && st.all_fast && P.A.cs_stride >= 0 && P.B.rs_stride >= 0 && P.A.cs_stride < kStrideLimit && P.B.rs_stride < kStrideLimit) {
+        // (computed addresses of missing rows would leave the operand.)  A tile whose last k-steps are padded takes
+        // the table-free loop for the k-steps before them, if there are any, and the tables for the rest.
+        if (whole && (st.all_fast || st.kfull - D >= 2) && P.A.cs_stride >= 0 && P.B.rs_stride >= 0 && P.A.cs_stride < kStrideLimit && P.B.rs_stride < kStrideLimit) {
             int64_t sxA = P.A.rs_stride, sxB = P.B.cs_stride;
             int64_t fA[NTA], fB[NTB];
             bool ok = true;
@@ -1111,6 +1111,15 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
                 st.template run_fast<1, false>(nfast, affine);
         }
         if constexpr (D == 2) st.issued_fast[SETS - 1] = true;  // the gather of k-step nfast + 1 is in flight (issued unchecked)
+        if constexpr (VA && VB && CF::EXACT && KT == 32) {
+            // the table-free loop of these families fetches no scatter entries: those of the first k-step that the
+            // loop below gathers (nfast + 2; the gather of nfast + 1 is in flight) are fetched here
+            if (affine && !st.all_fast) {
+                const int kn = (nfast + 2) * KT;
+                st.ent_dst[0] = kn < st.ent_limit ? 8 * st.ent_ptr[kn] : kSentinel;
+                __syncthreads();
+            }
+        }
     }
     st.run_checked(nfast);
 

@@ -40,6 +40,7 @@ struct Step {
     // STEP_FUSED: the last tail_tiles tiles are cut into tail_chunks chunks of tail_kc contracted entries (0: none)
     int tail_tiles = 0, tail_chunks = 0;
     int64_t tail_kc = 0;
+    double free_frac = 0.0;  // STEP_FUSED: share of the tiles gathered by stride (what the model prices; tails not looked at)
 };
 
 // vector ids inside the plan's store
@@ -277,6 +278,7 @@ int terms_class(int n_a, int n_b) { return (n_a != 3 && n_b != 3) ? 8 * n_a + n_
 
 extern const tc_model_params_t kDefaultModel;
 void choose_tiles(const tc_plan_t* p, Step& s, const tc_model_params_t& mp, int tile_mode, int tail_mode, int64_t* chunk_elems);
+int64_t count_table_free(const tc_plan_t* p, const Step& s);
 
 int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* B, const tc_tensor_desc_t* C, int level, int variant,
                const tc_options_t* opts, void* stream) {
@@ -799,19 +801,21 @@ void copy_labels(char* out, const std::vector<Dim>& b) {
 }
 
 // ---- performance model (Sec. 5) on the plan's schedule ----
-// Defaults fitted to the measured grid of paper_1704_03092_amd/sweep.py on one MI355X (RMS error of log time 6 %).
+// Defaults: python -m paper_1704_03092_amd.sweep --fit on one MI355X (every launch of six plans of each shape of the
+// grid; launches of a millisecond and more are reproduced to 5 - 8 % RMS).
 extern const tc_model_params_t kDefaultModel = {
     78.6e12,               // published FP64 matrix peak
-    {0.90, 0.80, 0.66},    // fused kernel with 1 / 2 / 4-term operand sums
+    {0.953, 0.930, 0.806}, // tiles gathered by stride, 1 / 2 / 4-term operand sums
     8.0e12,                // HBM3E
-    0.6,                   // element-wise passes and destination updates
-    6.0e-6,                // per launch
-    5.0e-6,                // per wave of tiles: gather tables, pipeline fill, destination update
+    0.736,                 // element-wise passes and destination updates
+    12.3e-6,               // per launch (the fixed part of a kernel's duration)
+    11.2e-6,               // per wave of tiles: gather tables, pipeline fill, destination update
     256, {0, 0, 0},
-    0.97,                  // 128 x 64 tiles: half the reuse of B fragments per wavefront
-    3.2e-6,                // and one workgroup's fill and update partly hidden behind the other's multiplications
-    0.95,                  // element-by-element gathers
-    0.0};                  // operand reads: hidden behind the matrix cores
+    0.994,                 // 128 x 64 tiles
+    4.82e-6,               // and one workgroup's fill and update partly hidden behind the other's multiplications
+    0.775,                 // element-by-element gathers
+    0.066,                 // operand reads not hidden behind the matrix cores
+    {0.880, 0.831, 0.606}};  // tiles gathered through the scatter tables   // tiles gathered through the scatter tables
 
 // What the model needs to know of a fused launch.
 struct FusedShape {
@@ -820,10 +824,11 @@ struct FusedShape {
     double c_elems;
     double op_elems;  // elements of A and B that the tiles of the launch read (every tile its panels of every summed block)
     bool pairs;       // both operands gathered two contiguous elements at a time
+    double free_frac; // share of the tiles gathered by stride
 };
 
 FusedShape fused_shape(const tc_plan_t* p, const Step& s) {
-    FusedShape f{0, 0, 1, 128, 0.0, 0.0, true};
+    FusedShape f{0, 0, 1, 128, 0.0, 0.0, true, s.free_frac};
     f.tile_n = s.cfg.tile_n;
     f.pairs = s.cfg.a_vec && s.cfg.b_vec;
     const int64_t per_prod = ((s.rows + 127) / 128) * ((s.cols + f.tile_n - 1) / f.tile_n);
@@ -905,8 +910,9 @@ int64_t count_table_free(const tc_plan_t* p, const Step& s) {
                     if (ok && rb.len != INT64_MAX) ok = f0 % rb.len + TN <= rb.len;
                 }
                 if (!ok) continue;
-                // no padded k-step: every term reaches the full depth, which is a whole, even number of k-steps
-                auto depth_ok = [&](int64_t depth, int64_t real) { return real == depth && depth % (2 * KT) == 0; };
+                // either no padded k-step (every term reaches the full depth, which is a whole, even number of
+                // k-steps), or at least four whole k-steps ahead of the padded ones (those then go through the tables)
+                auto depth_ok = [&](int64_t depth, int64_t real) { return (real == depth && depth % (2 * KT) == 0) || real / KT >= 4; };
                 // position of the tile in the launch: the last tail_tiles logical ids are cut into chunks
                 const int64_t gsz = 8 * tiles_n, grp = tm / 8, gm0 = grp * 8, gh = std::min<int64_t>(8, tiles_m - gm0);
                 const int64_t lid = (int64_t)pi * per_prod + grp * gsz + tn * gh + (tm - gm0);
@@ -936,7 +942,8 @@ int64_t tiles_per_wave(const tc_model_params_t& mp, int tile_n) { return (int64_
 
 TailCost fused_cost(const tc_model_params_t& mp, const FusedShape& f, int64_t tail_tiles, int64_t chunks, int64_t kc) {
     const bool small = f.tile_n == 64;
-    const double rho = (f.terms <= 1 ? mp.rho_a[0] : f.terms <= 2 ? mp.rho_a[1] : mp.rho_a[2]) * (small ? mp.rho_small : 1.0) *
+    const int cls = f.terms <= 1 ? 0 : f.terms <= 2 ? 1 : 2;
+    const double rho = 1.0 / (f.free_frac / mp.rho_a[cls] + (1.0 - f.free_frac) / mp.rho_table[cls]) * (small ? mp.rho_small : 1.0) *
                        (f.pairs ? 1.0 : mp.rho_gather);
     const double fixed = small ? mp.t_tile_small : mp.t_tile;
     const int64_t per = tiles_per_wave(mp, f.tile_n);
@@ -983,12 +990,17 @@ double choose_tail(const tc_plan_t* p, Step& s, const tc_model_params_t& mp, int
 // *chunk_elems grows to the elements of workspace that the launch's chunks need.
 void choose_tiles(const tc_plan_t* p, Step& s, const tc_model_params_t& mp, int tile_mode, int tail_mode, int64_t* chunk_elems) {
     const bool may_small = s.cfg.nta == 1 && s.cfg.ntb == 1;
-    s.cfg.tile_n = 128;
-    double t = choose_tail(p, s, mp, tail_mode);
+    auto with_tiles = [&](int tile_n) {
+        s.cfg.tile_n = tile_n;
+        s.tail_tiles = s.tail_chunks = 0;
+        const int64_t tiles = (int64_t)s.count * ((s.rows + 127) / 128) * ((s.cols + tile_n - 1) / tile_n);
+        s.free_frac = tiles > 0 ? (double)count_table_free(p, s) / (double)tiles : 0.0;
+        return choose_tail(p, s, mp, tail_mode);
+    };
+    const double t = with_tiles(128);
     if (may_small && tile_mode != 128) {
         const Step big = s;
-        s.cfg.tile_n = 64;
-        const double ts = choose_tail(p, s, mp, tail_mode);
+        const double ts = with_tiles(64);
         if (tile_mode == 0 && ts >= t) s = big;
     }
     *chunk_elems = std::max<int64_t>(*chunk_elems, (int64_t)s.tail_tiles * s.tail_chunks * 128 * s.cfg.tile_n);

@@ -186,7 +186,7 @@ def _gemm_desc(m, n, k):
 # 128 x 128 with 512 contracted entries is 16 * 2 * 128 * 128 * 512 = 2^28 flops; rho_a * peak = 2^28, 2^27, 2^26
 # flop/s for one-, two- and four-block sums; rho_b * bandwidth = 2^24 byte/s.
 _HAND = dict(peak_flops=2.0 ** 29, rho_a=[0.5, 0.25, 0.125], bandwidth=2.0 ** 25, rho_b=0.5, t_launch=0.125, t_tile=0.25, units=16,
-             rho_small=0.5, t_tile_small=0.125, rho_gather=0.5, lambda_ab=0.0)
+             rho_small=0.5, t_tile_small=0.125, rho_gather=0.5, lambda_ab=0.0, rho_table=[0.5, 0.25, 0.125])
 
 
 @pytest.mark.parametrize("shape,level,variant,opts,want", [
@@ -218,6 +218,9 @@ _HAND = dict(peak_flops=2.0 ** 29, rho_a=[0.5, 0.25, 0.125], bandwidth=2.0 ** 25
     # A without a stride-one index (stored with stride 2 along its rows): gathered element by element, half the rate:
     # 4 waves of 2 s + 0.25 s
     ((1024, 1024, 512), 0, "abc", dict(tile_n=128, stride_a=2), dict(arith=9.0, c_update=1.0, temporaries=0.0, launch=0.125)),
+    # 1000 rows: the 8 tiles of the last tile row are ragged and go through the scatter tables at half the rate of the
+    # 56 others: 1 / rho = (7/8) / 0.5 + (1/8) / 0.25 = 2.25, a wave takes 2.25 * 2^28 / 2^29 s + 0.25 s; C: 2 * 1000 * 1024 * 8 B
+    ((1000, 1024, 512), 0, "abc", dict(tile_n=128, rho_table=[0.25, 0.25, 0.25]), dict(arith=5.5, c_update=0.9765625, temporaries=0.0, launch=0.125)),
 ])
 def test_model_prediction_hand_computed(shape, level, variant, opts, want):
     """Sec. 5 eq. (2)-(4): the modelled time is the sum of the arithmetic term, the destination updates, the operand
@@ -226,6 +229,7 @@ def test_model_prediction_hand_computed(shape, level, variant, opts, want):
     opts = dict(opts)
     params = dict(tc.tc_model_defaults(), **_HAND)
     params["lambda_ab"] = opts.pop("lambda_ab", 0.0)
+    params["rho_table"] = opts.pop("rho_table", params["rho_table"])
     sa = opts.pop("stride_a", 1)
     A, B, C = _gemm_desc(*shape)
     A = (A[0], A[1], (sa, sa * shape[0]))
@@ -242,21 +246,25 @@ def test_model_prediction_hand_computed(shape, level, variant, opts, want):
 def test_model_reduces_to_the_printed_model_for_whole_waves():
     """With every launch a whole number of waves, no fixed costs and one efficiency for every kernel family, the
     library's arithmetic and destination-update terms are T_a^x and T_m^{Cx} of the model as printed (Sec. 5 eq. (2)-(4),
-    one-level ABC with k_C equal to the block's contracted extent)."""
+    one-level ABC with k_C equal to the block's contracted extent).  Its operand term with weight 1 is the printed
+    T_m^{Ax} with n_C = 128 (every tile of 128 columns reads its panel of A) plus the printed T_m^{Bx} once per tile
+    row (the printed model packs B once; here every tile of 128 rows reads its panel of B)."""
     import oracle
     from oracle import model as M
 
     m = n = 128 * 16  # 2 x 2 blocks of 8 x 8 tiles = one wave of 64 each
     k = 4096
-    params = dict(tc.tc_model_defaults(), peak_flops=50e12, rho_a=[0.9, 0.9, 0.9], bandwidth=4e12, rho_b=0.5, t_launch=0.0, t_tile=0.0, units=64)
+    params = dict(tc.tc_model_defaults(), peak_flops=50e12, rho_a=[0.9, 0.9, 0.9], rho_table=[0.9, 0.9, 0.9], bandwidth=4e12, rho_b=0.5, t_launch=0.0,
+                  t_tile=0.0, units=64, lambda_ab=1.0)
     plan = _plan(*_gemm_desc(m, n, k), level=1, variant="abc", tile_n=128)
     got = tc.tc_plan_predict(plan, params)
     tc.tc_destroy(plan)
-    p = M.PaperParams(50e3, 4e3, rho_a=0.9, rho_b=0.5, lam=1.0, k_c=k, n_c=n)
+    p = M.PaperParams(50e3, 4e3, rho_a=0.9, rho_b=0.5, lam=1.0, k_c=k, n_c=128)
     t = M.paper_terms(m, n, k, 1, "abc", p)
     assert got["arith"] == pytest.approx(t["a_mul"], rel=1e-13)
     assert got["c_update"] == pytest.approx(t["m_Cx"], rel=1e-13)
-    assert got["total"] == pytest.approx(t["a_mul"] + t["m_Cx"], rel=1e-13)
+    assert got["operands"] == pytest.approx(t["m_Ax"] + t["m_Bx"] * (m // 2 // 128), rel=1e-13)
+    assert got["total"] == pytest.approx(t["a_mul"] + t["m_Cx"] + got["operands"], rel=1e-13)
 
 
 def test_automatic_choice_is_the_argmin_of_the_model():
@@ -289,8 +297,9 @@ def test_automatic_choice_is_the_argmin_of_the_model():
 
 def test_launch_info_counts_tiles_gathered_by_stride():
     """Sec. 4.1 "Packing": a tile is gathered by stride iff every block scatter entry of its rows and columns is
-    non-zero in every summed block (here also: the contracted bundle is one run, no zero padding in the tile, pairs of
-    entries contiguous).  tc_plan_launch reports how many tiles of each launch that is."""
+    non-zero in every summed block (here also: the contracted bundle is one run, no missing row or column in the tile,
+    at least four k-steps without zero padding, pairs of entries contiguous).  tc_plan_launch reports how many tiles
+    of each launch that is."""
     def launches(A, B, C, level=0, variant="abc", **kw):
         p = _plan(A, B, C, level=level, variant=variant, **kw)
         out = [(L["tiles"], L["tiles_table_free"]) for L in tc.tc_plan_launches(p) if L["kind"] == 0]
@@ -309,12 +318,14 @@ def test_launch_info_counts_tiles_gathered_by_stride():
     assert launches(cm("aeb", L), cm("ecd", L), cm("abcd", L)) == [(12, 0)]
     L = dict(a=192, b=4, c=128, d=2, e=64)  # rows 0..767: tiles [0,128) ok, [128,256) crosses 192, [256,384) ok, [384,512) ok, [512,640) crosses 576, [640,768) ok
     assert launches(cm("aeb", L), cm("ecd", L), cm("abcd", L)) == [(12, 8)]
-    # plain matrices: whole tiles without padding only (10001 = 78 * 128 + 17, and 10001 is no multiple of the k-step)
+    # plain matrices: whole tiles only (10001 = 78 * 128 + 17); a padded last k-step goes through the tables after
+    # the whole ones, of which there must be four (32-deep k-steps: 500 = 15 whole ones + 20, 100 = 3 + 4)
     g = lambda n, k: (("ik", (n, k), (1, n)), ("kj", (k, n), (1, k)), ("ij", (n, n), (1, n)))
     assert launches(*g(1024, 512)) == [(64, 64)]
     assert launches(*g(1000, 512)) == [(64, 49)]
-    assert launches(*g(1024, 500)) == [(64, 0)]
-    assert launches(*g(10001, 10001)) == [(6241, 0)]
+    assert launches(*g(1024, 500)) == [(64, 64)]
+    assert launches(*g(1024, 100)) == [(64, 0)]
+    assert launches(*g(10001, 10001)) == [(6241, 78 * 78)]
     # element-by-element gathers (odd leading extent next to another dimension): never by stride
     L = dict(a=127, b=4, c=128, d=2, e=64)
     assert launches(cm("aeb", L), cm("ecd", L), cm("abcd", L)) == [(8, 0)]
@@ -422,3 +433,34 @@ def test_tail_split_shapes():
     L = tc.tc_plan_launches(plan)[0]
     assert (L["tail_tiles"], L["tail_chunks"], L["tail_kc"]) == (6, 2, 64)
     tc.tc_destroy(plan)
+
+
+def test_sweep_families_plan_on_the_host():
+    """The regression grid's case generators (Sec. 6.1 families): seeded, reproducible, and every case plans in every
+    mode; the ladder family keeps 2 N_a^4 N_i^2 within a factor 1.5 of 2 * 16000^3 flops over the ratios 1 ... 5."""
+    from paper_1704_03092_amd import sweep
+
+    for reduced in (True, False):
+        for fam in sweep.FAMILIES:
+            a, b = sweep.cases(fam, reduced), sweep.cases(fam, reduced)
+            assert [c.name for c in a] == [c.name for c in b] and [c.lengths for c in a] == [c.lengths for c in b] and a
+            for c in a:
+                desc = []
+                for idx in (c.idxA, c.idxB, c.idxC):
+                    lens = [c.lengths[x] for x in idx]
+                    st, acc = [], 1
+                    for n in lens:
+                        st.append(acc)
+                        acc *= n
+                    desc.append((idx, tuple(lens), tuple(st)))
+                assert 2 <= max(len(d[0]) for d in desc) <= 6
+                for level, variant in ((0, "abc"), (1, "abc"), (2, "hybrid"), (tc.TC_LEVEL_AUTO, "auto")):
+                    plan = tc.tc_plan(*desc, level, variant, host_only=True)
+                    info = tc.tc_plan_info(plan)
+                    assert (info["m"], info["n"], info["k"]) == c.mnk()
+                    tc.tc_destroy(plan)
+    ratios = {}
+    for c in sweep.cases("ladder"):
+        na, ni = c.lengths["a"], c.lengths["i"]
+        ratios[round(na / ni)] = c.flops() / (2.0 * 16000.0 ** 3)
+    assert sorted(ratios) == [1, 2, 3, 4, 5] and all(1 / 1.5 <= v <= 1.5 for v in ratios.values()), ratios

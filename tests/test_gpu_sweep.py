@@ -1,0 +1,51 @@
+"""The regression grid of the paper's shape families (Sec. 6.1: square, rank-k, fixed-k, the ladder shape dependence,
+tensor-shaped cases) at reduced sizes: every case agrees with the oracle in the mode the library picks by itself, and
+that mode is within 5 % of the fastest mode measured."""
+import numpy as np
+import pytest
+
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+TOL = {0: 1e-13, 1: 1e-13, 2: 1e-12}
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_1704_03092_amd as tc
+
+    tc.load_library()
+    return tc
+
+
+@pytest.mark.parametrize("family", ["square", "rankk", "fixedk", "ladder", "tensor"])
+def test_reduced_grid_parity_and_automatic_choice(gpu, family):
+    import torch
+
+    from gpu_util import logical, run_gpu
+    from paper_1704_03092_amd import sweep
+
+    tc = gpu
+    for cfg in sweep.cases(family, reduced=True):
+        m, n, k = cfg.mnk()
+        print(f"case {cfg.name} m={m} n={n} k={k}", flush=True)
+        # parity in the automatic mode, on sampled rows of the matrix view (the full product at the larger sizes
+        # would take the oracle minutes)
+        A, B, C = cfg.tensors()
+        got_flat, info = run_gpu(A, B, C, 1.5, 0.5, tc.TC_LEVEL_AUTO, "auto")
+        view = oracle.matrix_view(A, B, C)
+        rows = np.unique(np.linspace(0, m - 1, 24).astype(np.int64))
+        ref_rows = oracle.contract_rows(A, B, C, rows, 1.5, 0.5, view=view)
+        got_rows = got_flat[view["rsC"][rows][:, None] + view["csC"][None, :]]
+        scale = oracle.tensor_norm(A) * oracle.tensor_norm(B) * np.sqrt(len(rows) / m)
+        err = float(np.linalg.norm(got_rows - ref_rows)) / scale
+        assert err <= TOL[info["level"]], (cfg.name, info["level"], err)
+        # the automatic choice against every mode, measured
+        rows_ms, auto = sweep.measure(cfg, reps=5)
+        best = min(v[0] for v in rows_ms.values())
+        assert rows_ms[auto][0] <= 1.05 * best + 0.003, (cfg.name, auto, rows_ms)
+        torch.cuda.empty_cache()
