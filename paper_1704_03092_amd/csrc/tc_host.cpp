@@ -353,10 +353,20 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     const int g = 1 << level;
     // Block extents: the matrix view is cut at multiples of the extent; the last block of each direction may be
     // short (or empty) and is completed with zeros (Sec. 3, last paragraph: zero padding of the whole bundle).
-    auto extent = [g](int64_t len) { return g == 1 ? len : round_up((len + g - 1) / g, 16); };
-    p->mb = extent(p->m);
-    p->nb = extent(p->n);
-    p->kb = extent(p->k);
+    // Extents are even (pair-wise gathers never straddle a block).  Where an operand reads the bundle through its
+    // block scatter vector (the bundle is no single constant-stride run in that operand) they are multiples of the
+    // 16 entries of a block, so that blocks of the vector do not straddle Strassen blocks.  Small units keep the
+    // blocks of a direction equally long wherever the length allows: operand sums whose blocks end at different rows
+    // need the padding-checked loop in the tiles where they differ.
+    auto unit = [](const std::vector<Dim>& bundle, std::initializer_list<int> readers) {
+        for (int which : readers)
+            if (affine_stride(make_bundle(bundle, which)) < 0) return 16;
+        return 2;
+    };
+    auto extent = [g](int64_t len, int q) { return g == 1 ? len : round_up((len + g - 1) / g, q); };
+    p->mb = extent(p->m, unit(p->I, {0}));
+    p->nb = extent(p->n, unit(p->J, {1}));
+    p->kb = extent(p->k, unit(p->P, {0, 1}));
 
     // ---- vectors in the device store ----
     p->bundles.resize(V_COUNT);

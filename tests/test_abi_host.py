@@ -159,13 +159,33 @@ def test_schedule_satisfies_brent_equations(level, variant):
 
 
 def test_schedule_prunes_blocks_in_the_padding():
-    # m = 20 at level 2: block extent 16 => block rows 2 and 3 are empty
-    p = _plan(("ik", (20, 64), (1, 20)), ("kj", (64, 64), (1, 64)), ("ij", (20, 64), (1, 20)), level=2)
+    """Block extents (Sec. 3, last paragraph: zero padding): even where the operands read a bundle as one constant-stride
+    run, multiples of the 16-entry blocks of the block scatter vectors elsewhere; blocks wholly in the padding are
+    pruned from the schedule."""
+    # m = 20 as rows a + 4 b of an A whose b stride (8) leaves gaps: read through the block scatter vector, extent 16
+    # at level 2 => block rows 2 and 3 are empty
+    p = _plan(("abk", (4, 5, 64), (1, 8, 40)), ("kj", (64, 64), (1, 64)), ("abj", (4, 5, 64), (1, 4, 20)), level=2)
     info = tc.tc_plan_info(p)
-    assert info["mb"] == 16
+    assert (info["m"], info["mb"]) == (20, 16)
     for e in tc.tc_plan_schedule(p):
         assert all(r < 2 for (r, _, _) in e["a"]) and all(r < 2 for (r, _, _) in e["c"])
         assert e["a"] and e["b"] and e["c"]
+    tc.tc_destroy(p)
+    # plain matrices: m = 20 => 6, 6, 6, 2 rows, nothing pruned; m = 9 => extent 4, block row 3 is empty
+    p = _plan(("ik", (20, 64), (1, 20)), ("kj", (64, 64), (1, 64)), ("ij", (20, 64), (1, 20)), level=2)
+    assert tc.tc_plan_info(p)["mb"] == 6 and len(tc.tc_plan_schedule(p)) == 49
+    tc.tc_destroy(p)
+    p = _plan(("ik", (9, 64), (1, 9)), ("kj", (64, 64), (1, 64)), ("ij", (9, 64), (1, 9)), level=2)
+    assert tc.tc_plan_info(p)["mb"] == 4
+    for e in tc.tc_plan_schedule(p):
+        assert all(r < 3 for (r, _, _) in e["a"]) and all(r < 3 for (r, _, _) in e["c"])
+    tc.tc_destroy(p)
+    # equal blocks wherever the length allows: 16200 = 2 * 8100 = 4 * 4050
+    for level, want in ((1, 8100), (2, 4050)):
+        p = _plan(*_gemm_desc(16200, 16200, 16200), level=level)
+        info = tc.tc_plan_info(p)
+        assert (info["mb"], info["nb"], info["kb"]) == (want, want, want)
+        tc.tc_destroy(p)
 
 
 def test_empty_bundles():
