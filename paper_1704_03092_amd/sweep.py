@@ -204,7 +204,8 @@ def launch_samples(cfg, reps=5):
 
     dev = _Device(cfg)
     out = []
-    for level, variant, kw in ((0, "abc", {"tile_n": 128}), (0, "abc", {"tile_n": 64}), (1, "abc", {}), (2, "abc", {}), (1, "hybrid", {}), (1, "ab", {})):
+    for level, variant, kw in ((0, "abc", {"tile_n": 128}), (0, "abc", {"tile_n": 64}), (1, "abc", {"tile_n": 128}), (2, "abc", {"tile_n": 128}),
+                               (1, "hybrid", {"tile_n": 128}), (1, "hybrid", {"tile_n": 64}), (1, "ab", {"tile_n": 128})):
         plan = tc.tc_plan(dev.A, dev.B, dev.C, level, variant, dev.st, tail_split=-1, **kw)
         if tc.tc_plan_info(plan)["level"] != level:
             tc.tc_destroy(plan)
@@ -217,7 +218,7 @@ def launch_samples(cfg, reps=5):
         for i, L in enumerate(info):
             if L["kind"] == 0 and L["terms_a"] == 0:
                 continue  # the family that counts terms at run time is not modelled apart
-            out.append(dict(L, ms=sorted(t[i] for t in times)[reps // 2], case=cfg.name))
+            out.append(dict(L, ms=sorted(t[i] for t in times)[reps // 2], case=cfg.name, plan_level=level, plan_variant=variant))
     return out
 
 
@@ -251,7 +252,18 @@ def fit(samples, defaults):
     pairs = [L for L in samples if L["kind"] == 1 or (L["pairs_a"] and L["pairs_b"])]
     w = np.array([L["ms"] / (L["ms"] + 0.05) for L in pairs])
     M = np.array([row(L) / (L["ms"] * 1e-3) for L in pairs])
-    x, _ = nnls(M * w[:, None], w)
+    # first everything but the 128 x 64 geometry, then its two parameters with the others held, on the classical
+    # plans alone (each of them was also measured in 128 x 128 tiles: the choice between the two shapes is what these
+    # parameters are for)
+    small = np.array([L["kind"] == 0 and L["tile_n"] == 64 for L in pairs])
+    direct = np.array([L["kind"] == 0 and L["tile_n"] == 64 and L.get("plan_level", 0) == 0 for L in pairs])
+    own = [3, 7, 9]
+    rest = [c for c in range(NU) if c not in own]
+    x = np.zeros(NU)
+    x[rest], _ = nnls(M[~small][:, rest] * w[~small, None], w[~small])
+    if direct.any():
+        target = 1.0 - M[direct][:, rest] @ x[rest]
+        x[own], _ = nnls(M[direct][:, own] * w[direct, None], target * w[direct])
     rel = M @ x - 1.0
     p = dict(defaults)
     inv = lambda v, d: 1.0 / v if v > 0 else d
