@@ -211,7 +211,8 @@ int tc_plan_ex(tc_plan_t **plan_out, const tc_tensor_desc_t *A, const tc_tensor_
  * stores every product M as a dense matrix before it is accumulated into C (one block of C here: the products run one
  * after the other); Naive also stores the operand sums (plus one block of A and one of B); HYBRID: one first-level
  * block of A and of B.  Level 0 needs none unless split_k is used.  Where a launch splits its tail
- * (tc_options_t.tail_split) add 128 KiB per chunk of a tail tile (at most 128 MiB). */
+ * (tc_options_t.tail_split) add one dense tile (128 x tile_n elements: 128 or 64 KiB) per chunk of a tail tile (at
+ * most 1024 chunks). */
 size_t tc_plan_workspace_bytes(const tc_plan_t *plan);
 
 /* C := alpha * A * B + beta * C: the tensor contraction as defined in Sec. 2.3 ("Tensor Contraction": the sum over the

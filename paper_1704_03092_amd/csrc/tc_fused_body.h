@@ -4,8 +4,9 @@
 // FP64 matrix cores and adds the tile to every destination block of C from registers (Sec. 4.2).  Level 0 is the same
 // kernel with one term and one destination.
 //
-// Matrix-core instruction: v_mfma_f64_4x4x4_4b_f64.  One instruction multiplies four independent 4x4x4 blocks;
-// measured on MI355X it sustains twice the rate of v_mfma_f64_16x16x4_f64.  Register layout (lane l):
+// Matrix-core instruction: v_mfma_f64_4x4x4_4b_f64.  One instruction multiplies four independent 4x4x4 blocks; its
+// operands come out of 16-byte LDS reads without any shuffling.  (Measured on MI355X with nothing else in the loop it
+// sustains 76.7 TFLOP/s, v_mfma_f64_16x16x4_f64 77.7: see tc_bench_mfma_peak.)  Register layout (lane l):
 //   A operand: block (l/4)%4, row l%4, k = l/16        B operand: block (l/4)%4, column l%4, k = l/16
 //   D result : block (l/4)%4, column l%4, row l/16
 // A 16x16 output patch is covered by 4 instructions whose B operand has its four column blocks rotated by
@@ -21,10 +22,10 @@
 // This file is compiled for two workgroup geometries (TC_GEO_SMALL, set by the including header):
 //   tc::fused        128 x 128 tiles, 512 threads (8 waves, 2 x 4), one workgroup per compute unit: all kernel families
 //   tc::fused_small  128 x 64 tiles, 256 threads (4 waves, 2 x 2), two workgroups per compute unit: single-term products
-//                    only.  Half the arithmetic per gathered element, but one workgroup's table set-up, first gathers
-//                    and destination update overlap the other's matrix-core work, and the two waves of a SIMD belong
-//                    to different workgroups, so neither waits at the other's barriers.  For products with few k-steps
-//                    per tile or fewer tiles than the device has compute units.
+//                    only.  Less arithmetic per gathered element (1.5 x the operand reads), but one workgroup's
+//                    table set-up, first gathers and destination update may overlap the other's matrix-core work, and
+//                    twice as many tiles are in flight.  For products with few k-steps per tile or fewer tiles than
+//                    the device has compute units (measured: 3 - 15 % there, 6 - 8 % slower with long k).
 #include <hip/hip_runtime.h>
 
 #include <atomic>
@@ -802,7 +803,7 @@ __device__ __forceinline__ TileId tile_of(int lid, int tiles_m, int tiles_n) {
 // Workgroups [0, main_count) compute one whole tile each.  The tiles left over after the last full round of the
 // machine (tail_tiles of them, logical ids main_count ...) are cut along the contracted bundle into chunks of tail_kc
 // entries, one workgroup per (tile, chunk): workgroup main_count + c * tail_tiles + t stores the raw accumulators of
-// chunk c of tail tile t as a dense 128 x 128 tile at partial + 16384 * (c * tail_tiles + t); tail_fixup_kernel adds
+// chunk c of tail tile t as a dense TM x TN tile at partial + TM * TN * (c * tail_tiles + t); tail_fixup_kernel adds
 // the chunks in a fixed order and updates the destinations.
 template <int AMODE, int BMODE, class CF, bool VA, bool VB>
 __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __restrict__ prods, int first, int tiles_m, int tiles_n,
@@ -1189,7 +1190,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
 }
 
 // Tail of a launch cut into chunks (see fused_kernel): tiles = tail tiles, chunks per tile, kc = entries per chunk
-// (a multiple of 64), partial = room for tiles * chunks dense 128 x 128 tiles.  tiles = 0: every tile is computed whole.
+// (a multiple of 64), partial = room for tiles * chunks dense TM x TN tiles.  tiles = 0: every tile is computed whole.
 struct TailSplit {
     int tiles, chunks, kc;
     double* partial;
