@@ -68,8 +68,12 @@ constexpr int OPITCH = 130;  // row pitch of the output tile staged in LDS by th
 #ifndef TC_ROLL
 #define TC_ROLL 1      // 1: the multi-term families gather in a rolling fashion (see Cfg::ROLL); 0: one burst per k-step
 #endif
+#ifndef TC_MFMA16
+#define TC_MFMA16 1    // 1: v_mfma_f64_16x16x4_f64 (one instruction per 16 x 16 output patch and four contracted entries);
+                       // 0: v_mfma_f64_4x4x4_4b_f64 (four, with rotated B fragments)
+#endif
 #ifndef TC_PIN8
-#define TC_PIN8 0      // KT = 32: keep the compiler from moving the parts of a rolling gather across instruction groups
+#define TC_PIN8 1      // KT = 32: keep the compiler from moving the parts of a rolling gather across instruction groups
 #endif
 #ifndef TC_PIN4
 #define TC_PIN4 1      // KT = 16: likewise
@@ -79,7 +83,10 @@ template <int NTA_, int NTB_, bool EXACT_>
 struct Cfg {
     static constexpr int NTA = NTA_, NTB = NTB_;
     static constexpr bool EXACT = EXACT_;
-    static constexpr int KT = (!SMALL && EXACT && NTA <= 2 && NTB <= 2) ? 32 : 16;  // (small geometry: LDS for two workgroups)
+#ifndef TC_KT32_SUM
+#define TC_KT32_SUM 4  // 32-deep k-steps for families with at most this many terms in both sums together (registers)
+#endif
+    static constexpr int KT = (!SMALL && EXACT && NTA + NTB <= TC_KT32_SUM) ? 32 : 16;  // (small geometry: LDS for two workgroups)
     static constexpr bool SINGLE = EXACT && NTA == 1 && NTB == 1;
     // D = how many k-steps ahead of the multiplying step a gather is issued; SETS = register sets for gathers in
     // flight.  Single-term operands: D = 2 with two sets (issued during step s, stored to LDS during step s + 1).
@@ -93,7 +100,10 @@ struct Cfg {
     // multi-term families and none for the single-term one.)  Without ROLL: D = 1, issue at the start (first wave of
     // a SIMD) or in the middle (second wave) of a step, store after its last group.
     // The small geometry rolls its single-term gathers too: its SIMD partner is another workgroup, which covers a late load.
-    static constexpr bool ROLL = TC_ROLL && EXACT && (!SINGLE || SMALL);
+#ifndef TC_ROLL_SINGLE
+#define TC_ROLL_SINGLE 1  // the single-term family in 128 x 128 tiles rolls too (one register set; 8192^3 classical 69.7 -> 72.2 TFLOP/s)
+#endif
+    static constexpr bool ROLL = TC_ROLL && EXACT && (!SINGLE || SMALL || TC_ROLL_SINGLE);
     static constexpr int D = (SINGLE || ROLL) ? 2 : 1;
     static constexpr int SETS = (SINGLE && !ROLL) ? 2 : 1;
     static constexpr int NEA = TM * KT / NTHREADS;  // elements of the A tile (per term) a thread gathers per k-step
@@ -108,8 +118,8 @@ struct Cfg {
     static constexpr int ISSUE_LATE = (SETS == 2) ? 5 : (NQ == 8 ? 4 : 3);
     static constexpr int STAGE_EARLY = (SETS == 2) ? 6 : NQ;
     static constexpr int STAGE_LATE = (SETS == 2) ? 4 : NQ;
-    // Measured at 16384^3: the 32-deep rolling families are fastest when the compiler may place the parts freely
-    // (one-level ABC 73.8 against 73.4 TFLOP/s), the 16-deep ones when each part stays next to its group.
+    // Measured: every rolling family is fastest when each part stays next to its instruction group (8192^3, two-term
+    // families 65.3 -> 68 TFLOP/s executed; the four-term families lose 10 - 20 % without).
     static constexpr bool PIN = SETS == 1 && (D == 1 || (NQ == 8 ? TC_PIN8 : TC_PIN4));
     static_assert(SETS == 1 || NQ == 8, "the two-set schedule is written for 8 groups");
     static_assert(NEA % (NQ / 2) == 0 && (NEA / (NQ / 2)) % 2 == 0 && NEB % (NQ / 2) == 0 && (NEB / (NQ / 2)) % 2 == 0,
@@ -123,6 +133,7 @@ typedef const __attribute__((address_space(1))) int64_t* gvec_t;
 __device__ __forceinline__ gvec_t as_global(const int64_t* p) { return (gvec_t)p; }
 typedef const __attribute__((address_space(1))) double* gdbl_t;
 typedef double double2_t __attribute__((ext_vector_type(2)));
+typedef double double4_t __attribute__((ext_vector_type(4)));
 typedef double2_t double2_u __attribute__((aligned(8)));  // an element pair in global memory: 8-byte aligned only
 typedef const __attribute__((address_space(1))) double2_u* gdbl2_t;
 
@@ -518,8 +529,13 @@ struct State {
     Bases ba, bb;
     // per-lane fragment bases
     const double* fa;
-    const double* fb[4];
+    static constexpr int NS = TC_MFMA16 ? 1 : 4;  // B fragments per 16 x 16 output patch (rotations of the four column blocks)
+    const double* fb[NS];
+#if TC_MFMA16
+    double4_t acc[4][2];
+#else
     double acc[4][2][4];
+#endif
     double la[SETS][NTA][NEA], lb[SETS][NTB][NEB];  // register sets of the gathers in flight
     unsigned pa[SETS], pb[SETS];
     bool issued_fast[SETS];    // the loads of a set were issued without padding checks
@@ -626,7 +642,7 @@ struct State {
     }
 
     template <int CUR, int Q>
-    __device__ __forceinline__ void read_frags(double (&af)[4], double (&bf)[8]) {
+    __device__ __forceinline__ void read_frags(double (&af)[4], double (&bf)[2 * NS]) {
         constexpr int ROW = 16 * (Q / 4) + (Q % 4);
 #pragma unroll
         for (int xp = 0; xp < 2; ++xp) {
@@ -635,14 +651,20 @@ struct State {
             af[2 * xp + 1] = v.y;
         }
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
+        for (int s = 0; s < NS; ++s) {
             const double2_t v = *reinterpret_cast<const double2_t*>(fb[s] + CUR * TILE + ROW * PITCH);
             bf[s] = v.x;
-            bf[4 + s] = v.y;
+            bf[NS + s] = v.y;
         }
     }
 
-    __device__ __forceinline__ void multiply(const double (&af)[4], const double (&bf)[8]) {
+    __device__ __forceinline__ void multiply(const double (&af)[4], const double (&bf)[2 * NS]) {
+#if TC_MFMA16
+#pragma unroll
+        for (int y = 0; y < 2; ++y)
+#pragma unroll
+            for (int x = 0; x < 4; ++x) acc[x][y] = __builtin_amdgcn_mfma_f64_16x16x4f64(af[x], bf[y], acc[x][y], 0, 0, 0);
+#else
 #pragma unroll
         for (int y = 0; y < 2; ++y)
 #pragma unroll
@@ -650,6 +672,7 @@ struct State {
 #pragma unroll
                 for (int x = 0; x < 4; ++x)
                     acc[x][y][s] = __builtin_amdgcn_mfma_f64_4x4x4f64(af[x], bf[y * 4 + s], acc[x][y][s], 0, 0, 0);
+#endif
     }
 
     // With one register set the compiler must not move the waits for gathered data up into the MFMA groups;
@@ -704,7 +727,7 @@ struct State {
     // instruction groups Q .. NQ-1 of the k-step in LDS buffer CUR; the fragments of group Q are in af/bf[Q % 2] and
     // those of group Q + 1 are read while group Q multiplies
     template <int CUR, int Q, int ROLE, bool FAST, bool UNIT, bool AFF>
-    __device__ __forceinline__ void groups(double (&af)[2][4], double (&bf)[2][8], int step) {
+    __device__ __forceinline__ void groups(double (&af)[2][4], double (&bf)[2][2 * NS], int step) {
         if constexpr (Q < NQ) {
             if constexpr (Q + 1 < NQ) read_frags<CUR, Q + 1>(af[(Q + 1) & 1], bf[(Q + 1) & 1]);
             // D = 2: a wave in the first half of its k-step outranks its SIMD partner in the second half, which
@@ -728,7 +751,7 @@ struct State {
         if constexpr (!NOENT) raw_entry = ent_ptr[have ? kn : 0];  // unconditional load: ent_ptr always points at readable memory
 
         between_groups<CUR, 0, ROLE, FAST, UNIT, AFF>(step);
-        double af[2][4], bf[2][8];
+        double af[2][4], bf[2][2 * NS];
         read_frags<CUR, 0>(af[0], bf[0]);
         groups<CUR, 0, ROLE, FAST, UNIT, AFF>(af, bf, step);
 
@@ -1053,7 +1076,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     const int krow = 8 * (lk & 1) + 4 * (lk >> 1);
     st.fa = &S.a[0][0] + krow * PITCH + wm * 64 + 2 * l16;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) st.fb[s] = &S.b[0][0] + krow * PITCH + wn * 32 + 2 * ((l16 + 4 * s) & 15);
+    for (int s = 0; s < St::NS; ++s) st.fb[s] = &S.b[0][0] + krow * PITCH + wn * 32 + 2 * ((l16 + 4 * s) & 15);
     {
         typedef Map<AMODE, KT, VA, TM> MA;
         typedef Map<BMODE, KT, VB, TN> MB;
@@ -1088,7 +1111,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
 #pragma unroll
         for (int y = 0; y < 2; ++y)
 #pragma unroll
-            for (int s = 0; s < 4; ++s) st.acc[x][y][s] = 0.0;
+            for (int s = 0; s < 4; ++s) st.acc[x][y][s] = 0.0;  // (the four results of a lane: rotations s, or rows 4 s + lane / 16)
     __syncthreads();
 
     // k-steps whose gathers need no padding checks run in a loop specialised for the wave's role on its SIMD
@@ -1174,9 +1197,15 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
 #pragma unroll
-                    for (int x = 0; x < 4; ++x)
+                    for (int x = 0; x < 4; ++x) {
+#if TC_MFMA16
+                        // result s of the lane: row 4 s + lane / 16 of A's 16 lanes, column lane % 16 of B's
+                        otile[(cw + 2 * (lane & 15) + y) * OPITCH + wm * 64 + 32 * (x >> 1) + 2 * (4 * s + di) + (x & 1)] = alpha * st.acc[x][y][s];
+#else
                         otile[(cw + 2 * (((dblk + s) & 3) * 4 + dj) + y) * OPITCH + wm * 64 + 32 * (x >> 1) + 2 * (dblk * 4 + di) + (x & 1)] =
                             alpha * st.acc[x][y][s];
+#endif
+                    }
         }
         __syncthreads();
 #pragma unroll
