@@ -885,7 +885,7 @@ int64_t count_table_free(const tc_plan_t* p, const Step& s) {
     if (s.kind != STEP_FUSED || !s.cfg.a_vec || !s.cfg.b_vec || s.cfg.nta == 0) return 0;  // pair-wise gathers and exact term counts only
     const int64_t limit = (int64_t)1 << 20;
     const int64_t TN = s.cfg.tile_n;
-    const int KT = (TN == 128 && s.cfg.nta <= 2 && s.cfg.ntb <= 2) ? 32 : 16;
+    const int KT = (TN == 128 && s.cfg.nta + s.cfg.ntb <= 6) ? 32 : 16;  // the kernel's k-step depth (Cfg::KT)
     const int64_t tiles_m = (s.rows + 127) / 128, tiles_n = (s.cols + TN - 1) / TN;
     const int64_t per_prod = tiles_m * tiles_n, main_count = (int64_t)s.count * per_prod - s.tail_tiles;
     int64_t n = 0;
