@@ -815,17 +815,17 @@ void copy_labels(char* out, const std::vector<Dim>& b) {
 // grid; launches of a millisecond and more are reproduced to 5 - 8 % RMS).
 extern const tc_model_params_t kDefaultModel = {
     78.6e12,               // published FP64 matrix peak
-    {0.927, 0.889, 0.759}, // tiles gathered by stride, 1 / 2 / 4-term operand sums
+    {0.988, 0.943, 0.805}, // tiles gathered by stride, 1 / 2 / 4-term operand sums
     8.0e12,                // HBM3E
-    0.731,                 // element-wise passes and destination updates
-    12.4e-6,               // per launch (the fixed part of a kernel's duration)
-    10.6e-6,               // per wave of tiles: gather tables, pipeline fill, destination update
+    0.730,                 // element-wise passes and destination updates
+    12.3e-6,               // per launch (the fixed part of a kernel's duration)
+    12.7e-6,               // per wave of tiles: gather tables, pipeline fill, destination update
     256, {0, 0, 0},
-    0.963,                 // 128 x 64 tiles (fitted to the classical plans measured in both tile shapes)
+    0.930,                 // 128 x 64 tiles (fitted to the classical plans measured in both tile shapes)
     0.0,                   // no cost per wave of their own: one workgroup's fill and update hide behind the other's multiplications
-    0.750,                 // element-by-element gathers
-    0.0441,                // operand reads not hidden behind the matrix cores
-    {0.876, 0.855, 0.630}};  // tiles gathered through the scatter tables  // tiles gathered through the scatter tables  // tiles gathered through the scatter tables   // tiles gathered through the scatter tables
+    0.701,                 // element-by-element gathers
+    0.0303,                // operand reads not hidden behind the matrix cores
+    {0.907, 0.870, 0.616}};  // tiles gathered through the scatter tables  // tiles gathered through the scatter tables  // tiles gathered through the scatter tables  // tiles gathered through the scatter tables   // tiles gathered through the scatter tables
 
 // What the model needs to know of a fused launch.
 struct FusedShape {
