@@ -108,7 +108,14 @@ typedef struct {
                      * per compute unit; 64 = 128 x 64 tiles, two workgroups of 256 threads per compute unit (for products
                      * with few k-steps per tile or few tiles: one workgroup's set-up and destination update overlap the
                      * other's matrix-core work).  Launches with multi-block sums always use 128. */
-    int reserved[2];
+    int no_peel;    /* Sizes that 2^level does not divide (Sec. 3, last paragraph, names dynamic peeling and zero padding):
+                     * 0 = in the ABC and AB variants, where the row or column bundle is not a whole number of equal blocks and is at least 2^level
+                     * tiles of 128 long, the Strassen products cover the largest part that is, and the rows / columns
+                     * left over (fewer than 2^level times the block unit of 2 or 16) are done by one classical product
+                     * each (dynamic peeling); shorter bundles and the contracted bundle are completed with zeros.
+                     * 1 = zero padding everywhere (the last block of a direction is then shorter than the others, and
+                     * sums of blocks of different length run a slower, padding-checked loop in the tiles where they differ). */
+    int reserved[1];
 } tc_options_t;
 
 /* Facts about a plan (tc_plan_info). */
@@ -121,8 +128,12 @@ typedef struct {
     int n_launches;       /* kernel launches per tc_contract() */
     int bs_block;
     int a_mode, b_mode;   /* 0: stride-1 direction of the operand is its free bundle, 1: the contracted bundle */
-    int64_t mb, nb, kb;   /* extents of one Strassen block: ceil(m / 2^level) rounded up to a multiple of 16, etc. */
+    int64_t mb, nb, kb;   /* extents of one Strassen block: ceil(length / 2^level) rounded up to an even number (to a multiple of
+                           * 16 where an operand reads the bundle through its block scatter vector) */
     char I[TC_MAX_NDIM + 1], J[TC_MAX_NDIM + 1], P[TC_MAX_NDIM + 1]; /* labels of each bundle, fastest first, NUL-terminated */
+    int64_t m_peel, n_peel; /* last rows / columns of the matrix view left to classical edge products (dynamic peeling); the
+                             * 2^level x 2^level block grid of tc_plan_schedule covers the first m - m_peel rows and
+                             * n - n_peel columns */
 } tc_plan_info_t;
 
 /* One term of a Strassen product as scheduled (tc_plan_schedule): block (row, col) of the 2^L x 2^L grid and its sign. */

@@ -70,7 +70,7 @@ class tc_tensor_desc_t(ctypes.Structure):
 
 class tc_options_t(ctypes.Structure):
     _fields_ = [("bs_block", ctypes.c_int), ("host_only", ctypes.c_int), ("no_merge", ctypes.c_int), ("split_k", ctypes.c_int),
-                ("tail_split", ctypes.c_int), ("tile_n", ctypes.c_int), ("reserved", ctypes.c_int * 2)]
+                ("tail_split", ctypes.c_int), ("tile_n", ctypes.c_int), ("no_peel", ctypes.c_int), ("reserved", ctypes.c_int * 1)]
 
 
 class tc_launch_info_t(ctypes.Structure):
@@ -85,7 +85,8 @@ class tc_plan_info_t(ctypes.Structure):
                 ("level", ctypes.c_int), ("variant", ctypes.c_int), ("n_products", ctypes.c_int), ("n_launches", ctypes.c_int),
                 ("bs_block", ctypes.c_int), ("a_mode", ctypes.c_int), ("b_mode", ctypes.c_int), ("mb", ctypes.c_int64),
                 ("nb", ctypes.c_int64), ("kb", ctypes.c_int64), ("I", ctypes.c_char * (TC_MAX_NDIM + 1)),
-                ("J", ctypes.c_char * (TC_MAX_NDIM + 1)), ("P", ctypes.c_char * (TC_MAX_NDIM + 1))]
+                ("J", ctypes.c_char * (TC_MAX_NDIM + 1)), ("P", ctypes.c_char * (TC_MAX_NDIM + 1)), ("m_peel", ctypes.c_int64),
+                ("n_peel", ctypes.c_int64)]
 
 
 class tc_product_t(ctypes.Structure):
@@ -207,7 +208,7 @@ class Plan:
 
 
 def tc_plan(A, B, C, level: int = 0, variant="abc", stream=None, bs_block: int = 0, host_only: bool = False,
-            no_merge: bool = False, split_k: int = 0, tail_split: int = 0, tile_n: int = 0) -> Plan:
+            no_merge: bool = False, split_k: int = 0, tail_split: int = 0, tile_n: int = 0, no_peel: bool = False) -> Plan:
     """A, B, C: (labels, lengths, strides) triples or objects with .idx/.lens/.strides.
     tail_split: 0 = automatic, -1 = never, 2..16 = forced chunk count; tile_n: 0 = automatic, 64 or 128 (see tc_options_t)."""
     lib = load_library()
@@ -219,7 +220,8 @@ def tc_plan(A, B, C, level: int = 0, variant="abc", stream=None, bs_block: int =
             ds.append(_desc(*T))
     v = VARIANTS[variant] if isinstance(variant, str) else int(variant)
     out = ctypes.c_void_p()
-    opts = tc_options_t(int(bs_block), int(bool(host_only)), int(bool(no_merge)), int(split_k), int(tail_split), int(tile_n))
+    opts = tc_options_t(int(bs_block), int(bool(host_only)), int(bool(no_merge)), int(split_k), int(tail_split), int(tile_n),
+                        int(bool(no_peel)))
     rc = lib.tc_plan_ex(ctypes.byref(out), ctypes.byref(ds[0]), ctypes.byref(ds[1]), ctypes.byref(ds[2]), int(level), v,
                         ctypes.byref(opts), _stream(stream))
     if rc != 0:

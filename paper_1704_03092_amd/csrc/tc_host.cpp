@@ -67,6 +67,7 @@ struct tc_plan {
     size_t workspace_bytes = 0;
     int64_t wsM = 0, wsTA = 0, wsTB = 0;  // offsets (elements) of the temporaries inside the workspace
     int64_t wsPart = 0;                   // offset of the chunks of split tail tiles
+    int64_t m_peel = 0, n_peel = 0;       // rows / columns left to classical edge products (dynamic peeling)
     // device
     std::vector<BundleDesc> bundles;      // V_COUNT entries (temporaries may be unused: total = 0)
     int64_t store_entries = 0;
@@ -287,7 +288,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     if (level < 0 || level > 2) return TC_ERR_LEVEL;
     if (variant < TC_VARIANT_NAIVE || variant > TC_VARIANT_HYBRID) return TC_ERR_VARIANT;
     p->bs_block = 16;
-    bool no_merge = false;
+    bool no_merge = false, no_peel = false;
     int tail_mode = 0;  // 0: the model decides, -1: never, 2..16: that many chunks wherever a launch has a tail
     int tile_mode = 0;  // 0: the model decides, 64 / 128: tile columns of the single-term launches
     int split = 1;
@@ -300,6 +301,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         if (opts->bs_block > 0) p->bs_block = opts->bs_block;
         p->host_only = opts->host_only != 0;
         no_merge = opts->no_merge != 0;
+        no_peel = opts->no_peel != 0;
         if (opts->split_k > 4 || opts->split_k < -1) return TC_ERR_STATE;
         split = std::max(opts->split_k, 1);  // -1 has been resolved by the caller (tc_plan_ex)
     }
@@ -364,6 +366,21 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         return 2;
     };
     auto extent = [g](int64_t len, int q) { return g == 1 ? len : round_up((len + g - 1) / g, q); };
+    // Dynamic peeling of the row and column bundles (Sec. 3, last paragraph): the Strassen products cover the largest
+    // leading part that is a whole number of equal blocks, classical edge products (appended after the schedule) the
+    // rest.  While the Strassen schedule is generated, m and n stand for that leading part.
+    const int64_t m_full = p->m, n_full = p->n;
+    // (Only the schedules that sum blocks inside the multiplying kernel gain: single-block products have no blocks of
+    // different length to reconcile, the edge products would only add to them.)
+    if (level > 0 && !no_peel && (variant == TC_VARIANT_ABC || variant == TC_VARIANT_AB)) {
+        auto leading = [g](int64_t len, int q) {
+            const int64_t cut = (int64_t)g * q, lead = len / cut * cut;
+            return lead != len && lead >= (int64_t)g * 128 ? lead : len;
+        };
+        p->m = leading(m_full, unit(p->I, {0}));
+        p->n = leading(n_full, unit(p->J, {1}));
+    }
+    p->m_peel = m_full - p->m, p->n_peel = n_full - p->n;
     p->mb = extent(p->m, unit(p->I, {0}));
     p->nb = extent(p->n, unit(p->J, {1}));
     p->kb = extent(p->k, unit(p->P, {0, 1}));
@@ -778,6 +795,27 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         }
         tc::FusedConfig base_cfg{p->a_mode, p->b_mode, 1, 1, p->a_vec, p->b_vec, 0, 0, p->c_mode, 128};
         emit(list, base_cfg, variant == TC_VARIANT_ABC || level == 0);
+    }
+    // ---- edge products of the peeled rows and columns: classical, each the first and only writer of its part of C ----
+    p->m = m_full, p->n = n_full;
+    if (!empty && p->k > 0) {
+        auto edge = [&](int64_t r0, int64_t rows, int64_t c0, int64_t cols) {
+            Product pr;
+            std::memset(&pr, 0, sizeof pr);
+            setop(pr.A, V_RSA, V_CSA, r0 + rows, p->k, 0, 0);
+            add_term(pr.A, r0, 0, 1.0);
+            setop(pr.B, V_RSB, V_CSB, p->k, c0 + cols, 0, 0);
+            add_term(pr.B, 0, c0, 1.0);
+            setop(pr.C, V_RSC, V_CSC, r0 + rows, c0 + cols, 0, 0);
+            add_term(pr.C, r0, c0, 1.0);
+            pr.mb = rows, pr.nb = cols, pr.kb = p->k;
+            pr.first_mask = 1;
+            const tc::FusedConfig cfg{p->a_mode, p->b_mode, 1, 1, p->a_vec, p->b_vec, 0, 0, p->c_mode, 128};
+            p->steps.push_back(Step{STEP_FUSED, (int)p->prods.size(), 1, cfg, rows, cols, 0, 0});
+            p->prods.push_back(pr);
+        };
+        if (p->m_peel > 0) edge(m_full - p->m_peel, p->m_peel, 0, n_full);
+        if (p->n_peel > 0) edge(0, m_full - p->m_peel, n_full - p->n_peel, p->n_peel);
     }
     p->n_launches = (int)p->steps.size();
     // ---- tile shape and tails (launches whose tiles do not fill whole rounds of the compute units) ----
@@ -1295,6 +1333,7 @@ int tc_plan_info(const tc_plan_t* plan, tc_plan_info_t* out) {
     copy_labels(out->I, plan->I);
     copy_labels(out->J, plan->J);
     copy_labels(out->P, plan->P);
+    out->m_peel = plan->m_peel, out->n_peel = plan->n_peel;
     return TC_OK;
 }
 

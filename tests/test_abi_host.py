@@ -484,3 +484,36 @@ def test_sweep_families_plan_on_the_host():
         na, ni = c.lengths["a"], c.lengths["i"]
         ratios[round(na / ni)] = c.flops() / (2.0 * 16000.0 ** 3)
     assert sorted(ratios) == [1, 2, 3, 4, 5] and all(1 / 1.5 <= v <= 1.5 for v in ratios.values()), ratios
+
+
+def test_dynamic_peeling_of_rows_and_columns():
+    """Sec. 3, last paragraph (dynamic peeling): where the row or column bundle is no whole number of equal blocks (and
+    long enough), the Strassen grid covers the largest leading part that is, and classical edge products the rest:
+    rows [m - m_peel, m) over all columns, then the leading rows over columns [n - n_peel, n).  The contracted bundle
+    and short bundles are completed with zeros; no_peel turns peeling off."""
+    # 10001 = 4 * 2500 + 1: one row and one column are peeled at one level; at two levels 10001 = 8 * 1250 + 1
+    for level, block in ((1, 5000), (2, 2500)):
+        p = _plan(*_gemm_desc(10001, 10001, 10001), level=level)
+        info = tc.tc_plan_info(p)
+        assert (info["m_peel"], info["n_peel"], info["mb"], info["nb"]) == (1, 1, block, block)
+        assert info["kb"] == 2 * ((10001 + 2 ** (level + 1) - 1) // 2 ** (level + 1))  # zero padding: even, >= k / 2^level
+        fused = [L for L in tc.tc_plan_launches(p) if L["kind"] == 0]
+        assert [(L["rows"], L["cols"], L["depth"], L["terms_a"], L["terms_b"]) for L in fused[-2:]] == [(1, 10001, 10001, 1, 1), (10000, 1, 10001, 1, 1)]
+        assert all((L["rows"], L["cols"]) == (block, block) for L in fused[:-2])
+        assert len(tc.tc_plan_schedule(p)) == 7 ** level  # the schedule lists the Strassen products only
+        tc.tc_destroy(p)
+        q = _plan(*_gemm_desc(10001, 10001, 10001), level=level, no_peel=True)
+        info = tc.tc_plan_info(q)
+        assert (info["m_peel"], info["n_peel"]) == (0, 0) and info["mb"] == 2 * ((10001 + 2 ** (level + 1) - 1) // 2 ** (level + 1))
+        tc.tc_destroy(q)
+    # nothing to peel: divisible lengths, level 0, bundles shorter than 2^level tiles of 128
+    for shape, level in (((16200, 16200, 16200), 2), ((10001, 10001, 10001), 0), ((501, 300, 657), 2)):
+        p = _plan(*_gemm_desc(*shape), level=level)
+        info = tc.tc_plan_info(p)
+        assert (info["m_peel"], info["n_peel"]) == (0, 0), shape
+        tc.tc_destroy(p)
+    # a row bundle read through the block scatter vector: blocks are multiples of 16, so up to 31 rows are peeled at one level
+    p = _plan(("abk", (24, 50, 64), (1, 32, 1600)), ("kj", (64, 700), (1, 64)), ("abj", (24, 50, 700), (1, 24, 1200)), level=1)
+    info = tc.tc_plan_info(p)
+    assert (info["m"], info["mb"], info["m_peel"], info["n_peel"]) == (1200, 592, 16, 0)
+    tc.tc_destroy(p)

@@ -350,6 +350,38 @@ def test_both_tile_shapes_of_single_block_products(gpu, tile_n):
         _check(gpu, A, B, C, 1.0, 1.0, 0, "abc", exact=True, tile_n=tile_n, **kw)
 
 
+@pytest.mark.parametrize("no_peel", [False, True])
+def test_sizes_that_the_block_grid_does_not_divide(gpu, no_peel):
+    """Sec. 3, last paragraph: dynamic peeling (classical edge products for the rows and columns beyond the largest
+    whole number of equal blocks) and zero padding (no_peel) give the classical result; odd extents in every bundle,
+    every variant, both levels, general strides, beta = 0 over NaN in the peeled part."""
+    import paper_1704_03092_amd as tc
+
+    run_gpu, logical = gpu
+    st = __import__("torch").cuda.current_stream()
+    for (m, n, k), kind in (((645, 583, 657), "smallint"), ((1031, 517, 300), "uniform"), ((519, 1290, 129), "smallint")):
+        c = workloads.Contraction("g", "ij", "ik", "kj", {"i": m, "j": n, "k": k}, seed=m + n)
+        A, B, C = c.tensors(kind=kind)
+        for level, variant in MODES[1:]:
+            _check(gpu, A, B, C, 1.5, 0.5, level, variant, exact=(kind == "smallint"), no_peel=no_peel)
+        plan = tc.tc_plan(A, B, C, 1, "abc", st, no_peel=no_peel)
+        info = tc.tc_plan_info(plan)
+        tc.tc_destroy(plan)
+        assert (info["m_peel"] > 0 or info["n_peel"] > 0) == (not no_peel)
+        C.data[:] = np.nan
+        got_flat, _ = run_gpu(A, B, C, 2.0, 0.0, 2, "abc", no_peel=no_peel)
+        ref = from_dense("ij", np.zeros((m, n)))
+        oracle.contract_matrix(A, B, ref, 2.0, 0.0)
+        assert oracle.error_metric(logical(C, got_flat), ref.view(), oracle.tensor_norm(A), oracle.tensor_norm(B)) <= TOL[2]
+    # tensor-shaped: rows a + 24 b (read through the block scatter vector: blocks in multiples of 16, 16 rows peeled)
+    L = dict(a=24, b=50, c=30, d=23, e=40, f=9)
+    A = workloads.make_tensor("aebf", L, 7, 0, "smallint")
+    B = workloads.make_tensor("fdec", L, 7, 1, "smallint")
+    C = workloads.make_tensor("abcd", L, 7, 2, "smallint")
+    for level, variant in ((1, "abc"), (1, "hybrid"), (2, "abc"), (1, "ab")):
+        _check(gpu, A, B, C, 1.0, 1.0, level, variant, exact=True, no_peel=no_peel)
+
+
 def test_column_stride_beyond_the_table_free_limit(gpu):
     """Plain matrices whose column stride is 2^20 + 8 elements: the table-free gather (strides below 2^20 only) must
     step aside for the gather through the scatter tables; full tiles, several k-steps, every family at level 1."""
@@ -395,7 +427,7 @@ def test_contract_timed_matches_contract(gpu):
     import paper_1704_03092_amd as tc
     from gpu_util import to_dev
 
-    c = workloads.Contraction("g", "ij", "ik", "kj", {"i": 520, "j": 390, "k": 260}, seed=11)
+    c = workloads.Contraction("g", "ij", "ik", "kj", {"i": 520, "j": 392, "k": 260}, seed=11)  # (no rows or columns to peel)
     A, B, C = c.tensors()
     st = torch.cuda.current_stream()
     for level, variant, fused, other in ((0, "abc", 1, 0), (1, "abc", 4, 0), (1, "hybrid", 7, 10), (1, "naive", 7, 21)):
