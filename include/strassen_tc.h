@@ -109,10 +109,12 @@ typedef struct {
                      * with few k-steps per tile or few tiles: one workgroup's set-up and destination update overlap the
                      * other's matrix-core work).  Launches with multi-block sums always use 128. */
     int no_peel;    /* Sizes that 2^level does not divide (Sec. 3, last paragraph, names dynamic peeling and zero padding):
-                     * 0 = in the ABC and AB variants, where the row or column bundle is not a whole number of equal blocks and is at least 2^level
-                     * tiles of 128 long, the Strassen products cover the largest part that is, and the rows / columns
-                     * left over (fewer than 2^level times the block unit of 2 or 16) are done by one classical product
-                     * each (dynamic peeling); shorter bundles and the contracted bundle are completed with zeros.
+                     * 0 = the Strassen products cover a leading part of the row and of the column bundle and one
+                     * classical product each does the rows / columns left over (dynamic peeling).  The leading part is
+                     * a whole number of 128-wide tiles per block if that leaves at most a tenth of the bundle over;
+                     * else, in the ABC and AB variants, if the bundle is no whole number of equal blocks and at least
+                     * 2^level tiles long, the largest whole number of block units (2 or 16 entries); else nothing is
+                     * peeled.  The contracted bundle and whatever is not peeled are completed with zeros.
                      * 1 = zero padding everywhere (the last block of a direction is then shorter than the others, and
                      * sums of blocks of different length run a slower, padding-checked loop in the tiles where they differ). */
     int reserved[1];

@@ -372,10 +372,18 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     const int64_t m_full = p->m, n_full = p->n;
     // (Only the schedules that sum blocks inside the multiplying kernel gain: single-block products have no blocks of
     // different length to reconcile, the edge products would only add to them.)
-    if (level > 0 && !no_peel && (variant == TC_VARIANT_ABC || variant == TC_VARIANT_AB)) {
-        auto leading = [g](int64_t len, int q) {
-            const int64_t cut = (int64_t)g * q, lead = len / cut * cut;
-            return lead != len && lead >= (int64_t)g * 128 ? lead : len;
+    const bool sums_in_kernel = variant == TC_VARIANT_ABC || variant == TC_VARIANT_AB;
+    if (level > 0 && !no_peel) {
+        // Long bundles are cut at a whole number of 128-wide tiles per block if that leaves at most a tenth to the edge
+        // product: the Strassen products then have no ragged tiles at all (every tile of theirs can be gathered by
+        // stride), and the fringe is done once, by the single-term kernel, instead of once per block.  Otherwise at
+        // a whole number of block units, which at least makes the blocks equally long.
+        auto leading = [g, sums_in_kernel](int64_t len, int q) {
+            const int64_t tiles = (int64_t)g * 128, coarse = len / tiles * tiles;
+            if (coarse == len) return len;
+            if (coarse * 10 >= len * 9) return coarse;
+            const int64_t cut = (int64_t)g * q, fine = len / cut * cut;
+            return sums_in_kernel && fine != len && fine >= tiles ? fine : len;
         };
         p->m = leading(m_full, unit(p->I, {0}));
         p->n = leading(n_full, unit(p->J, {1}));

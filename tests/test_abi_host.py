@@ -180,11 +180,16 @@ def test_schedule_prunes_blocks_in_the_padding():
     for e in tc.tc_plan_schedule(p):
         assert all(r < 3 for (r, _, _) in e["a"]) and all(r < 3 for (r, _, _) in e["c"])
     tc.tc_destroy(p)
-    # equal blocks wherever the length allows: 16200 = 2 * 8100 = 4 * 4050
-    for level, want in ((1, 8100), (2, 4050)):
-        p = _plan(*_gemm_desc(16200, 16200, 16200), level=level)
+    # equal blocks wherever the length allows: 16200 = 2 * 8100 = 4 * 4050 (zero padding; with peeling the row and
+    # column blocks are whole tiles: 63 and 31 of them)
+    for level, want, tiles in ((1, 8100, 63), (2, 4050, 31)):
+        p = _plan(*_gemm_desc(16200, 16200, 16200), level=level, no_peel=True)
         info = tc.tc_plan_info(p)
         assert (info["mb"], info["nb"], info["kb"]) == (want, want, want)
+        tc.tc_destroy(p)
+        p = _plan(*_gemm_desc(16200, 16200, 16200), level=level)
+        info = tc.tc_plan_info(p)
+        assert (info["mb"], info["nb"], info["kb"]) == (128 * tiles, 128 * tiles, want)
         tc.tc_destroy(p)
 
 
@@ -402,7 +407,8 @@ def test_tail_split_is_the_argmin_of_the_model(shape, level, variant, tile_n):
     assert len(L0) == len(L1)
     most = 0
     for a, b in zip(L0, L1):
-        assert {k: v for k, v in a.items() if not k.startswith("tail")} == {k: v for k, v in b.items() if not k.startswith("tail")}
+        same = lambda L: {k: v for k, v in L.items() if not k.startswith("tail") and k != "tiles_table_free"}  # (chunks have their own depth)
+        assert same(a) == same(b)
         assert a["tail_tiles"] == 0
         if b["kind"] == 1 or b["tail_tiles"] == 0:
             assert b["tail_tiles"] == 0
@@ -487,30 +493,46 @@ def test_sweep_families_plan_on_the_host():
 
 
 def test_dynamic_peeling_of_rows_and_columns():
-    """Sec. 3, last paragraph (dynamic peeling): where the row or column bundle is no whole number of equal blocks (and
-    long enough), the Strassen grid covers the largest leading part that is, and classical edge products the rest:
-    rows [m - m_peel, m) over all columns, then the leading rows over columns [n - n_peel, n).  The contracted bundle
-    and short bundles are completed with zeros; no_peel turns peeling off."""
-    # 10001 = 4 * 2500 + 1: one row and one column are peeled at one level; at two levels 10001 = 8 * 1250 + 1
-    for level, block in ((1, 5000), (2, 2500)):
+    """Sec. 3, last paragraph (dynamic peeling): the Strassen grid covers a leading part of the row
+    and column bundles, classical edge products the rest: rows [m - m_peel, m) over all columns, then the leading
+    rows over columns [n - n_peel, n).  Long bundles are cut at whole tiles per block (at most a tenth left over),
+    others at whole block units if they are no whole number of equal blocks; the contracted bundle and short bundles
+    are completed with zeros; no_peel turns peeling off."""
+    # 10001 = 39 * 256 + 17 = 19 * 512 + 273
+    for level, block, peel in ((1, 4992, 17), (2, 2432, 273)):
         p = _plan(*_gemm_desc(10001, 10001, 10001), level=level)
         info = tc.tc_plan_info(p)
-        assert (info["m_peel"], info["n_peel"], info["mb"], info["nb"]) == (1, 1, block, block)
+        assert (info["m_peel"], info["n_peel"], info["mb"], info["nb"]) == (peel, peel, block, block)
         assert info["kb"] == 2 * ((10001 + 2 ** (level + 1) - 1) // 2 ** (level + 1))  # zero padding: even, >= k / 2^level
         fused = [L for L in tc.tc_plan_launches(p) if L["kind"] == 0]
-        assert [(L["rows"], L["cols"], L["depth"], L["terms_a"], L["terms_b"]) for L in fused[-2:]] == [(1, 10001, 10001, 1, 1), (10000, 1, 10001, 1, 1)]
-        assert all((L["rows"], L["cols"]) == (block, block) for L in fused[:-2])
+        assert [(L["rows"], L["cols"], L["depth"], L["terms_a"], L["terms_b"]) for L in fused[-2:]] == \
+            [(peel, 10001, 10001, 1, 1), (10001 - peel, peel, 10001, 1, 1)]
+        assert all((L["rows"], L["cols"]) == (block, block) and L["tiles_table_free"] == L["tiles"] for L in fused[:-2])
         assert len(tc.tc_plan_schedule(p)) == 7 ** level  # the schedule lists the Strassen products only
         tc.tc_destroy(p)
         q = _plan(*_gemm_desc(10001, 10001, 10001), level=level, no_peel=True)
         info = tc.tc_plan_info(q)
         assert (info["m_peel"], info["n_peel"]) == (0, 0) and info["mb"] == 2 * ((10001 + 2 ** (level + 1) - 1) // 2 ** (level + 1))
         tc.tc_destroy(q)
-    # nothing to peel: divisible lengths, level 0, bundles shorter than 2^level tiles of 128
-    for shape, level in (((16200, 16200, 16200), 2), ((10001, 10001, 10001), 0), ((501, 300, 657), 2)):
+        for variant in ("ab", "naive", "hybrid"):  # whole tiles per block: every variant
+            q = _plan(*_gemm_desc(10001, 10001, 10001), level=level, variant=variant)
+            info = tc.tc_plan_info(q)
+            assert (info["m_peel"], info["n_peel"], info["mb"]) == (peel, peel, block)
+            tc.tc_destroy(q)
+    # 16200 = 63 * 256 + 72 (equal blocks of 8100 would have ragged last tiles); 2000 = 7 * 256 + 208 is more than a
+    # tenth: cut at block units, and 2000 is two equal blocks already; 2001 leaves one row
+    for shape, level, want in (((16200, 16384, 16200), 1, (72, 0)), ((2000, 2001, 657), 1, (0, 1)), ((16384, 8192, 100), 2, (0, 0)),
+                               ((10001, 10001, 10001), 0, (0, 0)), ((501, 300, 657), 2, (0, 0))):
         p = _plan(*_gemm_desc(*shape), level=level)
         info = tc.tc_plan_info(p)
-        assert (info["m_peel"], info["n_peel"]) == (0, 0), shape
+        assert (info["m_peel"], info["n_peel"]) == want, shape
+        tc.tc_destroy(p)
+    # block units are peeled only where blocks are summed inside the multiplying kernel (ABC, AB): single-block products
+    # have no blocks of different length to reconcile
+    for variant, want in (("ab", (0, 1)), ("naive", (0, 0)), ("hybrid", (0, 0))):
+        p = _plan(*_gemm_desc(2000, 2001, 657), level=1, variant=variant)
+        info = tc.tc_plan_info(p)
+        assert (info["m_peel"], info["n_peel"]) == want, variant
         tc.tc_destroy(p)
     # a row bundle read through the block scatter vector: blocks are multiples of 16, so up to 31 rows are peeled at one level
     p = _plan(("abk", (24, 50, 64), (1, 32, 1600)), ("kj", (64, 700), (1, 64)), ("abj", (24, 50, 700), (1, 24, 1200)), level=1)

@@ -427,7 +427,7 @@ def test_contract_timed_matches_contract(gpu):
     import paper_1704_03092_amd as tc
     from gpu_util import to_dev
 
-    c = workloads.Contraction("g", "ij", "ik", "kj", {"i": 520, "j": 392, "k": 260}, seed=11)  # (no rows or columns to peel)
+    c = workloads.Contraction("g", "ij", "ik", "kj", {"i": 512, "j": 384, "k": 260}, seed=11)  # (whole tiles per block: no rows or columns to peel)
     A, B, C = c.tensors()
     st = torch.cuda.current_stream()
     for level, variant, fused, other in ((0, "abc", 1, 0), (1, "abc", 4, 0), (1, "hybrid", 7, 10), (1, "naive", 7, 21)):
