@@ -297,7 +297,7 @@ int tc_contract_timed(const tc_plan_t *plan, double alpha, const double *A_dev, 
                       double *C_dev, void *workspace_dev, void *stream, tc_launch_times_t *out);
 
 /* What the FP64 matrix cores of this GPU sustain when they do nothing else: a kernel of independent MFMA chains, no
- * memory traffic (instruction 0: v_mfma_f64_4x4x4_4b_f64, the one the library's kernels use; 1: v_mfma_f64_16x16x4_f64).
+ * memory traffic (instruction 0: v_mfma_f64_4x4x4_4b_f64; 1: v_mfma_f64_16x16x4_f64, the one the library's kernels use).
  * Writes the achieved TFLOP/s to *tflops_out.  Uses the static workspace of tc_contract_static for its (discarded)
  * results; blocks until the measurement is done (about 50 ms). */
 int tc_bench_mfma_peak(int instruction, void *stream, double *tflops_out);

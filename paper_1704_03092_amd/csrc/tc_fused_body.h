@@ -4,13 +4,15 @@
 // FP64 matrix cores and adds the tile to every destination block of C from registers (Sec. 4.2).  Level 0 is the same
 // kernel with one term and one destination.
 //
-// Matrix-core instruction: v_mfma_f64_4x4x4_4b_f64.  One instruction multiplies four independent 4x4x4 blocks; its
-// operands come out of 16-byte LDS reads without any shuffling.  (Measured on MI355X with nothing else in the loop it
-// sustains 76.7 TFLOP/s, v_mfma_f64_16x16x4_f64 77.7: see tc_bench_mfma_peak.)  Register layout (lane l):
-//   A operand: block (l/4)%4, row l%4, k = l/16        B operand: block (l/4)%4, column l%4, k = l/16
-//   D result : block (l/4)%4, column l%4, row l/16
-// A 16x16 output patch is covered by 4 instructions whose B operand has its four column blocks rotated by
-// s = 0..3 positions: block slot b of instruction s multiplies row block b by column block (b + s) % 4.
+// Matrix-core instruction: v_mfma_f64_16x16x4_f64, one per 16 x 16 output patch and four contracted entries.
+// Register layout (lane l; probed on the device for the result):
+//   A operand: row l % 16, k = l / 16        B operand: column l % 16, k = l / 16
+//   D result v (0..3): row 4 v + l / 16, column l % 16
+// Lane l % 16 stands for tile rows (columns) 2 (l % 16) + {0, 1} of a 32-wide strip, so that one 16-byte LDS read
+// delivers the fragments of two patches without any shuffling.  (TC_MFMA16 = 0 builds the kernel on
+// v_mfma_f64_4x4x4_4b_f64 instead, which it was written for: the same operand layout read as four independent 4 x 4
+// blocks, a patch covered by four instructions whose B operand has its column blocks rotated by s = 0..3.  Measured
+// with nothing else in the loop the two sustain 77.7 and 76.7 TFLOP/s: tc_bench_mfma_peak.)
 //
 // Other VALU instructions delay these MFMAs on this chip (measured: integer or fp64 VALU work added to an MFMA loop
 // adds its issue time), so the main loop needs few of them: the gather tables hold ready-made byte addresses (one
@@ -62,11 +64,11 @@ constexpr int OPITCH = 130;  // row pitch of the output tile staged in LDS by th
 // One kernel family per (NTA, NTB) = terms of the operand sums of A and B.
 //   EXACT : every product of the launch has exactly NTA and NTB terms; the term loops are compile-time.
 //   !EXACT: up to NTA / NTB terms, counted at run time (a four-term sum that lost a block to the zero padding).
-// The k-step is 32 deep while both sums have at most two terms, 16 deep for four-term sums (registers).  How far
-// ahead the gathers run and how they are turned over is described at Cfg::D / Cfg::ROLL.
+// The k-step is 32 deep, 16 deep for the (4,4) family, the run-time-counted one and the small geometry (registers, LDS).
+// How far ahead the gathers run and how they are turned over is described at Cfg::D / Cfg::ROLL.
 // Build-time switches of the schedule (measurement aids; the defaults are the measured optima).
 #ifndef TC_ROLL
-#define TC_ROLL 1      // 1: the multi-term families gather in a rolling fashion (see Cfg::ROLL); 0: one burst per k-step
+#define TC_ROLL 1      // 1: the families with exact term counts gather in a rolling fashion (see Cfg::ROLL); 0: one burst per k-step
 #endif
 #ifndef TC_MFMA16
 #define TC_MFMA16 1    // 1: v_mfma_f64_16x16x4_f64 (one instruction per 16 x 16 output patch and four contracted entries);
@@ -90,19 +92,19 @@ struct Cfg {
     static constexpr int KT = (!SMALL && EXACT && NTA + NTB <= TC_KT32_SUM) ? 32 : 16;  // (small geometry: LDS for two workgroups)
     static constexpr bool SINGLE = EXACT && NTA == 1 && NTB == 1;
     // D = how many k-steps ahead of the multiplying step a gather is issued; SETS = register sets for gathers in
-    // flight.  Single-term operands: D = 2 with two sets (issued during step s, stored to LDS during step s + 1).
-    // Sums of several terms have registers for one set only.  ROLL: that set is turned over piecewise.  The tile of
+    // flight.  ROLL (every family with exact term counts): D = 2 with ONE set that is turned over piecewise.  The tile of
     // the next k-step is cut into NQ parts (the first half of the groups takes A's, the second half B's); next to
     // instruction group g a wave waits for part g of the loads it issued one k-step earlier, adds the terms, stores
     // the sums to the other LDS buffer and at once re-issues that part's loads for the k-step after the next.
     // Every load has exactly one k-step to arrive, the waits are for the oldest loads in flight only, and loads and
     // LDS stores are spread evenly over the step.  (Issuing a whole k-step of a multi-term tile in one burst, 16 to
     // 32 loads per wave, fills the address queue of the CU: the profiler counts cycles with that queue full for the
-    // multi-term families and none for the single-term one.)  Without ROLL: D = 1, issue at the start (first wave of
-    // a SIMD) or in the middle (second wave) of a step, store after its last group.
-    // The small geometry rolls its single-term gathers too: its SIMD partner is another workgroup, which covers a late load.
+    // multi-term families.)  Without ROLL (the run-time-counted family; build-time alternatives): multi-term sums
+    // D = 1, issue at the start (first wave of a SIMD) or in the middle (second wave) of a step, store after its last
+    // group; single-term operands D = 2 with two sets (issued during step s, stored to LDS during step s + 1), which
+    // was the fastest single-term schedule with the 4x4x4 instruction (TC_ROLL_SINGLE = 0).
 #ifndef TC_ROLL_SINGLE
-#define TC_ROLL_SINGLE 1  // the single-term family in 128 x 128 tiles rolls too (one register set; 8192^3 classical 69.7 -> 72.2 TFLOP/s)
+#define TC_ROLL_SINGLE 1  // the single-term family in 128 x 128 tiles rolls too (8192^3 classical 69.7 -> 72.2 TFLOP/s)
 #endif
     static constexpr bool ROLL = TC_ROLL && EXACT && (!SINGLE || SMALL || TC_ROLL_SINGLE);
     static constexpr int D = (SINGLE || ROLL) ? 2 : 1;
