@@ -1166,32 +1166,51 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     static_assert(BATCH == TM / RS, "both thread mappings cover the pass");
     // c_mode 0, lanes along the rows: thread = (row r, column group cg), columns cg + CG b.
     // c_mode 1, lanes along the columns: thread = (column c, row group rg), rows rg + RS b.
+    // Either way element b of a thread has one fixed and one stepping scatter entry, and sits at a fixed step in the
+    // staged tile.
     const int e_r = tid % TM, e_cg = tid / TM, e_c = tid % CP, e_rg = tid / CP;
-    auto offset = [&](int d, int pass, int b) -> int64_t {
-        return c_mode == 0 ? c_rs[d][e_r] + c_cs[d][pass * CP + e_cg + CG * b] : c_rs[d][e_rg + RS * b] + c_cs[d][pass * CP + e_c];
-    };
+    const int s_first = c_mode == 0 ? e_cg * OPITCH + e_r : e_c * OPITCH + e_rg, s_step = c_mode == 0 ? CG * OPITCH : RS;
+    const int o_step = c_mode == 0 ? CG : RS;
     auto factor = [&](int d) -> double { return (part || P.overwrite) ? 0.0 : (((P.first_mask >> d) & 1u) ? beta : 1.0); };
-    // current contents of destination d (where the update needs them)
-    auto fetch = [&](int d, int pass, double (&cur)[BATCH]) {
-        const bool need = factor(d) != 0.0;
-#pragma unroll
-        for (int b = 0; b < BATCH; ++b) {
-            const int64_t off = offset(d, pass, b);
-            cur[b] = (need && off >= 0) ? Cbase[off] : 0.0;
-        }
-    };
-    auto update = [&](int d, int pass, const double (&cur)[BATCH]) {
+    auto staged = [&](int b) -> double { return otile[s_first + s_step * b]; };
+    // One destination's share of a pass.  The thread's offsets are read first; where none of a wave's is a sentinel (every
+    // tile but those on a ragged edge) the wave takes a path without per-element conditions, on which the loads of C,
+    // the reads of the staged tile and the stores are each issued as one batch.  (With a condition around every element
+    // the compiler orders the work element by element, and every element then waits for its own LDS read.)
+    auto apply = [&](int d, int pass) {
         const double g = part ? 1.0 : P.C.coef[d], f = factor(d);
+        const int64_t o_fixed = c_mode == 0 ? c_rs[d][e_r] : c_cs[d][pass * CP + e_c];
+        const int64_t* o_var = c_mode == 0 ? &c_cs[d][pass * CP + e_cg] : &c_rs[d][e_rg];
+        int64_t off[BATCH];
+        bool edge = false;
 #pragma unroll
-        for (int b = 0; b < BATCH; ++b) {
-            const int64_t off = offset(d, pass, b);
-            const double v = g * (c_mode == 0 ? otile[(e_cg + CG * b) * OPITCH + e_r] : otile[e_c * OPITCH + e_rg + RS * b]);
-            if (off >= 0) Cbase[off] = (f == 0.0) ? v : __builtin_fma(f, cur[b], v);
+        for (int b = 0; b < BATCH; ++b) off[b] = o_fixed + o_var[o_step * b], edge |= off[b] < 0;
+        if (!__builtin_amdgcn_ballot_w64(edge)) {
+            double cur[BATCH];
+            if (f != 0.0) {
+#pragma unroll
+                for (int b = 0; b < BATCH; ++b) cur[b] = Cbase[off[b]];
+#pragma unroll
+                for (int b = 0; b < BATCH; ++b) cur[b] = __builtin_fma(f, cur[b], g * staged(b));
+            } else {
+#pragma unroll
+                for (int b = 0; b < BATCH; ++b) cur[b] = g * staged(b);
+            }
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) Cbase[off[b]] = cur[b];
+        } else {
+            double cur[BATCH];
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) cur[b] = (f != 0.0 && off[b] >= 0) ? Cbase[off[b]] : 0.0;
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) {
+                const double v = g * staged(b);
+                if (off[b] >= 0) Cbase[off[b]] = (f == 0.0) ? v : __builtin_fma(f, cur[b], v);
+            }
         }
     };
 #pragma unroll 1
     for (int pass = 0; pass < NPASS; ++pass) {
-        double cur[BATCH];
         if (pass > 0) __syncthreads();  // the previous pass has been read out
         if (wn / (WN / NPASS) == pass) {
             const int cw = (wn % (WN / NPASS)) * 32;
@@ -1213,10 +1232,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         __syncthreads();
 #pragma unroll
         for (int d = 0; d < MAXC; ++d) {
-            if (d < nC) {
-                fetch(d, pass, cur);  // (fetching ahead, during the transposition, costs registers and measured slower)
-                update(d, pass, cur);
-            }
+            if (d < nC) apply(d, pass);
         }
     }
 }
