@@ -117,7 +117,12 @@ typedef struct {
                      * peeled.  The contracted bundle and whatever is not peeled are completed with zeros.
                      * 1 = zero padding everywhere (the last block of a direction is then shorter than the others, and
                      * sums of blocks of different length run a slower, padding-checked loop in the tiles where they differ). */
-    int reserved[1];
+    int no_repack;  /* An operand that the kernel could only gather element by element, with consecutive entries of the
+                     * gather direction in different memory lines (both A and B have their unit-stride index in the
+                     * contracted bundle, whose order can follow only one of them; or a tensor without a unit-stride
+                     * index), is copied once into a dense temporary in the workspace by an element-wise pass and
+                     * the products read that (the packing of Sec. 4.1 made explicit, once per contraction; classical,
+                     * ABC and AB schedules).  1 = never: every product gathers from the caller's tensors. */
 } tc_options_t;
 
 /* Facts about a plan (tc_plan_info). */

@@ -70,7 +70,7 @@ class tc_tensor_desc_t(ctypes.Structure):
 
 class tc_options_t(ctypes.Structure):
     _fields_ = [("bs_block", ctypes.c_int), ("host_only", ctypes.c_int), ("no_merge", ctypes.c_int), ("split_k", ctypes.c_int),
-                ("tail_split", ctypes.c_int), ("tile_n", ctypes.c_int), ("no_peel", ctypes.c_int), ("reserved", ctypes.c_int * 1)]
+                ("tail_split", ctypes.c_int), ("tile_n", ctypes.c_int), ("no_peel", ctypes.c_int), ("no_repack", ctypes.c_int)]
 
 
 class tc_launch_info_t(ctypes.Structure):
@@ -208,7 +208,7 @@ class Plan:
 
 
 def tc_plan(A, B, C, level: int = 0, variant="abc", stream=None, bs_block: int = 0, host_only: bool = False,
-            no_merge: bool = False, split_k: int = 0, tail_split: int = 0, tile_n: int = 0, no_peel: bool = False) -> Plan:
+            no_merge: bool = False, split_k: int = 0, tail_split: int = 0, tile_n: int = 0, no_peel: bool = False, no_repack: bool = False) -> Plan:
     """A, B, C: (labels, lengths, strides) triples or objects with .idx/.lens/.strides.
     tail_split: 0 = automatic, -1 = never, 2..16 = forced chunk count; tile_n: 0 = automatic, 64 or 128 (see tc_options_t)."""
     lib = load_library()
@@ -221,7 +221,7 @@ def tc_plan(A, B, C, level: int = 0, variant="abc", stream=None, bs_block: int =
     v = VARIANTS[variant] if isinstance(variant, str) else int(variant)
     out = ctypes.c_void_p()
     opts = tc_options_t(int(bs_block), int(bool(host_only)), int(bool(no_merge)), int(split_k), int(tail_split), int(tile_n),
-                        int(bool(no_peel)))
+                        int(bool(no_peel)), int(bool(no_repack)))
     rc = lib.tc_plan_ex(ctypes.byref(out), ctypes.byref(ds[0]), ctypes.byref(ds[1]), ctypes.byref(ds[2]), int(level), v,
                         ctypes.byref(opts), _stream(stream))
     if rc != 0:

@@ -158,6 +158,33 @@ bool pairs_contiguous(const std::vector<Dim>& lane, int which) {
     return false;  // the bundle has a single entry: nothing to pair
 }
 
+BundleDesc make_bundle(const std::vector<Dim>& bundle, int which);
+
+// How many 128-byte lines the first 256 entries of a bundle's scatter vector touch in tensor `which`, over the 16
+// lines that 256 consecutive elements would: 1 for a contiguous run, 16 if every entry sits in a line of its own.
+// (A gather along such a bundle fetches that multiple of the operand's bytes, and the lines are seldom still cached
+// when their other entries come up.)
+double line_amplification(const std::vector<Dim>& bundle, int which) {
+    const BundleDesc b = make_bundle(bundle, which);
+    const int64_t window = std::min<int64_t>(b.total, 256);
+    if (window < 32) return 1.0;
+    std::vector<int64_t> lines;
+    int64_t idx[TC_MAX_NDIM] = {0};
+    int64_t off = 0;
+    for (int64_t e = 0; e < window; ++e) {
+        lines.push_back(off >> 4);  // (arithmetic shift: negative strides fall into lines too)
+        for (int d = 0; d < b.ndim; ++d) {
+            off += b.stride[d];
+            if (++idx[d] < b.len[d]) break;
+            off -= b.stride[d] * b.len[d];
+            idx[d] = 0;
+        }
+    }
+    std::sort(lines.begin(), lines.end());
+    const int64_t distinct = std::unique(lines.begin(), lines.end()) - lines.begin();
+    return (double)distinct / (double)((window + 15) / 16);
+}
+
 void order_bundle(std::vector<Dim>& bundle, int which) {
     std::stable_sort(bundle.begin(), bundle.end(), [which](const Dim& x, const Dim& y) {
         int64_t sx = which == 0 ? x.sA : which == 1 ? x.sB : x.sC;
@@ -288,7 +315,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     if (level < 0 || level > 2) return TC_ERR_LEVEL;
     if (variant < TC_VARIANT_NAIVE || variant > TC_VARIANT_HYBRID) return TC_ERR_VARIANT;
     p->bs_block = 16;
-    bool no_merge = false, no_peel = false;
+    bool no_merge = false, no_peel = false, no_repack = false;
     int tail_mode = 0;  // 0: the model decides, -1: never, 2..16: that many chunks wherever a launch has a tail
     int tile_mode = 0;  // 0: the model decides, 64 / 128: tile columns of the single-term launches
     int split = 1;
@@ -302,6 +329,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         p->host_only = opts->host_only != 0;
         no_merge = opts->no_merge != 0;
         no_peel = opts->no_peel != 0;
+        no_repack = opts->no_repack != 0;
         if (opts->split_k > 4 || opts->split_k < -1) return TC_ERR_STATE;
         split = std::max(opts->split_k, 1);  // -1 has been resolved by the caller (tc_plan_ex)
     }
@@ -418,10 +446,20 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
     p->bundles[V_RSM] = make_dense(use_M || use_S ? p->mb : 0, 1);
     p->bundles[V_CSM] = make_dense(use_M ? p->nb : use_S ? split * p->nb : 0, p->mb);  // the chunks' temporaries side by side
     const int64_t tm = use_H ? hsub * p->mb : p->mb, tn = use_H ? hsub * p->nb : p->nb, tk = use_H ? hsub * p->kb : p->kb;  // temporaries' extents
-    p->bundles[V_RSTA] = make_dense(use_T || use_H ? tm : 0, 1);
-    p->bundles[V_CSTA] = make_dense(use_T || use_H ? tk : 0, tm);
-    p->bundles[V_RSTB] = make_dense(use_T || use_H ? tk : 0, 1);
-    p->bundles[V_CSTB] = make_dense(use_T || use_H ? tn : 0, tk);
+    // Repacking (the explicit packing of Sec. 4.1, done once per contraction instead of once per tile): an operand
+    // that can only be gathered element by element, and whose consecutive entries along the gather direction lie in
+    // different memory lines, is first copied into a dense temporary by one element-wise pass; the products then
+    // read the temporary by stride.  (Such an operand arises when both A and B have their unit-stride index in the
+    // contracted bundle: the bundle's order can follow only one of them.)  Worth it if the tiles re-read the
+    // operand at least four times.  The stored-sum schedules have temporaries of their own and do not repack.
+    const bool can_repack = !no_repack && !empty && p->k > 0 && !use_S && !use_H && !use_T;
+    const bool repack_a = can_repack && !p->a_vec && n_full >= 4 * 128 && line_amplification(p->a_mode == 0 ? p->I : p->P, 0) >= 8.0;
+    const bool repack_b = can_repack && !p->b_vec && m_full >= 4 * 128 && line_amplification(p->b_mode == 0 ? p->J : p->P, 1) >= 8.0;
+    const bool own_T = use_T || use_H;
+    p->bundles[V_RSTA] = make_dense(own_T ? tm : repack_a ? m_full : 0, 1);
+    p->bundles[V_CSTA] = make_dense(own_T ? tk : repack_a ? p->k : 0, own_T ? tm : m_full);
+    p->bundles[V_RSTB] = make_dense(own_T ? tk : repack_b ? p->k : 0, 1);
+    p->bundles[V_CSTB] = make_dense(own_T ? tn : repack_b ? n_full : 0, own_T ? tk : p->k);
     int64_t off = 0;
     for (auto& b : p->bundles) {
         b.out_off = off;
@@ -453,6 +491,15 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         }
         p->workspace_bytes = (size_t)w * sizeof(double);
     }
+    if (repack_a || repack_b) {
+        int64_t w = (int64_t)(p->workspace_bytes / sizeof(double));
+        if (repack_a) p->wsTA = w, w += m_full * p->k;
+        if (repack_b) p->wsTB = w, w += p->k * n_full;
+        p->workspace_bytes = (size_t)w * sizeof(double);
+    }
+    // where the products read A and B, and how
+    const int a_mode = repack_a ? 0 : p->a_mode, b_mode = repack_b ? 1 : p->b_mode;  // the temporaries: A rows, B columns contiguous
+    const int a_vec = repack_a ? 1 : p->a_vec, b_vec = repack_b ? 1 : p->b_vec;
 
     if (!p->host_only) {
         // look up this GPU's static workspace now, so that tc_contract_static finds the address ready
@@ -476,6 +523,19 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         const bool use_bs = p->store_dev && p->bs_block == 16;
         op.rbs = use_bs ? p->store_dev + p->bundles[rs_id].bs_off : nullptr;
         op.cbs = use_bs ? p->store_dev + p->bundles[cs_id].bs_off : nullptr;
+    };
+
+    auto set_a = [&](Operand& op, int64_t rows) {
+        if (repack_a)
+            setop(op, V_RSTA, V_CSTA, rows, p->k, 1, p->wsTA);
+        else
+            setop(op, V_RSA, V_CSA, rows, p->k, 0, 0);
+    };
+    auto set_b = [&](Operand& op, int64_t cols) {
+        if (repack_b)
+            setop(op, V_RSTB, V_CSTB, p->k, cols, 1, p->wsTB);
+        else
+            setop(op, V_RSB, V_CSB, p->k, cols, 0, 0);
     };
 
     struct Pending {
@@ -763,6 +823,19 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
             emit(list, cfg, true);
         }
     } else {
+        for (int which = 0; which < 2; ++which) {
+            if (!(which == 0 ? repack_a : repack_b)) continue;
+            Product cp;
+            std::memset(&cp, 0, sizeof cp);
+            const int64_t rows = which == 0 ? m_full : p->k, cols = which == 0 ? p->k : n_full;
+            setop(cp.A, which == 0 ? V_RSA : V_RSB, which == 0 ? V_CSA : V_CSB, rows, cols, 0, 0);
+            add_term(cp.A, 0, 0, 1.0);
+            setop(cp.C, which == 0 ? V_RSTA : V_RSTB, which == 0 ? V_CSTA : V_CSTB, rows, cols, 1, which == 0 ? p->wsTA : p->wsTB);
+            add_term(cp.C, 0, 0, 1.0);
+            cp.mb = rows, cp.nb = cols, cp.first_mask = 1, cp.overwrite = 1;
+            p->steps.push_back(Step{STEP_LINCOMB, (int)p->prods.size(), 1, {}, rows, cols, (which == 0 ? p->a_mode == 0 : p->b_mode == 1) ? 1 : 0, which});
+            p->prods.push_back(cp);
+        }
         std::vector<std::vector<int>> U, V, W;
         block_tables(level, U, V, W);
         const int R = (int)U.size();
@@ -771,8 +844,8 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
             Pending e;
             std::memset(&e.pr, 0, sizeof e.pr);
             std::memset(&e.view, 0, sizeof e.view);
-            setop(e.pr.A, V_RSA, V_CSA, p->m, p->k, 0, 0);
-            setop(e.pr.B, V_RSB, V_CSB, p->k, p->n, 0, 0);
+            set_a(e.pr.A, p->m);
+            set_b(e.pr.B, p->n);
             setop(e.pr.C, V_RSC, V_CSC, p->m, p->n, 0, 0);
             e.pr.mb = p->mb;
             e.pr.nb = p->nb;
@@ -801,7 +874,7 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
             if (e.view.n_a == 0 || e.view.n_b == 0 || e.view.n_c == 0) continue;
             list.push_back(e);
         }
-        tc::FusedConfig base_cfg{p->a_mode, p->b_mode, 1, 1, p->a_vec, p->b_vec, 0, 0, p->c_mode, 128};
+        tc::FusedConfig base_cfg{a_mode, b_mode, 1, 1, a_vec, b_vec, repack_a ? 1 : 0, repack_b ? 1 : 0, p->c_mode, 128};
         emit(list, base_cfg, variant == TC_VARIANT_ABC || level == 0);
     }
     // ---- edge products of the peeled rows and columns: classical, each the first and only writer of its part of C ----
@@ -810,15 +883,15 @@ int build_plan(tc_plan_t* p, const tc_tensor_desc_t* A, const tc_tensor_desc_t* 
         auto edge = [&](int64_t r0, int64_t rows, int64_t c0, int64_t cols) {
             Product pr;
             std::memset(&pr, 0, sizeof pr);
-            setop(pr.A, V_RSA, V_CSA, r0 + rows, p->k, 0, 0);
+            set_a(pr.A, r0 + rows);
             add_term(pr.A, r0, 0, 1.0);
-            setop(pr.B, V_RSB, V_CSB, p->k, c0 + cols, 0, 0);
+            set_b(pr.B, c0 + cols);
             add_term(pr.B, 0, c0, 1.0);
             setop(pr.C, V_RSC, V_CSC, r0 + rows, c0 + cols, 0, 0);
             add_term(pr.C, r0, c0, 1.0);
             pr.mb = rows, pr.nb = cols, pr.kb = p->k;
             pr.first_mask = 1;
-            const tc::FusedConfig cfg{p->a_mode, p->b_mode, 1, 1, p->a_vec, p->b_vec, 0, 0, p->c_mode, 128};
+            const tc::FusedConfig cfg{a_mode, b_mode, 1, 1, a_vec, b_vec, repack_a ? 1 : 0, repack_b ? 1 : 0, p->c_mode, 128};
             p->steps.push_back(Step{STEP_FUSED, (int)p->prods.size(), 1, cfg, rows, cols, 0, 0});
             p->prods.push_back(pr);
         };

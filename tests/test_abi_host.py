@@ -8,6 +8,7 @@ import numpy as np
 import pytest
 
 import paper_1704_03092_amd as tc
+import workloads
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -539,3 +540,34 @@ def test_dynamic_peeling_of_rows_and_columns():
     info = tc.tc_plan_info(p)
     assert (info["m"], info["mb"], info["m_peel"], info["n_peel"]) == (1200, 592, 16, 0)
     tc.tc_destroy(p)
+
+
+def test_operand_with_scattered_gathers_is_repacked():
+    """Both A and B have their unit-stride index in the contracted bundle; the bundle follows A, so consecutive contracted
+    entries of B lie megabytes apart: B is copied into a dense temporary first (one element-wise pass), and the
+    product reads the temporary pair-wise.  no_repack keeps the gather from the caller's tensor."""
+    lengths = {"e": 2, "d": 256, "a": 256, "f": 12, "g": 16, "h": 16}
+    descs = []
+    for idx in ("fgehd", "hgaf", "ead"):
+        lens = [lengths[c] for c in idx]
+        descs.append((idx, tuple(lens), tuple(workloads.col_major(lens))))
+    m, n, k = 2 * 256, 256, 12 * 16 * 16
+    for level, variant in ((0, "abc"), (1, "abc"), (1, "ab")):
+        plan = tc.tc_plan(*descs, level, variant, None, host_only=True)
+        L = tc.tc_plan_launches(plan)
+        assert L[0]["kind"] == 1 and (L[0]["rows"], L[0]["cols"]) == (k, n)  # the copy of B
+        fused = [l for l in L if l["kind"] == 0]
+        assert fused and all(l["pairs_a"] == 1 and l["pairs_b"] == 1 for l in fused)
+        plain = tc.tc_plan(*descs, level, variant, None, host_only=True, no_repack=True)
+        Lp = tc.tc_plan_launches(plain)
+        assert len(Lp) == len(L) - 1 and all(l["pairs_b"] == 0 for l in Lp if l["kind"] == 0)
+        assert tc.tc_plan_workspace_bytes(plan) == tc.tc_plan_workspace_bytes(plain) + 8 * k * n
+    # too few row tiles to pay for the copy; the stored-sum schedules keep their own temporaries
+    small = dict(lengths, d=64)
+    descs_small = []
+    for idx in ("fgehd", "hgaf", "ead"):
+        lens = [small[c] for c in idx]
+        descs_small.append((idx, tuple(lens), tuple(workloads.col_major(lens))))
+    assert all(l["kind"] == 0 for l in tc.tc_plan_launches(tc.tc_plan(*descs_small, 0, "abc", None, host_only=True)))
+    hyb = tc.tc_plan_launches(tc.tc_plan(*descs, 1, "hybrid", None, host_only=True))
+    assert not (hyb[0]["kind"] == 1 and (hyb[0]["rows"], hyb[0]["cols"]) == (k, n))

@@ -382,6 +382,25 @@ def test_sizes_that_the_block_grid_does_not_divide(gpu, no_peel):
         _check(gpu, A, B, C, 1.0, 1.0, level, variant, exact=True, no_peel=no_peel)
 
 
+@pytest.mark.parametrize("no_repack", [False, True])
+def test_operand_repacked_into_a_dense_temporary(gpu, no_repack):
+    # A and B both have their unit-stride index in the contracted bundle, which follows A: B's gathers are scattered
+    # and B is copied into a dense temporary first (unless told not to).  Small integers: bit for bit.
+    c = workloads.Contraction("hostile", "ead", "fgehd", "hgaf", {"e": 2, "d": 260, "a": 200, "f": 8, "g": 16, "h": 16}, seed=77)
+    run_gpu, logical = gpu
+    for level, variant in [(0, "abc"), (1, "abc"), (1, "ab"), (2, "abc")]:
+        A, B, C = c.tensors(kind="smallint")
+        info = _check(gpu, A, B, C, 2.0, -1.0, level, variant, exact=True, no_repack=no_repack)
+        A, B, C = c.tensors()
+        _check(gpu, A, B, C, 0.5, 1.0, level, variant, no_repack=no_repack)
+    import paper_1704_03092_amd as tc
+
+    A, B, C = c.tensors()
+    plan = tc.tc_plan(A, B, C, 0, "abc", None, host_only=True, no_repack=no_repack)
+    kinds = [l["kind"] for l in tc.tc_plan_launches(plan)]
+    assert kinds == ([0] if no_repack else [1, 0])
+
+
 def test_column_stride_beyond_the_table_free_limit(gpu):
     """Plain matrices whose column stride is 2^20 + 8 elements: the table-free gather (strides below 2^20 only) must
     step aside for the gather through the scatter tables; full tiles, several k-steps, every family at level 1."""
