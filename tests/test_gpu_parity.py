@@ -401,6 +401,26 @@ def test_operand_repacked_into_a_dense_temporary(gpu, no_repack):
     assert kinds == ([0] if no_repack else [1, 0])
 
 
+def test_operand_without_a_unit_stride_is_repacked(gpu):
+    # A is every 16th element of a larger array along both of its indices (no unit-stride index at all: each gathered
+    # element has a memory line of its own) and is read by 5 column tiles: copied into a dense temporary first.  B has
+    # the same layout but is read by 2 row tiles only and stays where it is.
+    L = {"i": 200, "k": 150, "j": 600}
+    run_gpu, logical = gpu
+    import paper_1704_03092_amd as tc
+
+    for kind, exact in (("smallint", True), ("uniform", False)):
+        A = workloads.make_tensor("ik", L, 5, 0, kind, (16, 16 * 200 + 48))
+        B = workloads.make_tensor("kj", L, 6, 1, kind, (16, 16 * 150))
+        C = workloads.make_tensor("ij", L, 7, 2, kind)
+        for level, variant in [(0, "abc"), (1, "abc"), (1, "ab")]:
+            _check(gpu, A, B, C, -1.0, 2.0, level, variant, exact=exact)
+            _check(gpu, A, B, C, -1.0, 2.0, level, variant, exact=exact, no_repack=True)
+    launches = tc.tc_plan_launches(tc.tc_plan(A, B, C, 0, "abc", None, host_only=True))
+    assert [(l["kind"], l["rows"], l["cols"]) for l in launches[:1]] == [(1, 200, 150)] and len(launches) == 2
+    assert launches[1]["pairs_a"] == 1 and launches[1]["pairs_b"] == 0
+
+
 def test_column_stride_beyond_the_table_free_limit(gpu):
     """Plain matrices whose column stride is 2^20 + 8 elements: the table-free gather (strides below 2^20 only) must
     step aside for the gather through the scatter tables; full tiles, several k-steps, every family at level 1."""
