@@ -826,6 +826,39 @@ __device__ __forceinline__ TileId tile_of(int lid, int tiles_m, int tiles_n) {
     return t;
 }
 
+// The same with the divisions done by multiplication, so that they stay on the scalar unit (an integer division by
+// a run-time value compiles to vector floating-point code, and vector instructions of a workgroup that is setting
+// up its tile wait for the matrix-core instructions of the workgroup it shares the compute unit with).
+// TileDiv holds floor(2^32 / d) for the three divisors (2^32 - 1 for d = 1), computed by the host.
+struct TileDiv {
+    unsigned per_prod, gsz, gh_last, tail_tiles;
+};
+__host__ inline unsigned tile_div_rcp(int64_t d) { return d <= 1 ? 0xffffffffu : (unsigned)(((uint64_t)1 << 32) / (uint64_t)d); }
+// x / d and the remainder for x < 2^32, d >= 1: the estimate from rcp is at most one too small
+__device__ __forceinline__ unsigned div_by(unsigned x, unsigned d, unsigned rcp, unsigned& rem) {
+    unsigned q = __umulhi(x, rcp);
+    unsigned r = x - q * d;
+    if (r >= d) ++q, r -= d;
+    if (r >= d) ++q, r -= d;
+    rem = r;
+    return q;
+}
+__device__ __forceinline__ TileId tile_of(int lid, int tiles_m, int tiles_n, const TileDiv& dv) {
+    TileId t;
+    unsigned rem, in_group, rest;
+    t.pidx = (int)div_by((unsigned)lid, (unsigned)(tiles_m * tiles_n), dv.per_prod, rem);
+    const int grp = (int)div_by(rem, (unsigned)(GROUP_M * tiles_n), dv.gsz, in_group);
+    const int gm0 = grp * GROUP_M;
+    if (tiles_m - gm0 >= GROUP_M) {
+        t.tm = gm0 + (int)(in_group % GROUP_M);
+        t.tn = (int)(in_group / GROUP_M);
+    } else {  // the last, shorter group of tile rows
+        t.tn = (int)div_by(in_group, (unsigned)(tiles_m - gm0), dv.gh_last, rest);
+        t.tm = gm0 + (int)rest;
+    }
+    return t;
+}
+
 // Workgroups [0, main_count) compute one whole tile each.  The tiles left over after the last full round of the
 // machine (tail_tiles of them, logical ids main_count ...) are cut along the contracted bundle into chunks of tail_kc
 // entries, one workgroup per (tile, chunk): workgroup main_count + c * tail_tiles + t stores the raw accumulators of
@@ -835,7 +868,8 @@ template <int AMODE, int BMODE, class CF, bool VA, bool VB>
 __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __restrict__ prods, int first, int tiles_m, int tiles_n,
                                                             const double* __restrict__ Au, const double* __restrict__ Bu,
                                                             double* __restrict__ Cu, double* __restrict__ W, double alpha, double beta, int c_mode,
-                                                            int main_count, int tail_tiles, int tail_kc, double* __restrict__ partial) {
+                                                            int main_count, int tail_tiles, int tail_kc, double* __restrict__ partial,
+                                                            TileDiv tdiv) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     Smem<CF>& S = *reinterpret_cast<Smem<CF>*>(smem_raw);
     const int tid = threadIdx.x;
@@ -861,11 +895,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         }
         lid = main_count - 1 - v;
     } else {
-        const int u = bid - main_count;
-        lid = main_count + u % tail_tiles;
-        kbeg = (int64_t)(u / tail_tiles) * tail_kc;
+        unsigned t;
+        const unsigned chunk = div_by((unsigned)(bid - main_count), (unsigned)tail_tiles, tdiv.tail_tiles, t);
+        lid = main_count + (int)t;
+        kbeg = (int64_t)chunk * tail_kc;
     }
-    const TileId tile = tile_of(lid, tiles_m, tiles_n);
+    const TileId tile = tile_of(lid, tiles_m, tiles_n, tdiv);
     const Product& P = prods[first + tile.pidx];
     const int64_t i0 = (int64_t)tile.tm * TM, j0 = (int64_t)tile.tn * TN;
     const int nA = CF::EXACT ? NTA : P.A.nterms, nB = CF::EXACT ? NTB : P.B.nterms;
@@ -904,17 +939,22 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     // real in every term of A (B): the other rows are then gathered from the tile's first row instead (any readable
     // address will do, the epilogue drops them).  With pair-wise gathers along the rows a term's last odd row counts
     // as missing, since its pair would reach past the block.
+    // (Row and column counts fit 32 bits: a launch has at most 2^20 tiles per direction.  In 32 bits these
+    // workgroup-wide quantities are computed by the scalar unit; 64-bit comparisons would run on the vector unit.)
     int64_t klimit = kb;         // k entries that are real in every term of both operands
     int minA = TM, minB = TN;    // rows / columns of the tile that are real (and pair-complete) in every term
     int maxCr = 0, maxCc = 0;    // rows / columns that some destination keeps
+    bool wholeC = true;          // every destination keeps the whole tile
     int effA[NTA], effB[NTB];
-    auto clip = [](int64_t v, int hi) { return (int)(v < 0 ? 0 : (v > hi ? hi : v)); };
+    const int i0s = tile.tm * TM, j0s = tile.tn * TN, mb32 = (int)P.mb, nb32 = (int)P.nb;
+    auto clip = [](int v, int hi) { return v < 0 ? 0 : (v > hi ? hi : v); };
+    auto least = [](int a, int b) { return a < b ? a : b; };
 #pragma unroll
     for (int t = 0; t < NTA; ++t) {
         effA[t] = 0;
         if (t < nA) {
             klimit = min64(klimit, acs_len - P.A.coff[t]);
-            effA[t] = clip(min64(P.mb, P.A.rs_len - P.A.roff[t]) - i0, TM);
+            effA[t] = clip(least(mb32, (int)P.A.rs_len - (int)P.A.roff[t]) - i0s, TM);
             if (AMODE == 0 && VA) effA[t] &= ~1;
             minA = effA[t] < minA ? effA[t] : minA;
         }
@@ -924,16 +964,23 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         effB[t] = 0;
         if (t < nB) {
             klimit = min64(klimit, brs_len - P.B.roff[t]);
-            effB[t] = clip(min64(P.nb, P.B.cs_len - P.B.coff[t]) - j0, TN);
+            effB[t] = clip(least(nb32, (int)P.B.cs_len - (int)P.B.coff[t]) - j0s, TN);
             if (BMODE == 0 && VB) effB[t] &= ~1;
             minB = effB[t] < minB ? effB[t] : minB;
         }
     }
     for (int d = 0; d < P.C.nterms; ++d) {
-        const int r = clip(min64(P.mb, P.C.rs_len - P.C.roff[d]) - i0, TM), c = clip(min64(P.nb, P.C.cs_len - P.C.coff[d]) - j0, TN);
+        const int r = clip(least(mb32, (int)P.C.rs_len - (int)P.C.roff[d]) - i0s, TM);
+        const int c = clip(least(nb32, (int)P.C.cs_len - (int)P.C.coff[d]) - j0s, TN);
         maxCr = r > maxCr ? r : maxCr;
         maxCc = c > maxCc ? c : maxCc;
+        wholeC = wholeC && r == TM && c == TN;
     }
+    // Destinations whose rows and columns are each one run of a constant stride, all of the tile inside them: the
+    // epilogue computes their addresses (a scalar base per wave and element, a fixed offset per lane) and no scatter
+    // entries are fetched for them.
+    const bool c_affine = !part && wholeC && P.C.rs_stride >= 0 && P.C.cs_stride >= 0 && P.C.rs_stride < ((int64_t)1 << 20) &&
+                          P.C.cs_stride < ((int64_t)1 << 20);
     const bool whole = minA == TM && minB == TN;  // nothing missing at all
     const bool rows_ok = minA == TM || (minA >= 1 && minA >= maxCr), cols_ok = minB == TN || (minB >= 1 && minB >= maxCc);
     const bool tile_full = rows_ok && cols_ok;
@@ -986,7 +1033,11 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
             for (int d = 0; d < SETS; ++d) st.issued_fast[d] = true;
         }
     }
-    for (int e = tid; e < NTA * TM; e += NTHREADS) {
+    // A tile that is gathered by stride from its first k-step to its last reads none of the gather tables: they are
+    // not filled.  (Set-up work is not free even where its latency is hidden: with two workgroups per compute unit
+    // every vector instruction of the one setting up waits for a matrix-core instruction of the other to end.)
+    const bool lean = affine && st.all_fast;
+    for (int e = tid; e < (lean ? 0 : NTA * TM); e += NTHREADS) {
         const int t = e / TM, x = e % TM;
         int64_t val = kSentinel;
         int eff = 0;
@@ -995,12 +1046,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         if (t < nA) {
             if (tile_full && x >= eff)
                 val = (int64_t)Abase + 8 * as_global(P.A.rs)[P.A.roff[t] + i0];
-            else if (i0 + x < P.mb && P.A.roff[t] + i0 + x < P.A.rs_len)
+            else if (i0s + x < mb32 && (int)P.A.roff[t] + i0s + x < (int)P.A.rs_len)
                 val = (int64_t)Abase + 8 * as_global(P.A.rs)[P.A.roff[t] + i0 + x];
         }
         S.a_fix[t][x] = val;
     }
-    for (int e = tid; e < NTB * TN; e += NTHREADS) {
+    for (int e = tid; e < (lean ? 0 : NTB * TN); e += NTHREADS) {
         const int t = e / TN, x = e % TN;
         int64_t val = kSentinel;
         int eff = 0;
@@ -1009,7 +1060,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         if (t < nB) {
             if (tile_full && x >= eff)
                 val = (int64_t)Bbase + 8 * as_global(P.B.cs)[P.B.coff[t] + j0];
-            else if (j0 + x < P.nb && P.B.coff[t] + j0 + x < P.B.cs_len)
+            else if (j0s + x < nb32 && (int)P.B.coff[t] + j0s + x < (int)P.B.cs_len)
                 val = (int64_t)Bbase + 8 * as_global(P.B.cs)[P.B.coff[t] + j0 + x];
         }
         S.b_fix[t][x] = val;
@@ -1020,20 +1071,20 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     // A chunk of a tail tile has one destination: its dense slot of the partial buffer, contiguous along the
     // direction c_mode makes the lanes run, written as is (no alpha, no previous contents).
     const int nC = part ? 1 : P.C.nterms;
-    for (int e = tid; e < MAXC * TM; e += NTHREADS) {
+    for (int e = tid; e < (c_affine ? 0 : nC * TM); e += NTHREADS) {  // (the entries of destinations that do not exist are never read)
         const int d = e / TM, x = e % TM;
-        const int64_t gi = i0 + x, gj = j0 + x;
+        const int gi = i0s + x, gj = j0s + x;
         int64_t val = kSentinel;
         if (part) {
             if (d == 0) val = c_mode == 0 ? x : TN * x;
-        } else if (d < nC && gi < P.mb && P.C.roff[d] + gi < P.C.rs_len) {
+        } else if (d < nC && gi < mb32 && (int)P.C.roff[d] + gi < (int)P.C.rs_len) {
             val = as_global(P.C.rs)[P.C.roff[d] + gi];
         }
         c_rs[d][x] = val;
         val = kSentinel;
         if (part) {
             if (d == 0) val = c_mode == 0 ? TM * x : x;
-        } else if (d < nC && gj < P.nb && P.C.coff[d] + gj < P.C.cs_len) {
+        } else if (d < nC && gj < nb32 && (int)P.C.coff[d] + gj < (int)P.C.cs_len) {
             val = as_global(P.C.cs)[P.C.coff[d] + gj];
         }
         if (x < TN) c_cs[d][x] = val;
@@ -1045,7 +1096,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     st.ent_limit = 0;
     st.ent_dst = &S.dump[0][0];
     st.ent_stride = 64;
-    {
+    if (!lean) {
         const bool isB = tid >= NTHREADS / 2;
         const int q = tid % (NTHREADS / 2), t = q / KT, kl = q % KT;
         if (t < (isB ? NTB : NTA)) {
@@ -1177,8 +1228,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     // tile but those on a ragged edge) the wave takes a path without per-element conditions, on which the loads of C,
     // the reads of the staged tile and the stores are each issued as one batch.  (With a condition around every element
     // the compiler orders the work element by element, and every element then waits for its own LDS read.)
+    // (The tile is staged as accumulated; alpha joins the destination's sign: +-alpha * x rounds like +-(alpha * x).)
     auto apply = [&](int d, int pass) {
-        const double g = part ? 1.0 : P.C.coef[d], f = factor(d);
+        const double g = part ? 1.0 : P.C.coef[d] * alpha, f = factor(d);
         const int64_t o_fixed = c_mode == 0 ? c_rs[d][e_r] : c_cs[d][pass * CP + e_c];
         const int64_t* o_var = c_mode == 0 ? &c_cs[d][pass * CP + e_cg] : &c_rs[d][e_rg];
         int64_t off[BATCH];
@@ -1209,6 +1261,41 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
             }
         }
     };
+    // The same for destinations addressed by stride (c_affine): element b of a thread is at a base that is the same
+    // for the whole wave (kept in scalar registers, stepped by scalar additions) plus the lane's fixed offset, so the
+    // vector unit only combines: the loads and stores are buffer instructions (scalar descriptor at the base of the
+    // wave's first element, the step to element b as scalar offset, the lane's offset as vector offset).
+    auto apply_affine = [&](int d, int pass) {
+        const double g = P.C.coef[d] * alpha, f = factor(d);
+        const int wave_first = __builtin_amdgcn_readfirstlane(tid & ~63);  // the wave's first thread
+        const int64_t rsS = P.C.rs_stride, csS = P.C.cs_stride;
+        // lanes along the rows: row e_r, columns pass * CP + e_cg + CG * b; along the columns: column pass * CP + e_c, rows e_rg + RS * b
+        const int64_t row0 = P.C.roff[d] + i0 + (c_mode == 0 ? 0 : wave_first / CP);
+        const int64_t col0 = P.C.coff[d] + j0 + pass * CP + (c_mode == 0 ? wave_first / TM : 0);
+        // (strides below 2^20: the lane's offset is below 2^30 bytes, the last element's step below 2^31)
+        typedef unsigned int word2_t __attribute__((ext_vector_type(2)));
+        const int64_t ub = uniform64(reinterpret_cast<int64_t>(Cbase + (row0 * rsS + col0 * csS)));
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)ub, 0, -1, 0x00020000);
+        const int step = 8 * (c_mode == 0 ? CG * (int)csS : RS * (int)rsS);
+        const int lane_off = 8 * (c_mode == 0 ? e_r * (int)rsS : e_c * (int)csS);
+        double cur[BATCH];
+        if (f != 0.0) {
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) cur[b] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rsrc, lane_off, b * step, 0));
+            if (f == 1.0 && g == 1.0) {  // one instruction per element instead of two, with the same result
+#pragma unroll
+                for (int b = 0; b < BATCH; ++b) cur[b] += staged(b);
+            } else {
+#pragma unroll
+                for (int b = 0; b < BATCH; ++b) cur[b] = __builtin_fma(f, cur[b], g * staged(b));
+            }
+        } else {
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) cur[b] = g * staged(b);
+        }
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(word2_t, cur[b]), rsrc, lane_off, b * step, 0);
+    };
 #pragma unroll 1
     for (int pass = 0; pass < NPASS; ++pass) {
         if (pass > 0) __syncthreads();  // the previous pass has been read out
@@ -1222,17 +1309,22 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
                     for (int x = 0; x < 4; ++x) {
 #if TC_MFMA16
                         // result s of the lane: row 4 s + lane / 16 of A's 16 lanes, column lane % 16 of B's
-                        otile[(cw + 2 * (lane & 15) + y) * OPITCH + wm * 64 + 32 * (x >> 1) + 2 * (4 * s + di) + (x & 1)] = alpha * st.acc[x][y][s];
+                        otile[(cw + 2 * (lane & 15) + y) * OPITCH + wm * 64 + 32 * (x >> 1) + 2 * (4 * s + di) + (x & 1)] = st.acc[x][y][s];
 #else
                         otile[(cw + 2 * (((dblk + s) & 3) * 4 + dj) + y) * OPITCH + wm * 64 + 32 * (x >> 1) + 2 * (dblk * 4 + di) + (x & 1)] =
-                            alpha * st.acc[x][y][s];
+                            st.acc[x][y][s];
 #endif
                     }
         }
         __syncthreads();
 #pragma unroll
         for (int d = 0; d < MAXC; ++d) {
-            if (d < nC) apply(d, pass);
+            if (d < nC) {
+                if (c_affine)
+                    apply_affine(d, pass);
+                else
+                    apply(d, pass);
+            }
         }
     }
 }
@@ -1268,8 +1360,10 @@ int launch_one(const Product* prods, int first, int count, int tiles_m, int tile
     const int64_t main_count = total - tail.tiles;
     const int64_t blocks = main_count + (int64_t)tail.tiles * tail.chunks;
     if (blocks > 0x7fffffff) return (int)hipErrorInvalidValue;
+    const TileDiv tdiv{tile_div_rcp((int64_t)tiles_m * tiles_n), tile_div_rcp((int64_t)GROUP_M * tiles_n), tile_div_rcp(tiles_m % GROUP_M),
+                       tile_div_rcp(tail.tiles)};
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), smem, stream, prods, first, tiles_m, tiles_n, A, B, C, W, alpha, beta, c_mode,
-                       (int)main_count, tail.tiles, tail.kc, tail.partial);
+                       (int)main_count, tail.tiles, tail.kc, tail.partial, tdiv);
     return (int)hipGetLastError();
 }
 
