@@ -31,6 +31,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <type_traits>
 
 #include "tc_internal.h"
 
@@ -1265,7 +1266,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     // for the whole wave (kept in scalar registers, stepped by scalar additions) plus the lane's fixed offset, so the
     // vector unit only combines: the loads and stores are buffer instructions (scalar descriptor at the base of the
     // wave's first element, the step to element b as scalar offset, the lane's offset as vector offset).
-    auto apply_affine = [&](int d, int pass) {
+    // (The lane direction is a compile-time parameter here, so that the staged tile is read at constant offsets.)
+    auto apply_affine = [&](auto lane_dir, int d, int pass) {
+        constexpr int c_mode = decltype(lane_dir)::value;
+        auto staged = [&](int b) -> double {
+            return c_mode == 0 ? otile[e_cg * OPITCH + e_r + CG * OPITCH * b] : otile[e_c * OPITCH + e_rg + RS * b];
+        };
         const double g = P.C.coef[d] * alpha, f = factor(d);
         const int wave_first = __builtin_amdgcn_readfirstlane(tid & ~63);  // the wave's first thread
         const int64_t rsS = P.C.rs_stride, csS = P.C.cs_stride;
@@ -1320,10 +1326,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
 #pragma unroll
         for (int d = 0; d < MAXC; ++d) {
             if (d < nC) {
-                if (c_affine)
-                    apply_affine(d, pass);
-                else
+                if (!c_affine)
                     apply(d, pass);
+                else if (c_mode == 0)
+                    apply_affine(std::integral_constant<int, 0>{}, d, pass);
+                else
+                    apply_affine(std::integral_constant<int, 1>{}, d, pass);
             }
         }
     }
