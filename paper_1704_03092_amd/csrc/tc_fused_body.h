@@ -104,6 +104,9 @@ struct Cfg {
     // D = 1, issue at the start (first wave of a SIMD) or in the middle (second wave) of a step, store after its last
     // group; single-term operands D = 2 with two sets (issued during step s, stored to LDS during step s + 1), which
     // was the fastest single-term schedule with the 4x4x4 instruction (TC_ROLL_SINGLE = 0).
+#ifndef TC_C_POLICY
+#define TC_C_POLICY 2  // cache policy of the destination accesses by stride: 2 = non-temporal (every element of C is read and written once per launch)
+#endif
 #ifndef TC_ROLL_SINGLE
 #define TC_ROLL_SINGLE 1  // the single-term family in 128 x 128 tiles rolls too (8192^3 classical 69.7 -> 72.2 TFLOP/s)
 #endif
@@ -1287,7 +1290,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         double cur[BATCH];
         if (f != 0.0) {
 #pragma unroll
-            for (int b = 0; b < BATCH; ++b) cur[b] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rsrc, lane_off, b * step, 0));
+            for (int b = 0; b < BATCH; ++b) cur[b] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rsrc, lane_off, b * step, TC_C_POLICY));
             if (f == 1.0 && g == 1.0) {  // one instruction per element instead of two, with the same result
 #pragma unroll
                 for (int b = 0; b < BATCH; ++b) cur[b] += staged(b);
@@ -1300,7 +1303,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
             for (int b = 0; b < BATCH; ++b) cur[b] = g * staged(b);
         }
 #pragma unroll
-        for (int b = 0; b < BATCH; ++b) __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(word2_t, cur[b]), rsrc, lane_off, b * step, 0);
+        for (int b = 0; b < BATCH; ++b) __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(word2_t, cur[b]), rsrc, lane_off, b * step, TC_C_POLICY);
     };
 #pragma unroll 1
     for (int pass = 0; pass < NPASS; ++pass) {
