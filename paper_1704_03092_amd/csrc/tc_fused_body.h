@@ -27,7 +27,7 @@
 //                    only.  Less arithmetic per gathered element (1.5 x the operand reads), but one workgroup's
 //                    table set-up, first gathers and destination update may overlap the other's matrix-core work, and
 //                    twice as many tiles are in flight.  For products with few k-steps per tile or fewer tiles than
-//                    the device has compute units (measured: 3 - 15 % there, 6 - 8 % slower with long k).
+//                    the device has compute units (measured: 1 - 25 % there, 4 - 5 % slower with long k).
 #include <hip/hip_runtime.h>
 
 #include <atomic>
