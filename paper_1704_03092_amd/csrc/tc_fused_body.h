@@ -983,8 +983,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
     // Destinations whose rows and columns are each one run of a constant stride, all of the tile inside them: the
     // epilogue computes their addresses (a scalar base per wave and element, a fixed offset per lane) and no scatter
     // entries are fetched for them.
-    const bool c_affine = !part && wholeC && P.C.rs_stride >= 0 && P.C.cs_stride >= 0 && P.C.rs_stride < ((int64_t)1 << 20) &&
-                          P.C.cs_stride < ((int64_t)1 << 20);
+    // (A chunk of a tail tile goes to its dense slot of the partial buffer: the same case.)
+    const bool c_affine = part || (wholeC && P.C.rs_stride >= 0 && P.C.cs_stride >= 0 && P.C.rs_stride < ((int64_t)1 << 20) &&
+                                   P.C.cs_stride < ((int64_t)1 << 20));
     const bool whole = minA == TM && minB == TN;  // nothing missing at all
     const bool rows_ok = minA == TM || (minA >= 1 && minA >= maxCr), cols_ok = minB == TN || (minB >= 1 && minB >= maxCc);
     const bool tile_full = rows_ok && cols_ok;
@@ -1275,12 +1276,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
         auto staged = [&](int b) -> double {
             return c_mode == 0 ? otile[e_cg * OPITCH + e_r + CG * OPITCH * b] : otile[e_c * OPITCH + e_rg + RS * b];
         };
-        const double g = P.C.coef[d] * alpha, f = factor(d);
+        const double g = part ? 1.0 : P.C.coef[d] * alpha, f = factor(d);
         const int wave_first = __builtin_amdgcn_readfirstlane(tid & ~63);  // the wave's first thread
-        const int64_t rsS = P.C.rs_stride, csS = P.C.cs_stride;
+        // (a chunk's slot is a dense TM x TN tile, contiguous along the direction the lanes run)
+        const int64_t rsS = part ? (c_mode == 0 ? 1 : TN) : P.C.rs_stride, csS = part ? (c_mode == 0 ? TM : 1) : P.C.cs_stride;
         // lanes along the rows: row e_r, columns pass * CP + e_cg + CG * b; along the columns: column pass * CP + e_c, rows e_rg + RS * b
-        const int64_t row0 = P.C.roff[d] + i0 + (c_mode == 0 ? 0 : wave_first / CP);
-        const int64_t col0 = P.C.coff[d] + j0 + pass * CP + (c_mode == 0 ? wave_first / TM : 0);
+        const int64_t row0 = (part ? 0 : P.C.roff[d] + i0) + (c_mode == 0 ? 0 : wave_first / CP);
+        const int64_t col0 = (part ? 0 : P.C.coff[d] + j0) + pass * CP + (c_mode == 0 ? wave_first / TM : 0);
         // (strides below 2^20: the lane's offset is below 2^30 bytes, the last element's step below 2^31)
         typedef unsigned int word2_t __attribute__((ext_vector_type(2)));
         const int64_t ub = uniform64(reinterpret_cast<int64_t>(Cbase + (row0 * rsS + col0 * csS)));
