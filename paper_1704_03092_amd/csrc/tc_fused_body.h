@@ -113,6 +113,10 @@ struct Cfg {
     static constexpr bool ROLL = TC_ROLL && EXACT && (!SINGLE || SMALL || TC_ROLL_SINGLE);
     static constexpr int D = (SINGLE || ROLL) ? 2 : 1;
     static constexpr int SETS = (SINGLE && !ROLL) ? 2 : 1;
+    // The table-free loop fetches no scatter entries (they are fetched where it hands over to the table loop).  Not
+    // in the four-term family with its 16-deep k-steps, which measured 2 % slower without the fetch in its loop; in
+    // the 128 x 64 geometry every vector instruction saved counts (it waits for the partner workgroup's matrix cores).
+    static constexpr bool NOENT_AFF = KT == 32 || SMALL;
     static constexpr int NEA = TM * KT / NTHREADS;  // elements of the A tile (per term) a thread gathers per k-step
     static constexpr int NEB = TN * KT / NTHREADS;  // of the B tile
     static constexpr int NQ = KT / 4;              // matrix-core instruction groups per k-step
@@ -754,7 +758,7 @@ struct State {
         const int kn = (step + D + 1) * KT;
         const bool have = kn < ent_limit;
         int64_t raw_entry = 0;
-        constexpr bool NOENT = AFF && KT == 32;  // (measured: the four-term families lose 2 % without the fetch in their loop)
+        constexpr bool NOENT = AFF && CF::NOENT_AFF;
         if constexpr (!NOENT) raw_entry = ent_ptr[have ? kn : 0];  // unconditional load: ent_ptr always points at readable memory
 
         between_groups<CUR, 0, ROLE, FAST, UNIT, AFF>(step);
@@ -777,7 +781,7 @@ struct State {
         // the loop's own order, so that the loop's load counts are exact from its first trip on.
         if constexpr (CF::ROLL) {
             roll_issue_all<1, true, AFF>(1);
-            if constexpr (!(AFF && KT == 32)) __syncthreads();  // table slot 1 has been read by every thread (step 0 refills it)
+            if constexpr (!(AFF && CF::NOENT_AFF)) __syncthreads();  // table slot 1 has been read by every thread (step 0 refills it)
         }
         for (int step = 0; step < end; step += 2) {
             step_body<0, ROLE, true, UNIT, AFF>(step);
@@ -1194,7 +1198,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void fused_kernel(const Product* __res
                 st.template run_fast<1, false>(nfast, affine);
         }
         if constexpr (D == 2) st.issued_fast[SETS - 1] = true;  // the gather of k-step nfast + 1 is in flight (issued unchecked)
-        if constexpr (VA && VB && CF::EXACT && KT == 32) {
+        if constexpr (VA && VB && CF::EXACT && CF::NOENT_AFF) {
             // the table-free loop of these families fetches no scatter entries: those of the first k-step that the
             // loop below gathers (nfast + 2; the gather of nfast + 1 is in flight) are fetched here
             if (affine && !st.all_fast) {
