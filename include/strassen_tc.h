@@ -157,8 +157,8 @@ typedef struct {
  * tau_b = 8 / (rho_b * bandwidth).  The arithmetic penalty rho_a depends on how many blocks the larger operand sum
  * of a product has (1, 2, 4: index 0, 1, 2), which is what makes this kernel slower; rho_a holds for the tiles gathered
  * by stride, rho_table for the tiles gathered through the scatter tables (general layouts: the fraction of each kind
- * in a launch is what tc_launch_info_t.tiles_table_free reports); both are multiplied by rho_small
- * for launches in 128 x 64 tiles and by rho_gather for launches that gather an operand element by element (the
+ * in a launch is what tc_launch_info_t.tiles_table_free reports); in 128 x 64 tiles they are multiplied by rho_small
+ * and rho_small_table respectively, and both by rho_gather for launches that gather an operand element by element (the
  * operand has no stride-one index on the side the gather runs along: the model's bandwidth penalty for such operands,
  * which here shows as matrix cores waiting for the gather).  t_launch is added per kernel launch; the arithmetic term
  * counts whole waves of tiles (one 128 x 128 tile or two 128 x 64 tiles per compute unit), each wave with a fixed cost
@@ -174,11 +174,12 @@ typedef struct {
     double t_tile;      /* seconds per wave of tiles */
     int units;          /* compute units: each runs one 128 x 128 tile, or two 128 x 64 tiles, at a time */
     int reserved[3];
-    double rho_small;    /* 128 x 64 tiles: factor on rho_a */
+    double rho_small;    /* 128 x 64 tiles: factor on rho_a (above 1 where two workgroups per compute unit hide each other's set-up) */
     double t_tile_small; /* 128 x 64 tiles: seconds per wave of tiles */
     double rho_gather;   /* element-by-element gathers: factor on rho_a */
     double lambda_ab;    /* weight of the operand reads */
     double rho_table[3]; /* as rho_a, for tiles gathered through the scatter tables */
+    double rho_small_table; /* 128 x 64 tiles: factor on rho_table */
 } tc_model_params_t;
 
 /* One kernel launch of the plan's schedule, for inspection (tc_plan_launch). */

@@ -99,7 +99,7 @@ class tc_model_params_t(ctypes.Structure):
     _fields_ = [("peak_flops", ctypes.c_double), ("rho_a", ctypes.c_double * 3), ("bandwidth", ctypes.c_double), ("rho_b", ctypes.c_double),
                 ("t_launch", ctypes.c_double), ("t_tile", ctypes.c_double), ("units", ctypes.c_int), ("reserved", ctypes.c_int * 3),
                 ("rho_small", ctypes.c_double), ("t_tile_small", ctypes.c_double), ("rho_gather", ctypes.c_double), ("lambda_ab", ctypes.c_double),
-                ("rho_table", ctypes.c_double * 3)]
+                ("rho_table", ctypes.c_double * 3), ("rho_small_table", ctypes.c_double)]
 
 
 class tc_model_time_t(ctypes.Structure):
@@ -303,7 +303,7 @@ def tc_model_defaults() -> dict:
         raise TcError(rc, "tc_model_defaults")
     return {"peak_flops": mp.peak_flops, "rho_a": list(mp.rho_a), "bandwidth": mp.bandwidth, "rho_b": mp.rho_b, "t_launch": mp.t_launch,
             "t_tile": mp.t_tile, "units": mp.units, "rho_small": mp.rho_small, "t_tile_small": mp.t_tile_small,
-            "rho_gather": mp.rho_gather, "lambda_ab": mp.lambda_ab, "rho_table": list(mp.rho_table)}
+            "rho_gather": mp.rho_gather, "lambda_ab": mp.lambda_ab, "rho_table": list(mp.rho_table), "rho_small_table": mp.rho_small_table}
 
 
 def tc_plan_predict(plan: Plan, params: Optional[dict] = None) -> dict:
@@ -313,7 +313,7 @@ def tc_plan_predict(plan: Plan, params: Optional[dict] = None) -> dict:
         mp = tc_model_params_t(params["peak_flops"], (ctypes.c_double * 3)(*params["rho_a"]), params["bandwidth"], params["rho_b"],
                                params["t_launch"], params["t_tile"], int(params["units"]), (ctypes.c_int * 3)(),
                                params["rho_small"], params["t_tile_small"], params["rho_gather"], params["lambda_ab"],
-                               (ctypes.c_double * 3)(*params["rho_table"]))
+                               (ctypes.c_double * 3)(*params["rho_table"]), params["rho_small_table"])
     out = tc_model_time_t()
     rc = load_library().tc_plan_predict(plan.handle, ctypes.byref(mp) if mp is not None else None, ctypes.byref(out))
     if rc != 0:

@@ -950,7 +950,8 @@ extern const tc_model_params_t kDefaultModel = {
     // to the next, with a wide scatter over the tensors' layouts (0.70 - 0.93 per shape).  The default stays at the
     // low end on purpose: from 0.98 of the single-term figure on, the automatic choice takes a Strassen level for
     // two tensors of the sweep on which that level measures 12 - 13 % slower.
-    {0.870, 0.838, 0.592}};
+    {0.870, 0.838, 0.592},
+    0.960};                // 128 x 64 tiles gathered through the tables (their address arithmetic waits for the partner's matrix cores)
 
 // What the model needs to know of a fused launch.
 struct FusedShape {
@@ -1078,8 +1079,8 @@ int64_t tiles_per_wave(const tc_model_params_t& mp, int tile_n) { return (int64_
 TailCost fused_cost(const tc_model_params_t& mp, const FusedShape& f, int64_t tail_tiles, int64_t chunks, int64_t kc) {
     const bool small = f.tile_n == 64;
     const int cls = f.terms <= 1 ? 0 : f.terms <= 2 ? 1 : 2;
-    const double rho = 1.0 / (f.free_frac / mp.rho_a[cls] + (1.0 - f.free_frac) / mp.rho_table[cls]) * (small ? mp.rho_small : 1.0) *
-                       (f.pairs ? 1.0 : mp.rho_gather);
+    const double by_stride = mp.rho_a[cls] * (small ? mp.rho_small : 1.0), by_table = mp.rho_table[cls] * (small ? mp.rho_small_table : 1.0);
+    const double rho = 1.0 / (f.free_frac / by_stride + (1.0 - f.free_frac) / by_table) * (f.pairs ? 1.0 : mp.rho_gather);
     const double fixed = small ? mp.t_tile_small : mp.t_tile;
     const int64_t per = tiles_per_wave(mp, f.tile_n);
     auto wave = [&](int64_t depth) { return mp.units * 2.0 * 128.0 * 128.0 * (double)depth / (rho * mp.peak_flops) + fixed; };
@@ -1136,7 +1137,12 @@ void choose_tiles(const tc_plan_t* p, Step& s, const tc_model_params_t& mp, int 
     if (may_small && tile_mode != 128) {
         const Step big = s;
         const double ts = with_tiles(64);
-        if (tile_mode == 0 && ts >= t) s = big;
+        // A launch that mixes tiles gathered by stride with tiles gathered through the tables stays in 128 x 128 tiles
+        // whatever the model says: next to a workgroup whose loop is all matrix-core instructions, a workgroup whose
+        // loop computes addresses on the vector unit is starved (measured: 3.7 times the tile time; the model has no
+        // term for who a tile's neighbour is).  All by stride, or all through the tables, the two are even.
+        const bool mixed = s.free_frac > 0.0 && s.free_frac < 1.0;
+        if (tile_mode == 0 && (ts >= t || mixed)) s = big;
     }
     *chunk_elems = std::max<int64_t>(*chunk_elems, (int64_t)s.tail_tiles * s.tail_chunks * 128 * s.cfg.tile_n);
 }

@@ -270,6 +270,7 @@ def fit(samples, defaults):
     p["rho_a"] = [inv(x[i], defaults["rho_a"][i]) for i in range(3)]
     p["rho_table"] = [inv(x[4 + i], defaults["rho_table"][i]) for i in range(3)]
     p["rho_small"] = inv(x[3], p["rho_a"][0] * defaults["rho_small"]) / p["rho_a"][0]
+    p["rho_small_table"] = inv(x[7], p["rho_table"][0] * defaults["rho_small_table"]) / p["rho_table"][0]
     p["t_tile"], p["t_tile_small"] = float(x[8]), float(x[9])
     p["rho_b"] = inv(x[10], defaults["rho_b"])
     p["lambda_ab"] = float(x[11] * p["rho_b"])
@@ -314,7 +315,8 @@ def run_fit(families, reduced, out=sys.stdout, save=None, load=None):
     print("    {" + ", ".join(f"{v:.3f}" for v in p["rho_a"]) + "},", file=out)
     print(f"    {p['bandwidth']:.4g},\n    {p['rho_b']:.3f},\n    {p['t_launch']:.3g},\n    {p['t_tile']:.3g},\n    {p['units']}, {{0, 0, 0}},", file=out)
     print(f"    {p['rho_small']:.3f},\n    {p['t_tile_small']:.3g},\n    {p['rho_gather']:.3f},\n    {p['lambda_ab']:.4f},", file=out)
-    print("    {" + ", ".join(f"{v:.3f}" for v in p["rho_table"]) + "}};", file=out)
+    print("    {" + ", ".join(f"{v:.3f}" for v in p["rho_table"]) + "},", file=out)
+    print(f"    {p['rho_small_table']:.3f}}};", file=out)
     return p
 
 

@@ -212,7 +212,7 @@ def _gemm_desc(m, n, k):
 # 128 x 128 with 512 contracted entries is 16 * 2 * 128 * 128 * 512 = 2^28 flops; rho_a * peak = 2^28, 2^27, 2^26
 # flop/s for one-, two- and four-block sums; rho_b * bandwidth = 2^24 byte/s.
 _HAND = dict(peak_flops=2.0 ** 29, rho_a=[0.5, 0.25, 0.125], bandwidth=2.0 ** 25, rho_b=0.5, t_launch=0.125, t_tile=0.25, units=16,
-             rho_small=0.5, t_tile_small=0.125, rho_gather=0.5, lambda_ab=0.0, rho_table=[0.5, 0.25, 0.125])
+             rho_small=0.5, t_tile_small=0.125, rho_gather=0.5, lambda_ab=0.0, rho_table=[0.5, 0.25, 0.125], rho_small_table=0.25)
 
 
 @pytest.mark.parametrize("shape,level,variant,opts,want", [
@@ -247,6 +247,9 @@ _HAND = dict(peak_flops=2.0 ** 29, rho_a=[0.5, 0.25, 0.125], bandwidth=2.0 ** 25
     # 1000 rows: the 8 tiles of the last tile row are ragged and go through the scatter tables at half the rate of the
     # 56 others: 1 / rho = (7/8) / 0.5 + (1/8) / 0.25 = 2.25, a wave takes 2.25 * 2^28 / 2^29 s + 0.25 s; C: 2 * 1000 * 1024 * 8 B
     ((1000, 1024, 512), 0, "abc", dict(tile_n=128, rho_table=[0.25, 0.25, 0.25]), dict(arith=5.5, c_update=0.9765625, temporaries=0.0, launch=0.125)),
+    # the same in 128 x 64 tiles: 112 tiles by stride at 0.5 * 0.5, the 16 ragged ones through the tables at 0.25 * 0.25:
+    # 1 / rho = (7/8) / 0.25 + (1/8) / 0.0625 = 5.5; 4 waves of 32 tiles, each 5.5 * 2^28 / 2^29 s + 0.125 s
+    ((1000, 1024, 512), 0, "abc", dict(tile_n=64, rho_table=[0.25, 0.25, 0.25]), dict(arith=11.5, c_update=0.9765625, temporaries=0.0, launch=0.125)),
 ])
 def test_model_prediction_hand_computed(shape, level, variant, opts, want):
     """Sec. 5 eq. (2)-(4): the modelled time is the sum of the arithmetic term, the destination updates, the operand
