@@ -946,11 +946,11 @@ extern const tc_model_params_t kDefaultModel = {
     0.0,                   // no cost per wave of their own: one workgroup's fill and update hide behind the other's multiplications
     0.858,                 // element-by-element gathers
     0.0053,                // operand reads not hidden behind the matrix cores
-    // Tiles gathered through the scatter tables.  Two-term sums: the fit gives 0.838 - 0.883 from one box and day
-    // to the next, with a wide scatter over the tensors' layouts (0.70 - 0.93 per shape).  The default stays at the
-    // low end on purpose: from 0.98 of the single-term figure on, the automatic choice takes a Strassen level for
-    // two tensors of the sweep on which that level measures 12 - 13 % slower.
-    {0.870, 0.838, 0.592},
+    // Tiles gathered through the scatter tables.  Two-term sums: the fits give 0.838 - 0.883, with a wide scatter over
+    // the tensors' layouts (0.70 - 0.93 per shape).  The default is set below them on purpose: from 0.83 on the
+    // automatic choice takes a Strassen level for a tensor of the sweep on which that level measures 12 % slower
+    // (its own two-term launches run at 0.80).
+    {0.870, 0.810, 0.592},
     0.960};                // 128 x 64 tiles gathered through the tables (their address arithmetic waits for the partner's matrix cores)
 
 // What the model needs to know of a fused launch.
