@@ -25,9 +25,12 @@
 //   tc::fused        128 x 128 tiles, 512 threads (8 waves, 2 x 4), one workgroup per compute unit: all kernel families
 //   tc::fused_small  128 x 64 tiles, 256 threads (4 waves, 2 x 2), two workgroups per compute unit: single-term products
 //                    only.  Less arithmetic per gathered element (1.5 x the operand reads), but one workgroup's
-//                    table set-up, first gathers and destination update may overlap the other's matrix-core work, and
-//                    twice as many tiles are in flight.  For products with few k-steps per tile or fewer tiles than
-//                    the device has compute units (measured: 1 - 25 % there, 4 - 5 % slower with long k).
+//                    set-up, first gathers and destination update overlap the other's matrix-core work, and twice
+//                    as many tiles are in flight.  Measured: ahead of the large shape for tiles gathered by stride
+//                    at every size (25 % for a handful of tiles, 8 % at k = 256, 1 % at 16384^3), 3 - 4 % behind
+//                    for tiles gathered through the tables.  Its vector instructions outside the matrix-core loop
+//                    are costly (each waits for a matrix-core instruction of the other workgroup to end), which is
+//                    why set-up and epilogue keep workgroup-wide quantities on the scalar unit.
 #include <hip/hip_runtime.h>
 
 #include <atomic>
