@@ -105,9 +105,11 @@ typedef struct {
                      * in every launch that has a tail, whatever the model says (for tests and measurements) */
     int tile_n;     /* tile shape of the launches whose products have single-block operand sums (level 0, and the stored-sum
                      * variants): 0 = the performance model chooses; 128 = 128 x 128 tiles, one workgroup of 512 threads
-                     * per compute unit; 64 = 128 x 64 tiles, two workgroups of 256 threads per compute unit (for products
-                     * with few k-steps per tile or few tiles: one workgroup's set-up and destination update overlap the
-                     * other's matrix-core work).  Launches with multi-block sums always use 128. */
+                     * per compute unit; 64 = 128 x 64 tiles, two workgroups of 256 threads per compute unit (one
+                     * workgroup's set-up and destination update overlap the other's matrix-core work: the faster shape
+                     * where every tile is gathered by stride, the slower one through the scatter tables; a launch that
+                     * mixes the two kinds of tile is kept in 128 x 128 tiles by the automatic choice).  Launches with
+                     * multi-block sums always use 128. */
     int no_peel;    /* Sizes that 2^level does not divide (Sec. 3, last paragraph, names dynamic peeling and zero padding):
                      * 0 = the Strassen products cover a leading part of the row and of the column bundle and one
                      * classical product each does the rows / columns left over (dynamic peeling).  The leading part is
